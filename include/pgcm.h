@@ -1,0 +1,128 @@
+/*
+ * pgcm: batched AES-256-GCM on one AMD MI355X (gfx950).
+ *
+ * The operation is the one the paper's confidential-computing transport performs for every
+ * host<->GPU transfer: an AES-GCM invocation over the transfer's bytes with a shared key and a
+ * unique IV, whose receiver decrypts and rejects anything that fails the integrity check
+ * (paper section 2.2, "A closer look at NVIDIA CC"; section 4.1, "Swapping sequence and IVs";
+ * section 8.3 on why stale ciphertext must be rejected).  A batch is a list of such transfers
+ * ("chunks": KV-cache blocks, weight chunks, adapters), each with its own 96-bit IV and 128-bit
+ * tag, as issued between two synchronisation points (section 5.1, predictor input).
+ * The cipher is AES-256 (FIPS-197) in GCM (NIST SP 800-38D) with 96-bit IVs and full 16-byte tags.
+ *
+ * Conventions for every call
+ *   - "DEVICE" pointers address GPU memory of the current HIP device; "HOST" pointers address
+ *     ordinary process memory.  Host arrays are consumed before the call returns.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t cast to void*, NULL = the null stream) and
+ *     the call returns without synchronising.  Device outputs are valid once the stream has
+ *     reached the end of the batch; device inputs must stay alive and unchanged until then.
+ *   - One key object may be used by one stream at a time: its descriptor workspace is reused
+ *     from call to call and successive batches are ordered by the stream.
+ *   - Errors are return codes; nothing is enqueued when a call fails.  Authentication failure of
+ *     a chunk is not an error (see pgcm_decrypt_verify_batch).
+ *   - IV uniqueness per key is the caller's duty (the paper's transport uses a counter); it is
+ *     not checked.
+ */
+#ifndef PGCM_H
+#define PGCM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pgcm_key pgcm_key_t; /* opaque: device round keys, GHASH tables, workspace */
+
+typedef enum {
+    PGCM_OK = 0,
+    PGCM_ERR_ARG = -1,   /* a required pointer is NULL, or n is too large */
+    PGCM_ERR_ALIGN = -2, /* a src or dst pointer is not 16-byte aligned */
+    PGCM_ERR_LEN = -3,   /* a chunk is longer than 2^36 - 32 bytes (the GCM limit) */
+    PGCM_ERR_NOMEM = -4, /* host or device allocation failed */
+    PGCM_ERR_HIP = -5    /* a HIP call failed; see pgcm_last_hip_error */
+} pgcm_status;
+
+#define PGCM_MAX_CHUNK_BYTES ((((uint64_t)1) << 36) - 32)
+
+/*
+ * Key set-up (once per key, not per batch): the AES-256 key schedule, the GHASH key
+ * H = E_K(0^128) and the tables of powers of H the batch kernels use, all computed on the GPU.
+ *   key        HOST, 32 bytes.
+ *   hip_stream stream the set-up kernel runs on; the call synchronises it before returning.
+ *   out        HOST, receives the new object; release it with pgcm_free_key.
+ */
+int pgcm_expand_key(const uint8_t key[32], void *hip_stream, pgcm_key_t **out);
+
+/* Wipes the device and host copies of the key material and frees them.  NULL is allowed.
+ * The caller must have synchronised every stream that still uses the key. */
+void pgcm_free_key(pgcm_key_t *key);
+
+/*
+ * Authenticated encryption of n independent chunks (SP 800-38D section 7.1, once per chunk):
+ *   dst[i] = src[i] xor keystream(key, IV_i),  tags[i] = GHASH_H(aad_i, dst[i]) xor E_K(IV_i || 1).
+ *   ivs      DEVICE, n * 12 bytes; chunk i uses ivs[12 i .. 12 i + 11].
+ *   aad      HOST array of n DEVICE pointers (any alignment); entries with aad_len[i] == 0 are
+ *            not read.  Must be NULL exactly when aad_len is NULL.
+ *   aad_len  HOST array of n byte counts, or NULL for "no chunk has AAD".
+ *   src      HOST array of n DEVICE pointers, each 16-byte aligned (unused when len[i] == 0).
+ *   len      HOST array of n byte counts, 0 <= len[i] <= PGCM_MAX_CHUNK_BYTES; need not be a
+ *            multiple of 16.  Exactly len[i] bytes are read and written, never more.
+ *   dst      HOST array of n DEVICE pointers, 16-byte aligned.  dst[i] == src[i] (in place) is
+ *            allowed; any other overlap between buffers of the batch is undefined.
+ *   tags     DEVICE, n * 16 bytes, written.
+ * n == 0 succeeds and does nothing.
+ */
+int pgcm_encrypt_batch(pgcm_key_t *key, size_t n, const uint8_t *ivs, const void *const *aad,
+                       const uint32_t *aad_len, const void *const *src, const uint64_t *len,
+                       void *const *dst, uint8_t *tags, void *hip_stream);
+
+/*
+ * Authenticated decryption of n independent chunks (SP 800-38D section 7.2, once per chunk).
+ * Arguments as for pgcm_encrypt_batch, except:
+ *   tags     DEVICE, n * 16 bytes, read: the tag received with each chunk.
+ *   ok       DEVICE, n bytes, written: 1 when chunk i is authentic, 0 when it is rejected.
+ * The tag comparison looks at all 16 bytes with no data-dependent exit.  For a rejected chunk
+ * the len[i] bytes at dst[i] are overwritten with zeros before the batch ends on the stream
+ * (unauthenticated plaintext is never left behind); the call itself still returns PGCM_OK.
+ */
+int pgcm_decrypt_verify_batch(pgcm_key_t *key, size_t n, const uint8_t *ivs,
+                              const void *const *aad, const uint32_t *aad_len,
+                              const void *const *src, const uint64_t *len, void *const *dst,
+                              const uint8_t *tags, uint8_t *ok, void *hip_stream);
+
+/* Static text for a pgcm_status value. */
+const char *pgcm_strerror(int status);
+
+/* The hipError_t (as int) behind the calling thread's most recent PGCM_ERR_HIP, else 0. */
+int pgcm_last_hip_error(void);
+
+/*
+ * Host-only view of the chunk-to-wavefront schedule (section 5.1: requests arrive as batches of
+ * copies of differing sizes).  Every chunk is cut into segments of pgcm_segment_bytes() bytes
+ * counted back from its end, so only a chunk's first segment can be short; each segment is one
+ * work item.  Fills, for chunk i, nseg[i] (number of segments, 0 for an empty chunk),
+ * first_blocks[i] (16-byte blocks in its first segment) and part_base[i] (index of its first
+ * segment among all work items).  Any output pointer may be NULL.  Returns the total number of
+ * work items, or a negative pgcm_status.  Touches no GPU state.
+ */
+int64_t pgcm_plan_segments(size_t n, const uint64_t *len, uint32_t *nseg, uint32_t *first_blocks,
+                           uint32_t *part_base);
+
+/* Bytes per full segment (a multiple of the 1 KiB a wavefront handles per step). */
+uint32_t pgcm_segment_bytes(void);
+
+/*
+ * Measurement aid.  With timing enabled, every batch call also records a pair of HIP events on
+ * its stream around the bulk kernel (the one launch that touches the payload: keystream, XOR
+ * and GHASH of every segment).  pgcm_last_bulk_kernel_ms waits for the most recent batch's
+ * bulk kernel and returns its duration in milliseconds; PGCM_ERR_ARG when nothing was timed.
+ */
+int pgcm_set_timing(pgcm_key_t *key, int enable);
+int pgcm_last_bulk_kernel_ms(pgcm_key_t *key, float *ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PGCM_H */

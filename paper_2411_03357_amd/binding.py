@@ -1,0 +1,194 @@
+"""ctypes binding for the C ABI in include/pgcm.h: same names, argument marshalling only."""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpgcm.so")
+_lib = None
+
+EXPORTS = ("pgcm_expand_key", "pgcm_free_key", "pgcm_encrypt_batch", "pgcm_decrypt_verify_batch",
+           "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_segments", "pgcm_segment_bytes",
+           "pgcm_set_timing", "pgcm_last_bulk_kernel_ms")
+
+
+class PgcmError(RuntimeError):
+    def __init__(self, status, hip_error=0):
+        self.status, self.hip_error = status, hip_error
+        text = load_library().pgcm_strerror(status).decode()
+        super().__init__("pgcm status %d (%s)%s" % (
+            status, text, ", hipError %d" % hip_error if hip_error else ""))
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libpgcm.so; there is no fallback when it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libpgcm.so is not built: run `python -m paper_2411_03357_amd.build` "
+                          "(needs hipcc); there is no CPU fallback")
+    lib = C.CDLL(_LIB_PATH)
+    vp, sz = C.c_void_p, C.c_size_t
+    lib.pgcm_expand_key.argtypes = [vp, vp, C.POINTER(vp)]
+    lib.pgcm_expand_key.restype = C.c_int
+    lib.pgcm_free_key.argtypes = [vp]
+    lib.pgcm_free_key.restype = None
+    lib.pgcm_encrypt_batch.argtypes = [vp, sz, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.pgcm_encrypt_batch.restype = C.c_int
+    lib.pgcm_decrypt_verify_batch.argtypes = [vp, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.pgcm_decrypt_verify_batch.restype = C.c_int
+    lib.pgcm_strerror.argtypes = [C.c_int]
+    lib.pgcm_strerror.restype = C.c_char_p
+    lib.pgcm_last_hip_error.argtypes = []
+    lib.pgcm_last_hip_error.restype = C.c_int
+    lib.pgcm_plan_segments.argtypes = [sz, vp, vp, vp, vp]
+    lib.pgcm_plan_segments.restype = C.c_int64
+    lib.pgcm_segment_bytes.argtypes = []
+    lib.pgcm_segment_bytes.restype = C.c_uint32
+    lib.pgcm_set_timing.argtypes = [vp, C.c_int]
+    lib.pgcm_set_timing.restype = C.c_int
+    lib.pgcm_last_bulk_kernel_ms.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.pgcm_last_bulk_kernel_ms.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        raise PgcmError(status, load_library().pgcm_last_hip_error() if status == -5 else 0)
+
+
+def _stream_handle(stream):
+    """None -> torch's current stream; an int is taken as a hipStream_t; a torch stream -> its
+    handle"""
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _dev_ptr(t):
+    """device address of a torch CUDA tensor, or an int taken as is; None -> NULL"""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous CUDA tensor")
+    return t.data_ptr()
+
+
+def _host_array(a, dtype, n, what):
+    """host descriptor array: numpy array of `dtype` with n entries (None stays None)"""
+    if a is None:
+        return None
+    arr = np.ascontiguousarray(a, dtype=dtype)
+    if arr.shape != (n,):
+        raise ValueError("%s must have %d entries" % (what, n))
+    return arr
+
+
+def _addr(arr):
+    return None if arr is None else arr.ctypes.data
+
+
+class Key:
+    """Owns a pgcm_key_t; free() (or garbage collection) wipes and releases it."""
+
+    def __init__(self, handle):
+        self._h = handle
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("key already freed")
+        return self._h
+
+    def free(self):
+        if self._h is not None:
+            load_library().pgcm_free_key(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def expand_key(key, stream=None) -> Key:
+    """pgcm_expand_key: `key` is 32 bytes (bytes or uint8 array)."""
+    kb = np.frombuffer(bytes(key), dtype=np.uint8) if not isinstance(key, np.ndarray) else \
+        np.ascontiguousarray(key, dtype=np.uint8)
+    if kb.size != 32:
+        raise ValueError("AES-256 keys are 32 bytes")
+    out = C.c_void_p()
+    _check(load_library().pgcm_expand_key(kb.ctypes.data, _stream_handle(stream), C.byref(out)))
+    return Key(out.value)
+
+
+def encrypt_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, stream=None):
+    """pgcm_encrypt_batch.  ivs, tags: CUDA uint8 tensors (n*12, n*16 bytes) or device addresses;
+    src, dst, aad: sequences / uint64 arrays of n device addresses; length: n byte counts;
+    aad and aad_len are both None when no chunk has AAD."""
+    n = len(length)
+    src_a = _host_array(src, np.uint64, n, "src")
+    dst_a = _host_array(dst, np.uint64, n, "dst")
+    len_a = _host_array(length, np.uint64, n, "length")
+    aad_a = _host_array(aad, np.uint64, n, "aad")
+    alen_a = _host_array(aad_len, np.uint32, n, "aad_len")
+    _check(load_library().pgcm_encrypt_batch(
+        key.handle, n, _dev_ptr(ivs), _addr(aad_a), _addr(alen_a), _addr(src_a), _addr(len_a),
+        _addr(dst_a), _dev_ptr(tags), _stream_handle(stream)))
+
+
+def decrypt_verify_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, ok, stream=None):
+    """pgcm_decrypt_verify_batch.  As encrypt_batch; tags is read, ok (CUDA uint8 tensor of n
+    bytes) receives 1 per authentic chunk and 0 per rejected one."""
+    n = len(length)
+    src_a = _host_array(src, np.uint64, n, "src")
+    dst_a = _host_array(dst, np.uint64, n, "dst")
+    len_a = _host_array(length, np.uint64, n, "length")
+    aad_a = _host_array(aad, np.uint64, n, "aad")
+    alen_a = _host_array(aad_len, np.uint32, n, "aad_len")
+    _check(load_library().pgcm_decrypt_verify_batch(
+        key.handle, n, _dev_ptr(ivs), _addr(aad_a), _addr(alen_a), _addr(src_a), _addr(len_a),
+        _addr(dst_a), _dev_ptr(tags), _dev_ptr(ok), _stream_handle(stream)))
+
+
+def plan_segments(length):
+    """pgcm_plan_segments -> (total work items, nseg, first_blocks, part_base); host only."""
+    len_a = np.ascontiguousarray(length, dtype=np.uint64)
+    n = len_a.size
+    nseg = np.zeros(n, np.uint32)
+    first = np.zeros(n, np.uint32)
+    base = np.zeros(n, np.uint32)
+    total = load_library().pgcm_plan_segments(n, _addr(len_a) if n else None, nseg.ctypes.data,
+                                              first.ctypes.data, base.ctypes.data)
+    if total < 0:
+        raise PgcmError(int(total))
+    return int(total), nseg, first, base
+
+
+def set_timing(key: Key, enable: bool):
+    """pgcm_set_timing"""
+    _check(load_library().pgcm_set_timing(key.handle, 1 if enable else 0))
+
+
+def last_bulk_kernel_ms(key: Key) -> float:
+    """pgcm_last_bulk_kernel_ms"""
+    ms = C.c_float(0.0)
+    _check(load_library().pgcm_last_bulk_kernel_ms(key.handle, C.byref(ms)))
+    return float(ms.value)
+
+
+def segment_bytes() -> int:
+    return int(load_library().pgcm_segment_bytes())

@@ -1,0 +1,553 @@
+// HIP kernels for batched AES-256-GCM on gfx950 (MI355X).
+//
+// What is computed is the AES-GCM transform the paper's transport applies to every transfer
+// (paper sections 2.2 and 4.1), i.e. FIPS-197 AES-256 in the GCM mode of NIST SP 800-38D with a
+// 96-bit IV.  How it is computed here:
+//   * AES rounds read four 1 KiB round tables, each replicated 32 times in LDS so that lane l
+//     always reads bank l % 32: table lookups never collide, whatever the data.
+//   * GHASH multiplies by fixed powers of H with 4-bit tables (Shoup): the row power H^64 sits in
+//     LDS; the lane-combining tree uses H^32 .. H^1 from global memory once per segment.
+//   * One wavefront walks one segment (<= 64 KiB of one chunk) in rows of 64 blocks, one block
+//     per lane, 16-byte coalesced loads and stores, ciphertext hashed from registers.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pgcm_kernels.h"
+
+namespace pgcm {
+
+// ------------------------------------------------------------------------------------------
+// S-box, generated at compile time from its definition (FIPS-197 5.1.1): inverse in
+// GF(2^8) mod x^8+x^4+x^3+x+1, then the affine map.
+namespace {
+
+constexpr uint8_t xtime(uint8_t a) { return (uint8_t)((a << 1) ^ ((a & 0x80) ? 0x1B : 0)); }
+
+constexpr uint8_t mul8(uint8_t a, uint8_t b) {
+    uint8_t p = 0;
+    for (int i = 0; i < 8; ++i) {
+        if (b & (1 << i)) p ^= a;
+        a = xtime(a);
+    }
+    return p;
+}
+
+constexpr uint8_t inv8(uint8_t a) {
+    // a^254: the inverse of every non-zero element, and 0 for 0
+    uint8_t r = 1, s = a;
+    for (int bit = 1; bit < 8; ++bit) {
+        s = mul8(s, s);    // a^(2^bit)
+        r = mul8(r, s);
+    }
+    return r;              // a^(2+4+...+128) = a^254
+}
+
+constexpr uint8_t rotl8(uint8_t v, int k) { return (uint8_t)((v << k) | (v >> (8 - k))); }
+
+struct SboxTable {
+    uint8_t v[256];
+};
+
+constexpr SboxTable make_sbox() {
+    SboxTable t{};
+    for (int x = 0; x < 256; ++x) {
+        uint8_t b = inv8((uint8_t)x);
+        t.v[x] = (uint8_t)(b ^ rotl8(b, 1) ^ rotl8(b, 2) ^ rotl8(b, 3) ^ rotl8(b, 4) ^ 0x63);
+    }
+    return t;
+}
+
+__device__ const SboxTable kSbox = make_sbox();
+static_assert(make_sbox().v[0x00] == 0x63 && make_sbox().v[0x53] == 0xED, "S-box");
+
+// ------------------------------------------------------------------------------------------
+// GF(2^128) in GCM's bit order (SP 800-38D 6.3): bit 0 of a block is the top bit of byte 0.
+// For shifting, a block is held as two big-endian 64-bit halves.
+struct Gf {
+    uint64_t hi, lo;
+};
+
+__device__ __forceinline__ uint32_t bswap32(uint32_t v) { return __builtin_bswap32(v); }
+
+__device__ __forceinline__ Gf gf_from_block(const Block& b) {
+    Gf g;
+    g.hi = ((uint64_t)bswap32(b.w[0]) << 32) | bswap32(b.w[1]);
+    g.lo = ((uint64_t)bswap32(b.w[2]) << 32) | bswap32(b.w[3]);
+    return g;
+}
+
+__device__ __forceinline__ Block gf_to_block(const Gf& g) {
+    Block b;
+    b.w[0] = bswap32((uint32_t)(g.hi >> 32));
+    b.w[1] = bswap32((uint32_t)g.hi);
+    b.w[2] = bswap32((uint32_t)(g.lo >> 32));
+    b.w[3] = bswap32((uint32_t)g.lo);
+    return b;
+}
+
+// bit-serial product (SP 800-38D algorithm 1); used for set-up only
+__device__ Gf gf_mul_bits(const Gf& x, const Gf& y) {
+    Gf z{0, 0}, v = y;
+    for (int i = 0; i < 128; ++i) {
+        uint64_t bit = (i < 64) ? (x.hi >> (63 - i)) & 1 : (x.lo >> (127 - i)) & 1;
+        uint64_t m = 0 - bit;
+        z.hi ^= v.hi & m;
+        z.lo ^= v.lo & m;
+        uint64_t carry = 0 - (v.lo & 1);
+        v.lo = (v.lo >> 1) | (v.hi << 63);
+        v.hi = (v.hi >> 1) ^ (carry & 0xE100000000000000ull);
+    }
+    return z;
+}
+
+__device__ __forceinline__ void block_xor(Block& a, const Block& b) {
+    a.w[0] ^= b.w[0];
+    a.w[1] ^= b.w[1];
+    a.w[2] ^= b.w[2];
+    a.w[3] ^= b.w[3];
+}
+
+// X * C from C's nibble table in global memory: 32 lookups of 16 bytes
+__device__ Block gf_mul_table(const Block* __restrict__ tbl, const Block& x) {
+    Block z{{0, 0, 0, 0}};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t byte = (x.w[i] >> (8 * k)) & 0xFF;
+            uint32_t pos = 2 * (4 * i + k);
+            block_xor(z, tbl[pos * 16 + (byte >> 4)]);
+            block_xor(z, tbl[(pos + 1) * 16 + (byte & 15)]);
+        }
+    }
+    return z;
+}
+
+// ------------------------------------------------------------------------------------------
+// AES-256 block encryption from tables in global memory (set-up, J0, not the bulk path)
+__device__ __forceinline__ uint32_t byte_of(uint32_t w, int k) { return (w >> (8 * k)) & 0xFF; }
+
+__device__ void aes256_block_global(const KeyTables* __restrict__ kt, uint32_t s[4]) {
+    const uint32_t* rk = kt->rk;
+    uint32_t a0 = s[0] ^ rk[0], a1 = s[1] ^ rk[1], a2 = s[2] ^ rk[2], a3 = s[3] ^ rk[3];
+    for (int r = 1; r < 14; ++r) {
+        uint32_t t0 = kt->te[0][byte_of(a0, 0)] ^ kt->te[1][byte_of(a1, 1)] ^
+                      kt->te[2][byte_of(a2, 2)] ^ kt->te[3][byte_of(a3, 3)] ^ rk[4 * r + 0];
+        uint32_t t1 = kt->te[0][byte_of(a1, 0)] ^ kt->te[1][byte_of(a2, 1)] ^
+                      kt->te[2][byte_of(a3, 2)] ^ kt->te[3][byte_of(a0, 3)] ^ rk[4 * r + 1];
+        uint32_t t2 = kt->te[0][byte_of(a2, 0)] ^ kt->te[1][byte_of(a3, 1)] ^
+                      kt->te[2][byte_of(a0, 2)] ^ kt->te[3][byte_of(a1, 3)] ^ rk[4 * r + 2];
+        uint32_t t3 = kt->te[0][byte_of(a3, 0)] ^ kt->te[1][byte_of(a0, 1)] ^
+                      kt->te[2][byte_of(a1, 2)] ^ kt->te[3][byte_of(a2, 3)] ^ rk[4 * r + 3];
+        a0 = t0, a1 = t1, a2 = t2, a3 = t3;
+    }
+    const uint8_t* S = kSbox.v;
+    auto last = [&](uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
+        return (uint32_t)S[byte_of(c0, 0)] | ((uint32_t)S[byte_of(c1, 1)] << 8) |
+               ((uint32_t)S[byte_of(c2, 2)] << 16) | ((uint32_t)S[byte_of(c3, 3)] << 24);
+    };
+    s[0] = last(a0, a1, a2, a3) ^ rk[56];
+    s[1] = last(a1, a2, a3, a0) ^ rk[57];
+    s[2] = last(a2, a3, a0, a1) ^ rk[58];
+    s[3] = last(a3, a0, a1, a2) ^ rk[59];
+}
+
+__device__ __forceinline__ uint32_t sub_word(uint32_t w) {
+    const uint8_t* S = kSbox.v;
+    return (uint32_t)S[w & 0xFF] | ((uint32_t)S[(w >> 8) & 0xFF] << 8) |
+           ((uint32_t)S[(w >> 16) & 0xFF] << 16) | ((uint32_t)S[w >> 24] << 24);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// Key set-up: key schedule (FIPS-197 5.2), round tables, H and the nibble tables of H^(2^k).
+// One workgroup; `key_words` are the 32 key bytes as 8 little-endian words.
+__global__ __launch_bounds__(1024) void expand_key_kernel(KeyTables* __restrict__ kt,
+                                                          const uint32_t* __restrict__ key_words) {
+    __shared__ Gf powers[kNumPowers];
+    const uint32_t tid = threadIdx.x;
+
+    // round tables: te[0][x] = (2s, s, s, 3s) in bytes 0..3, te[r] = te[0] rotated left by 8r bits
+    for (uint32_t x = tid; x < 256; x += blockDim.x) {
+        uint32_t s = kSbox.v[x];
+        uint32_t s2 = xtime((uint8_t)s), s3 = s2 ^ s;
+        uint32_t t0 = s2 | (s << 8) | (s << 16) | (s3 << 24);
+        kt->te[0][x] = t0;
+        kt->te[1][x] = (t0 << 8) | (t0 >> 24);
+        kt->te[2][x] = (t0 << 16) | (t0 >> 16);
+        kt->te[3][x] = (t0 << 24) | (t0 >> 8);
+    }
+    if (tid == 0) {
+        uint32_t w[60];
+        for (int i = 0; i < 8; ++i) w[i] = key_words[i];
+        uint32_t rcon = 1;
+        for (int i = 8; i < 60; ++i) {
+            uint32_t t = w[i - 1];
+            if (i % 8 == 0) {
+                t = sub_word((t >> 8) | (t << 24)) ^ rcon;  // RotWord on little-endian bytes
+                rcon = xtime((uint8_t)rcon);
+            } else if (i % 8 == 4) {
+                t = sub_word(t);
+            }
+            w[i] = w[i - 8] ^ t;
+        }
+        for (int i = 0; i < 60; ++i) kt->rk[i] = w[i];
+        for (int i = 0; i < 4; ++i) kt->pad_[i] = 0;
+    }
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t z[4] = {0, 0, 0, 0};
+        aes256_block_global(kt, z);
+        Block h{{z[0], z[1], z[2], z[3]}};
+        kt->h = h;
+        Gf p = gf_from_block(h);
+        powers[0] = p;
+        for (uint32_t k = 1; k < kNumPowers; ++k) {
+            p = gf_mul_bits(p, p);
+            powers[k] = p;
+        }
+    }
+    __syncthreads();
+    for (uint32_t e = tid; e < kNumPowers * kNibbleTableEntries; e += blockDim.x) {
+        uint32_t k = e / kNibbleTableEntries, idx = e % kNibbleTableEntries;
+        uint32_t pos = idx / 16, val = idx % 16;
+        uint32_t byte = pos / 2;
+        uint32_t bits = (pos & 1) ? val : (val << 4);
+        Block x{{0, 0, 0, 0}};
+        x.w[byte / 4] = bits << (8 * (byte % 4));
+        kt->ghash[k][idx] = gf_to_block(gf_mul_bits(gf_from_block(x), powers[k]));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// GHASH state after the AAD of each chunk (SP 800-38D 6.4 over A || 0-pad); one thread a chunk.
+__global__ __launch_bounds__(64) void aad_state_kernel(const KeyTables* __restrict__ kt,
+                                 const ChunkDesc* __restrict__ chunks, uint32_t n,
+                                 Block* __restrict__ aad_state) {
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const ChunkDesc cd = chunks[i];
+    Block y{{0, 0, 0, 0}};
+    for (uint32_t off = 0; off < cd.aad_len; off += 16) {
+        uint32_t m = cd.aad_len - off < 16 ? cd.aad_len - off : 16;
+        Block x{{0, 0, 0, 0}};
+        for (uint32_t b = 0; b < m; ++b) x.w[b / 4] |= (uint32_t)cd.aad[off + b] << (8 * (b % 4));
+        block_xor(y, x);
+        y = gf_mul_table(kt->ghash[0], y);
+    }
+    aad_state[i] = y;
+}
+
+// ------------------------------------------------------------------------------------------
+// The bulk kernel.  LDS map (byte addresses; the object below is the kernel's only LDS):
+//   [0, 64 KiB)        row x (256 B): te[0][x] in dwords 0..31, te[1][x] in dwords 32..63
+//   [64 KiB, 128 KiB)  the same for te[2], te[3]
+//   [128 KiB, 136 KiB) nibble table of H^64
+// so a lookup address is  x << 8 | fixed per-lane byte  and takes one v_perm_b32 to form.
+namespace {
+
+constexpr uint32_t kLdsTeBytes = 4 * 256 * 32 * 4;
+constexpr uint32_t kLdsGhBase = kLdsTeBytes;
+constexpr uint32_t kLdsBytes = kLdsTeBytes + kNibbleTableEntries * 16;
+
+struct alignas(16) BulkLds {
+    uint32_t te[kLdsTeBytes / 4];
+    Block gh[kNibbleTableEntries];
+};
+static_assert(sizeof(BulkLds) == kLdsBytes, "LDS map");
+
+typedef __attribute__((address_space(3))) const uint32_t* lds_u32_ptr;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) const u32x4* lds_u128_ptr;
+
+__device__ __forceinline__ uint32_t lds_read32(uint32_t addr) {
+    return *reinterpret_cast<lds_u32_ptr>(addr);
+}
+__device__ __forceinline__ u32x4 lds_read128(uint32_t addr) {
+    return *reinterpret_cast<lds_u128_ptr>(addr);
+}
+
+// byte k of w placed in byte 1, over the lane's fixed bytes 0 and 2
+template <int K>
+__device__ __forceinline__ uint32_t te_addr_lo(uint32_t w, uint32_t lane_bytes) {
+    return __builtin_amdgcn_perm(w, lane_bytes, 0x0c0c0000u | ((4u + K) << 8));
+}
+template <int K>
+__device__ __forceinline__ uint32_t te_addr_hi(uint32_t w, uint32_t lane_bytes) {
+    return __builtin_amdgcn_perm(w, lane_bytes, 0x0c020000u | ((4u + K) << 8));
+}
+
+struct AesLane {
+    uint32_t lo;  // (lane % 32) * 4
+    uint32_t hi;  // same, plus 64 KiB in byte 2
+};
+
+#define PGCM_TE0(w, k) lds_read32(te_addr_lo<k>(w, L.lo))
+#define PGCM_TE1(w, k) lds_read32(te_addr_lo<k>(w, L.lo) + 128u)
+#define PGCM_TE2(w, k) lds_read32(te_addr_hi<k>(w, L.hi))
+#define PGCM_TE3(w, k) lds_read32(te_addr_hi<k>(w, L.hi) + 128u)
+
+// E_K of one block per lane; rk is wave-uniform (scalar registers)
+__device__ __forceinline__ void aes256_lds(const uint32_t* __restrict__ rk, const AesLane L,
+                                           uint32_t& s0, uint32_t& s1, uint32_t& s2,
+                                           uint32_t& s3) {
+    s0 ^= rk[0];
+    s1 ^= rk[1];
+    s2 ^= rk[2];
+    s3 ^= rk[3];
+#pragma unroll
+    for (int r = 1; r < 14; ++r) {
+        uint32_t t0 = PGCM_TE0(s0, 0) ^ PGCM_TE1(s1, 1) ^ PGCM_TE2(s2, 2) ^ PGCM_TE3(s3, 3) ^
+                      rk[4 * r + 0];
+        uint32_t t1 = PGCM_TE0(s1, 0) ^ PGCM_TE1(s2, 1) ^ PGCM_TE2(s3, 2) ^ PGCM_TE3(s0, 3) ^
+                      rk[4 * r + 1];
+        uint32_t t2 = PGCM_TE0(s2, 0) ^ PGCM_TE1(s3, 1) ^ PGCM_TE2(s0, 2) ^ PGCM_TE3(s1, 3) ^
+                      rk[4 * r + 2];
+        uint32_t t3 = PGCM_TE0(s3, 0) ^ PGCM_TE1(s0, 1) ^ PGCM_TE2(s1, 2) ^ PGCM_TE3(s2, 3) ^
+                      rk[4 * r + 3];
+        s0 = t0, s1 = t1, s2 = t2, s3 = t3;
+    }
+    // last round: S(x) sits in byte 0 of te[2], bytes 1 and 2 of te[0], byte 3 of te[1]
+    auto last = [&](uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
+        uint32_t b0 = PGCM_TE2(c0, 0), b1 = PGCM_TE0(c1, 1), b2 = PGCM_TE0(c2, 2),
+                 b3 = PGCM_TE1(c3, 3);
+        uint32_t lo = __builtin_amdgcn_perm(b1, b0, 0x0c0c0500u);  // byte0 of b0, byte1 of b1
+        uint32_t hi = __builtin_amdgcn_perm(b3, b2, 0x07020c0cu);  // byte2 of b2, byte3 of b3
+        return lo | hi;
+    };
+    uint32_t o0 = last(s0, s1, s2, s3) ^ rk[56];
+    uint32_t o1 = last(s1, s2, s3, s0) ^ rk[57];
+    uint32_t o2 = last(s2, s3, s0, s1) ^ rk[58];
+    uint32_t o3 = last(s3, s0, s1, s2) ^ rk[59];
+    s0 = o0, s1 = o1, s2 = o2, s3 = o3;
+}
+
+// Y * H^64 from the nibble table in LDS
+__device__ __forceinline__ void ghash_mul_row_lds(uint32_t y[4]) {
+    uint32_t z0 = 0, z1 = 0, z2 = 0, z3 = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t hi = y[i] & 0xF0F0F0F0u;
+        uint32_t lo = (y[i] << 4) & 0xF0F0F0F0u;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t pos = 2 * (4 * i + k);
+            u32x4 a = lds_read128(kLdsGhBase + pos * 256 + ((hi >> (8 * k)) & 0xFF));
+            u32x4 b = lds_read128(kLdsGhBase + (pos + 1) * 256 + ((lo >> (8 * k)) & 0xFF));
+            z0 ^= a.x ^ b.x;
+            z1 ^= a.y ^ b.y;
+            z2 ^= a.z ^ b.z;
+            z3 ^= a.w ^ b.w;
+        }
+    }
+    y[0] = z0, y[1] = z1, y[2] = z2, y[3] = z3;
+}
+
+// One row of a segment: block `blk` of the chunk in this lane (if `active`).
+// kEdge rows may have idle lanes, the chunk's ragged last block and the AAD state to fold in;
+// interior rows are full and take the short path.
+template <bool kDecrypt, bool kEdge>
+__device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, const AesLane L,
+                                         const ChunkDesc& cd, uint32_t iv0, uint32_t iv1,
+                                         uint32_t iv2, int64_t blk, int64_t first_blk,
+                                         const Block* __restrict__ aad_state, uint32_t chunk,
+                                         uint32_t y[4]) {
+    bool active = true;
+    uint32_t tail = 0;  // bytes in a ragged block, 0 = whole block
+    if (kEdge) {
+        active = blk >= first_blk;
+        if (active && (uint64_t)blk * 16 + 16 > cd.len) tail = (uint32_t)(cd.len & 15);
+    }
+    if (!active) return;
+
+    uint32_t x0, x1, x2, x3;
+    const uint8_t* sp = cd.src + (uint64_t)blk * 16;
+    uint8_t* dp = cd.dst + (uint64_t)blk * 16;
+    if (kEdge && tail) {
+        uint32_t t[4] = {0, 0, 0, 0};
+        for (uint32_t b = 0; b < tail; ++b) t[b / 4] |= (uint32_t)sp[b] << (8 * (b % 4));
+        x0 = t[0], x1 = t[1], x2 = t[2], x3 = t[3];
+    } else {
+        uint4 v = *reinterpret_cast<const uint4*>(sp);
+        x0 = v.x, x1 = v.y, x2 = v.z, x3 = v.w;
+    }
+
+    // counter block IV || be32(blk + 2) (SP 800-38D 7.1 step 3 with J0 = IV || 0^31 1)
+    uint32_t s0 = iv0, s1 = iv1, s2 = iv2, s3 = bswap32((uint32_t)blk + 2u);
+    aes256_lds(rk, L, s0, s1, s2, s3);
+    uint32_t o0 = x0 ^ s0, o1 = x1 ^ s1, o2 = x2 ^ s2, o3 = x3 ^ s3;
+
+    if (kEdge && tail) {
+        uint32_t o[4] = {o0, o1, o2, o3};
+        for (uint32_t b = 0; b < tail; ++b) dp[b] = (uint8_t)(o[b / 4] >> (8 * (b % 4)));
+        // bytes past the end count as zero in the hash
+        for (uint32_t b = tail; b < 16; ++b) o[b / 4] &= ~(0xFFu << (8 * (b % 4)));
+        o0 = o[0], o1 = o[1], o2 = o[2], o3 = o[3];
+    } else {
+        *reinterpret_cast<uint4*>(dp) = make_uint4(o0, o1, o2, o3);
+    }
+
+    // the ciphertext is what gets hashed: the output when encrypting, the input when decrypting
+    uint32_t c0 = kDecrypt ? x0 : o0, c1 = kDecrypt ? x1 : o1, c2 = kDecrypt ? x2 : o2,
+             c3 = kDecrypt ? x3 : o3;
+    if (kEdge && blk == 0 && aad_state != nullptr) {
+        const Block a = aad_state[chunk];
+        c0 ^= a.w[0], c1 ^= a.w[1], c2 ^= a.w[2], c3 ^= a.w[3];
+    }
+    y[0] ^= c0, y[1] ^= c1, y[2] ^= c2, y[3] ^= c3;
+}
+
+}  // namespace
+
+// item_chunk[i] = chunk of work item i; partials[i] receives the segment's GHASH contribution
+//   P = sum over its blocks C_b * H^(blocks from b to the segment's end, inclusive).
+template <bool kDecrypt>
+__global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
+    const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks,
+    const uint32_t* __restrict__ item_chunk, uint32_t nitems, const uint8_t* __restrict__ ivs,
+    const Block* __restrict__ aad_state, Block* __restrict__ partials) {
+    __shared__ BulkLds lds;
+
+    const uint32_t tid = threadIdx.x;
+    // fill: 32 copies of every table entry, lane-interleaved
+    for (uint32_t i = tid; i < kLdsTeBytes / 4; i += kGroupThreads) {
+        uint32_t pair = i >> 14, row = (i >> 6) & 255, t = ((i >> 5) & 1) + 2 * pair;
+        lds.te[i] = kt->te[t][row];
+    }
+    for (uint32_t i = tid; i < kNibbleTableEntries; i += kGroupThreads)
+        lds.gh[i] = kt->ghash[kRowPower][i];
+    __syncthreads();
+
+    const uint32_t lane = tid & 63;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    AesLane L;
+    L.lo = (lane & 31) * 4;
+    L.hi = L.lo | 0x10000u;
+    const uint32_t* __restrict__ rk = kt->rk;
+
+    for (uint32_t item = blockIdx.x * kWavesPerGroup + wave; item < nitems;
+         item += gridDim.x * kWavesPerGroup) {
+        const uint32_t chunk = item_chunk[item];
+        const ChunkDesc cd = chunks[chunk];
+        const uint32_t seg = item - cd.part_base;
+        // segment bounds in blocks of the chunk
+        const int64_t b0 = seg == 0 ? 0 : (int64_t)cd.first_blocks + (int64_t)(seg - 1) * kSegBlocks;
+        const int64_t b1 = seg == 0 ? (int64_t)cd.first_blocks : b0 + kSegBlocks;
+        const uint32_t nrows = (uint32_t)((b1 - b0 + kRowBlocks - 1) / kRowBlocks);
+
+        const uint8_t* ivp = ivs + (uint64_t)chunk * 12;
+        uint32_t iv[3];
+        for (int i = 0; i < 3; ++i)
+            iv[i] = (uint32_t)ivp[4 * i] | ((uint32_t)ivp[4 * i + 1] << 8) |
+                    ((uint32_t)ivp[4 * i + 2] << 16) | ((uint32_t)ivp[4 * i + 3] << 24);
+
+        uint32_t y[4] = {0, 0, 0, 0};
+        // rows are aligned to the segment's end; the first may start with idle lanes
+        int64_t blk = b1 - (int64_t)nrows * kRowBlocks + lane;
+        bulk_row<kDecrypt, true>(rk, L, cd, iv[0], iv[1], iv[2], blk, b0, aad_state, chunk, y);
+        for (uint32_t r = 1; r + 1 < nrows; ++r) {
+            blk += kRowBlocks;
+            ghash_mul_row_lds(y);
+            bulk_row<kDecrypt, false>(rk, L, cd, iv[0], iv[1], iv[2], blk, b0, aad_state, chunk, y);
+        }
+        if (nrows > 1) {
+            blk += kRowBlocks;
+            ghash_mul_row_lds(y);
+            bulk_row<kDecrypt, true>(rk, L, cd, iv[0], iv[1], iv[2], blk, b0, aad_state, chunk, y);
+        }
+
+        // lanes -> one value: lane j's sum still lacks H^(63 - j); fold halves, then one more H
+        Block acc{{y[0], y[1], y[2], y[3]}};
+#pragma unroll 1
+        for (int k = 5; k >= 0; --k) {
+            Block m = gf_mul_table(kt->ghash[k], acc);
+            const int s = 1 << k;
+            m.w[0] ^= __shfl_down(acc.w[0], s, 64);
+            m.w[1] ^= __shfl_down(acc.w[1], s, 64);
+            m.w[2] ^= __shfl_down(acc.w[2], s, 64);
+            m.w[3] ^= __shfl_down(acc.w[3], s, 64);
+            acc = m;
+        }
+        if (lane == 0) partials[item] = gf_mul_table(kt->ghash[0], acc);
+    }
+}
+
+template __global__ void bulk_kernel<false>(const KeyTables*, const ChunkDesc*, const uint32_t*,
+                                            uint32_t, const uint8_t*, const Block*, Block*);
+template __global__ void bulk_kernel<true>(const KeyTables*, const ChunkDesc*, const uint32_t*,
+                                           uint32_t, const uint8_t*, const Block*, Block*);
+
+// ------------------------------------------------------------------------------------------
+// Per chunk: combine segment contributions, add the length block, mask with E_K(J0)
+// (SP 800-38D 7.1 steps 5-6); then write the tag, or compare it and write the verdict (7.2).
+template <bool kDecrypt>
+__global__ __launch_bounds__(64) void finalize_kernel(const KeyTables* __restrict__ kt,
+                                const ChunkDesc* __restrict__ chunks, uint32_t n,
+                                const uint8_t* __restrict__ ivs,
+                                const Block* __restrict__ aad_state,
+                                const Block* __restrict__ partials, uint8_t* __restrict__ tags,
+                                uint8_t* __restrict__ ok) {
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const ChunkDesc cd = chunks[i];
+    Block acc{{0, 0, 0, 0}};
+    if (cd.nseg == 0) {
+        if (aad_state != nullptr) acc = aad_state[i];
+    } else {
+        // every segment after the first is full, so each step moves the sum kSegBlocks further
+        acc = partials[cd.part_base];
+        for (uint32_t s = 1; s < cd.nseg; ++s) {
+            acc = gf_mul_table(kt->ghash[kSegPower], acc);
+            block_xor(acc, partials[cd.part_base + s]);
+        }
+    }
+    // [8 |A|]_64 || [8 |C|]_64, big endian
+    uint64_t abits = (uint64_t)cd.aad_len * 8, cbits = cd.len * 8;
+    Block lens{{bswap32((uint32_t)(abits >> 32)), bswap32((uint32_t)abits),
+                bswap32((uint32_t)(cbits >> 32)), bswap32((uint32_t)cbits)}};
+    block_xor(acc, lens);
+    acc = gf_mul_table(kt->ghash[0], acc);
+
+    const uint8_t* ivp = ivs + (uint64_t)i * 12;
+    uint32_t j0[4];
+    for (int w = 0; w < 3; ++w)
+        j0[w] = (uint32_t)ivp[4 * w] | ((uint32_t)ivp[4 * w + 1] << 8) |
+                ((uint32_t)ivp[4 * w + 2] << 16) | ((uint32_t)ivp[4 * w + 3] << 24);
+    j0[3] = 0x01000000u;  // be32(1)
+    aes256_block_global(kt, j0);
+    uint32_t t[4] = {acc.w[0] ^ j0[0], acc.w[1] ^ j0[1], acc.w[2] ^ j0[2], acc.w[3] ^ j0[3]};
+
+    uint8_t* tp = tags + (uint64_t)i * 16;
+    if (!kDecrypt) {
+        for (int b = 0; b < 16; ++b) tp[b] = (uint8_t)(t[b / 4] >> (8 * (b % 4)));
+    } else {
+        // all 16 bytes, no data-dependent exit
+        uint32_t diff = 0;
+        for (int b = 0; b < 16; ++b) diff |= (uint32_t)tp[b] ^ ((t[b / 4] >> (8 * (b % 4))) & 0xFF);
+        ok[i] = diff == 0 ? 1 : 0;
+    }
+}
+
+template __global__ void finalize_kernel<false>(const KeyTables*, const ChunkDesc*, uint32_t,
+                                                const uint8_t*, const Block*, const Block*,
+                                                uint8_t*, uint8_t*);
+template __global__ void finalize_kernel<true>(const KeyTables*, const ChunkDesc*, uint32_t,
+                                               const uint8_t*, const Block*, const Block*,
+                                               uint8_t*, uint8_t*);
+
+// Overwrites the output of every rejected chunk with zeros; one workgroup walks chunks.
+__global__ __launch_bounds__(256) void wipe_rejected_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n,
+                                     const uint8_t* __restrict__ ok) {
+    for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
+        if (ok[i] != 0) continue;
+        const ChunkDesc cd = chunks[i];
+        const uint64_t whole = cd.len / 16;
+        uint4* d = reinterpret_cast<uint4*>(cd.dst);
+        for (uint64_t b = threadIdx.x; b < whole; b += blockDim.x) d[b] = make_uint4(0, 0, 0, 0);
+        for (uint64_t b = whole * 16 + threadIdx.x; b < cd.len; b += blockDim.x) cd.dst[b] = 0;
+    }
+}
+
+}  // namespace pgcm

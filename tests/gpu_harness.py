@@ -1,0 +1,60 @@
+"""Runs a workloads.Workload through the GPU library's C ABI (via the Python binding)."""
+import numpy as np
+import torch
+
+import paper_2411_03357_amd as pgcm
+
+
+class DeviceBatch:
+    """Device-resident inputs and outputs of one workload: packed payload buffer `plain`, packed
+    ciphertext buffer `cipher`, packed decrypt output `back`, ivs, aad, tags, ok, and the host
+    descriptor arrays the ABI takes."""
+
+    def __init__(self, w, plain: torch.Tensor, device="cuda"):
+        assert plain.dtype == torch.uint8 and plain.numel() == w.total_bytes
+        self.w = w
+        self.device = device
+        self.plain = plain
+        self.cipher = torch.empty_like(plain)
+        self.back = torch.empty_like(plain)
+        self.ivs = torch.from_numpy(w.ivs.reshape(-1).copy()).to(device)
+        self.tags = torch.zeros(16 * w.n, dtype=torch.uint8, device=device)
+        self.ok = torch.full((w.n,), 0x55, dtype=torch.uint8, device=device)
+        self.lens = w.lens.astype(np.uint64)
+        self.aad_dev = None
+        self.aad_ptrs = None
+        self.aad_lens = w.aad_lens()
+        if w.aad is not None:
+            self.aad_dev = torch.from_numpy(np.concatenate([w.aad, np.zeros(1, np.uint8)])).to(device)
+            self.aad_ptrs = (np.uint64(self.aad_dev.data_ptr()) + w.aad_off[:-1]).astype(np.uint64)
+
+    def ptrs(self, buf: torch.Tensor) -> np.ndarray:
+        return (np.uint64(buf.data_ptr()) + self.w.offsets).astype(np.uint64)
+
+    def encrypt(self, key, src=None, dst=None, stream=None):
+        src = self.plain if src is None else src
+        dst = self.cipher if dst is None else dst
+        pgcm.encrypt_batch(key, self.ivs, self.aad_ptrs, self.aad_lens, self.ptrs(src), self.lens,
+                           self.ptrs(dst), self.tags, stream)
+
+    def decrypt(self, key, src=None, dst=None, tags=None, stream=None):
+        src = self.cipher if src is None else src
+        dst = self.back if dst is None else dst
+        tags = self.tags if tags is None else tags
+        pgcm.decrypt_verify_batch(key, self.ivs, self.aad_ptrs, self.aad_lens, self.ptrs(src),
+                                  self.lens, self.ptrs(dst), tags, self.ok, stream)
+
+    def chunk_host(self, buf: torch.Tensor, i: int) -> np.ndarray:
+        off, ln = int(self.w.offsets[i]), int(self.w.lens[i])
+        return buf[off:off + ln].cpu().numpy()
+
+
+def apply_tampers(w, cipher: torch.Tensor, tags: torch.Tensor):
+    """flips the bits listed in w.tampers, in place, on device copies"""
+    for t in w.tampers:
+        if t.where == "ct":
+            pos = int(w.offsets[t.chunk]) + t.bit // 8
+            cipher[pos] ^= (1 << (t.bit % 8))
+        else:
+            pos = 16 * t.chunk + t.bit // 8
+            tags[pos] ^= (1 << (t.bit % 8))

@@ -1,0 +1,87 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/pgcm.h declares;
+host-only entry points behave as documented."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2411_03357_amd as pgcm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "pgcm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pgcm_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = ctypes.CDLL(pgcm.library_path())
+    names = _declared()
+    assert len(names) >= 8
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(pgcm.EXPORTS) == names
+
+
+def test_strerror_and_null_arguments_without_gpu():
+    lib = pgcm.load_library()
+    assert lib.pgcm_strerror(0) == b"success"
+    for code in (-1, -2, -3, -4, -5, 17):
+        assert len(lib.pgcm_strerror(code)) > 0
+    assert lib.pgcm_expand_key(None, None, None) == -1
+    assert lib.pgcm_encrypt_batch(None, 1, None, None, None, None, None, None, None, None) == -1
+    assert lib.pgcm_decrypt_verify_batch(None, 0, None, None, None, None, None, None, None, None,
+                                         None) == -1
+    lib.pgcm_free_key(None)
+    assert lib.pgcm_last_hip_error() == 0
+
+
+def test_segment_plan():
+    seg = pgcm.segment_bytes()
+    assert seg % 1024 == 0 and seg >= 1024
+    sb = seg // 16
+    lens = [0, 1, 15, 16, 17, seg - 1, seg, seg + 1, 3 * seg, 3 * seg + 16 * 7 + 3, 8 << 20]
+    total, nseg, first, base = pgcm.plan_segments(lens)
+    run = 0
+    for ln, ns, fb, pb in zip(lens, nseg, first, base):
+        nblk = (ln + 15) // 16
+        assert ns == (nblk + sb - 1) // sb
+        assert pb == run
+        run += ns
+        if nblk == 0:
+            assert (ns, fb) == (0, 0)
+        else:
+            # only the first segment may be short, and never empty
+            assert 1 <= fb <= sb and fb + (ns - 1) * sb == nblk
+    assert total == run
+    with pytest.raises(pgcm.PgcmError) as e:
+        pgcm.plan_segments([1 << 36])
+    assert e.value.status == -3
+    assert pgcm.plan_segments([])[0] == 0
+
+
+def test_workload_generators_are_seeded_and_shaped():
+    import workloads
+    a, b = workloads.config4(), workloads.config4()
+    assert np.array_equal(a.lens, b.lens) and np.array_equal(a.aad, b.aad)
+    assert a.n == 2000 and 16384 <= int(a.lens.min()) and int(a.lens.max()) <= (8 << 20)
+    ragged = float((a.lens % 16 != 0).mean())
+    assert 0.25 < ragged < 0.35
+    assert int(np.diff(a.aad_off).max()) <= 64
+    c2 = workloads.config2()
+    assert c2.n == 4096 and int(c2.lens[0]) == 327680 and c2.payload_bytes == 1342177280
+    assert c2.aad_of(41) == (1).to_bytes(8, "little") + (1).to_bytes(8, "little")
+    c3, c5 = workloads.config3(), workloads.config5()
+    assert (c3.n, c5.n) == (972, 1728) and c3.payload_bytes == 24 * 9216 ** 2
+    assert c5.payload_bytes == 24 * 12288 ** 2 and len(c5.tampers) == 17
+    assert len({t.chunk for t in c5.tampers}) == 17
+    # IVs count upward as a big-endian 96-bit integer
+    iv = workloads.iv_sequence((1 << 96) - 2, 4)
+    assert [int.from_bytes(r.tobytes(), "big") for r in iv] == [(1 << 96) - 2, (1 << 96) - 1, 0, 1]
+    m = workloads.mini(1)
+    h1, h2 = m.payload_host(), m.payload_host()
+    assert np.array_equal(h1, h2) and h1.size == m.total_bytes

@@ -1,0 +1,187 @@
+"""GPU library against the CPU oracle, element by element, through the C ABI.
+
+Tolerance: none.  AES-GCM is exact integer/byte work, so ciphertext, tags, recovered plaintext
+and verdicts must be bit-identical to the oracle's."""
+import numpy as np
+import pytest
+import torch
+
+import openssl_ref
+import oracle
+import workloads
+from gpu_harness import DeviceBatch, apply_tampers
+
+import paper_2411_03357_amd as pgcm
+
+pytestmark = pytest.mark.gpu
+
+NTHREADS = 16
+
+
+def _oracle_encrypt(w, host_buf, idx=None):
+    idx = list(range(w.n)) if idx is None else idx
+    srcs = [w.chunk(host_buf, i) for i in idx]
+    aads = None if w.aad is None else [np.frombuffer(w.aad_of(i), np.uint8) for i in idx]
+    cts, tags, _ = oracle.encrypt_batch(w.key, w.ivs[idx], aads, srcs, nthreads=NTHREADS)
+    return cts, tags
+
+
+def _full_parity(w, flip=None):
+    """encrypt + decrypt-verify of the whole workload compared with the oracle on every byte"""
+    host = w.payload_host()
+    key = pgcm.expand_key(w.key)
+    b = DeviceBatch(w, torch.from_numpy(host).cuda())
+    b.cipher.fill_(0xEE)            # gaps between chunks must stay untouched
+    b.encrypt(key)
+    torch.cuda.synchronize()
+    cts, tags = _oracle_encrypt(w, host)
+    got_tags = b.tags.cpu().numpy().reshape(-1, 16)
+    cipher_host = b.cipher.cpu().numpy()
+    expect_buf = np.full(w.total_bytes, 0xEE, np.uint8)
+    for i in range(w.n):
+        off = int(w.offsets[i])
+        expect_buf[off:off + cts[i].size] = cts[i]
+    bad = np.flatnonzero(cipher_host != expect_buf)
+    assert bad.size == 0, "%s: first ciphertext mismatch at byte %d" % (w.name, bad[0])
+    assert np.array_equal(got_tags, tags), "%s: tag mismatch in chunks %s" % (
+        w.name, np.flatnonzero((got_tags != tags).any(axis=1))[:8])
+
+    # decrypt-verify, with the workload's tampering (and optional extra flips) applied
+    cipher_t, tags_t = b.cipher.clone(), b.tags.clone()
+    apply_tampers(w, cipher_t, tags_t)
+    for (chunk, byte, bit, where) in (flip or []):
+        if where == "ct":
+            cipher_t[int(w.offsets[chunk]) + byte] ^= (1 << bit)
+        else:
+            tags_t[16 * chunk + byte] ^= (1 << bit)
+    b.back.fill_(0xDD)
+    b.decrypt(key, src=cipher_t, tags=tags_t)
+    torch.cuda.synchronize()
+    ct_host = cipher_t.cpu().numpy()
+    srcs = [w.chunk(ct_host, i) for i in range(w.n)]
+    aads = None if w.aad is None else [np.frombuffer(w.aad_of(i), np.uint8) for i in range(w.n)]
+    pts, ok, _ = oracle.decrypt_verify_batch(w.key, w.ivs, aads, srcs,
+                                             tags_t.cpu().numpy().reshape(-1, 16), NTHREADS)
+    assert np.array_equal(b.ok.cpu().numpy(), ok), w.name
+    back = b.back.cpu().numpy()
+    expect_buf = np.full(w.total_bytes, 0xDD, np.uint8)
+    for i in range(w.n):
+        off = int(w.offsets[i])
+        expect_buf[off:off + pts[i].size] = pts[i]
+    bad = np.flatnonzero(back != expect_buf)
+    assert bad.size == 0, "%s: first plaintext mismatch at byte %d" % (w.name, bad[0])
+    tampered = {t.chunk for t in w.tampers} | {f[0] for f in (flip or [])}
+    assert set(np.flatnonzero(ok == 0).tolist()) == tampered
+    key.free()
+    return b
+
+
+def test_config1_full_parity():
+    _full_parity(workloads.config1())
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_reduced_configs_full_parity(cfg):
+    _full_parity(workloads.mini(cfg))
+
+
+def test_ragged_edge_cases_full_parity():
+    w = workloads.ragged_small()
+    # reject a ragged chunk via its last byte, a multi-segment one via its first, one via its tag
+    last = int(w.lens[13]) - 1
+    _full_parity(w, flip=[(13, last, 7, "ct"), (25, 0, 0, "ct"), (2, 15, 3, "tag"),
+                          (0, 0, 0, "tag")])
+
+
+def test_no_aad_form_and_in_place():
+    w = workloads.ragged_small(seed_shift=1)
+    w.aad, w.aad_off = None, None
+    host = w.payload_host()
+    key = pgcm.expand_key(w.key)
+    b = DeviceBatch(w, torch.from_numpy(host).cuda())
+    work = b.plain.clone()
+    b.encrypt(key, src=work, dst=work)          # in place
+    torch.cuda.synchronize()
+    cts, tags = _oracle_encrypt(w, host)
+    wh = work.cpu().numpy()
+    for i in range(w.n):
+        assert np.array_equal(w.chunk(wh, i), cts[i]), i
+    assert np.array_equal(b.tags.cpu().numpy().reshape(-1, 16), tags)
+    b.decrypt(key, src=work, dst=work)
+    torch.cuda.synchronize()
+    assert torch.equal(work, b.plain)
+    assert bool((b.ok == 1).all())
+    key.free()
+
+
+def test_against_libcrypto_on_device_generated_payload():
+    w = workloads.mini(4)
+    key = pgcm.expand_key(w.key)
+    b = DeviceBatch(w, w.payload_device())
+    b.encrypt(key)
+    torch.cuda.synchronize()
+    tags = b.tags.cpu().numpy().reshape(-1, 16)
+    for i in range(w.n):
+        c, t = openssl_ref.encrypt(w.key.tobytes(), w.ivs[i].tobytes(), w.aad_of(i),
+                                   b.chunk_host(b.plain, i).tobytes())
+        assert b.chunk_host(b.cipher, i).tobytes() == c and tags[i].tobytes() == t, i
+    key.free()
+
+
+def test_two_keys_and_back_to_back_batches_on_one_stream():
+    """the descriptor staging buffers are reused from call to call; results must not mix"""
+    w1, w2 = workloads.mini(1), workloads.config1(n=37, size=5000)
+    h1, h2 = w1.payload_host(), w2.payload_host()
+    k1 = pgcm.expand_key(w1.key)
+    b1 = DeviceBatch(w1, torch.from_numpy(h1).cuda())
+    b2 = DeviceBatch(w2, torch.from_numpy(h2).cuda())
+    # same key object, different batches queued without synchronising in between
+    w2.key = w1.key
+    for _ in range(3):
+        b1.encrypt(k1)
+        b2.encrypt(k1)
+        b1.decrypt(k1)
+        b2.decrypt(k1)
+    torch.cuda.synchronize()
+    for w, h, b in ((w1, h1, b1), (w2, h2, b2)):
+        cts, tags = _oracle_encrypt(w, h)
+        ch = b.cipher.cpu().numpy()
+        for i in range(w.n):
+            assert np.array_equal(w.chunk(ch, i), cts[i])
+        assert np.array_equal(b.tags.cpu().numpy().reshape(-1, 16), tags)
+        assert bool((b.ok == 1).all())
+        bh = b.back.cpu().numpy()
+        for i in range(w.n):
+            assert np.array_equal(w.chunk(bh, i), w.chunk(h, i))
+    k1.free()
+
+
+def test_error_codes_and_empty_batch():
+    w = workloads.config1(n=4, size=64)
+    key = pgcm.expand_key(w.key)
+    b = DeviceBatch(w, torch.from_numpy(w.payload_host()).cuda())
+    before = b.cipher.clone()
+    # empty batch: nothing happens
+    pgcm.encrypt_batch(key, b.ivs, None, None, np.zeros(0, np.uint64), np.zeros(0, np.uint64),
+                       np.zeros(0, np.uint64), b.tags)
+    src, dst = b.ptrs(b.plain), b.ptrs(b.cipher)
+    with pytest.raises(pgcm.PgcmError) as e:
+        pgcm.encrypt_batch(key, b.ivs, None, None, src + np.uint64(4), b.lens, dst, b.tags)
+    assert e.value.status == -2
+    with pytest.raises(pgcm.PgcmError) as e:
+        big = b.lens.copy()
+        big[1] = (1 << 36) - 31
+        pgcm.encrypt_batch(key, b.ivs, None, None, src, big, dst, b.tags)
+    assert e.value.status == -3
+    with pytest.raises(pgcm.PgcmError) as e:
+        pgcm.encrypt_batch(key, b.ivs, None, np.zeros(4, np.uint32), src, b.lens, dst, b.tags)
+    assert e.value.status == -1
+    with pytest.raises(pgcm.PgcmError) as e:
+        pgcm.encrypt_batch(key, None, None, None, src, b.lens, dst, b.tags)
+    assert e.value.status == -1
+    with pytest.raises(pgcm.PgcmError) as e:
+        pgcm.decrypt_verify_batch(key, b.ivs, None, None, src, b.lens, dst, b.tags, None)
+    assert e.value.status == -1
+    torch.cuda.synchronize()
+    assert torch.equal(b.cipher, before)        # failed calls enqueue nothing
+    key.free()
