@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Throughput of batched AES-256-GCM (encrypt, then decrypt-verify) on one MI355X.
+
+A step is one pass of the whole path over one batch: pgcm_encrypt_batch followed by
+pgcm_decrypt_verify_batch of the same chunks, payload resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit op per lane-clock
+
+
+def cpu_baseline(w, chunks, threads):
+    """the oracle as it stands, timed on this host's cores over a bounded sample of the batch"""
+    import numpy as np
+    import oracle
+    idx = list(range(min(chunks, w.n)))
+    sub_lens = [int(w.lens[i]) for i in idx]
+    rng = np.random.default_rng(5)
+    srcs = [rng.integers(0, 256, ln, dtype=np.uint8) for ln in sub_lens]
+    aads = None if w.aad is None else [np.frombuffer(w.aad_of(i), np.uint8) for i in idx]
+    t0 = time.perf_counter()
+    cts, tags, used = oracle.encrypt_batch(w.key, w.ivs[idx], aads, srcs, nthreads=threads)
+    pts, ok, used2 = oracle.decrypt_verify_batch(w.key, w.ivs[idx], aads, cts, tags, threads)
+    dt = time.perf_counter() - t0
+    assert bool((ok == 1).all())
+    nbytes = 2 * sum(sub_lens)
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": int(max(used, used2)),
+            "kind": "oracle",
+            "sample": "encrypt + decrypt-verify of the first %d chunks (%d B each way) of the same "
+                      "batch shape, %.1f s" % (len(idx), sum(sub_lens), dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-chunks", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (chunks are independent; a multi-GPU "
+              "run would just split the chunk list); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import workloads
+    import paper_2411_03357_amd as pgcm
+    from gpu_harness import DeviceBatch
+
+    torch.cuda.set_device(0)
+    w = workloads.FULL[args.config]()
+    key = pgcm.expand_key(w.key)
+    b = DeviceBatch(w, w.payload_device())
+    payload = w.payload_bytes
+    stream = torch.cuda.current_stream()
+
+    def step():
+        b.encrypt(key)
+        b.decrypt(key)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # whole-path timing: host clock around K steps, synchronised on both sides
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    value = 2.0 * payload * args.steps / dt / 1e9
+
+    # per-direction whole-call timing with events on the launch stream
+    def timed_calls(fn, reps):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(reps)]
+        for s, e in ev:
+            s.record(stream)
+            fn(key)
+            e.record(stream)
+        torch.cuda.synchronize()
+        return sorted(s.elapsed_time(e) for s, e in ev)
+
+    reps = max(5, min(args.steps, 20))
+    enc_ms = timed_calls(b.encrypt, reps)
+    dec_ms = timed_calls(b.decrypt, reps)
+
+    # the dominant kernel alone: HIP events recorded by the library around the bulk kernel
+    pgcm.set_timing(key, True)
+    kern = {"enc": [], "dec": []}
+    for _ in range(reps):
+        b.encrypt(key)
+        kern["enc"].append(pgcm.last_bulk_kernel_ms(key))
+        b.decrypt(key)
+        kern["dec"].append(pgcm.last_bulk_kernel_ms(key))
+    pgcm.set_timing(key, False)
+    torch.cuda.synchronize()
+    assert bool((b.ok == 1).all()) and torch.equal(b.back, b.plain), "round trip failed"
+
+    kern_avg_ms = (sum(kern["enc"]) + sum(kern["dec"])) / (2 * reps)
+    # algorithmic HBM bytes of one bulk launch: every payload byte read once and written once,
+    # plus per chunk IV (12), descriptor (48), AAD state (16) and per segment the item map (4)
+    # and the partial hash (16)
+    nitems = pgcm.plan_segments(w.lens)[0]
+    algo_bytes = 2 * payload + w.n * (12 + 48 + 16) + nitems * (4 + 16)
+    achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "AES-256-GCM enc / dec+verify GB/s on 1 MI355X; % of HBM roofline",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": w.name, "chunks": w.n, "payload_bytes": payload,
+                   "step": "encrypt batch + decrypt-verify batch", "segment_bytes": pgcm.segment_bytes()},
+        "enc_GBps": round(payload / (enc_ms[len(enc_ms) // 2] * 1e-3) / 1e9, 2),
+        "dec_verify_GBps": round(payload / (dec_ms[len(dec_ms) // 2] * 1e-3) / 1e9, 2),
+        "pct_hbm_roofline": round(100.0 * 2.0 * value / HBM_PEAK_GBS, 2),
+        "roofline": {"bound": "hbm", "kernel": "bulk_kernel (CTR keystream + XOR + GHASH)",
+                     "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "avg_launch_ms": round(kern_avg_ms, 4),
+                     "enc_launch_ms": round(sum(kern["enc"]) / reps, 4),
+                     "dec_launch_ms": round(sum(kern["dec"]) / reps, 4)},
+    }
+    if not args.no_cpu_baseline:
+        chunks = args.cpu_chunks or max(1, int(40e6 // max(1, int(w.lens.mean()))))
+        threads = min(16, os.cpu_count() or 1)
+        out["cpu_baseline"] = cpu_baseline(w, chunks, threads)
+    key.free()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
