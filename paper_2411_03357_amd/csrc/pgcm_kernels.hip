@@ -12,6 +12,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "pgcm_kernels.h"
 
 namespace pgcm {
@@ -242,25 +244,38 @@ __global__ __launch_bounds__(64) void aad_state_kernel(const KeyTables* __restri
 
 // ------------------------------------------------------------------------------------------
 // The bulk kernel.  LDS map (byte addresses; the object below is the kernel's only LDS):
-//   [0, 64 KiB)        row x (256 B): te[0][x] in dwords 0..31, te[1][x] in dwords 32..63
-//   [64 KiB, 128 KiB)  the same for te[2], te[3]
-//   [128 KiB, 136 KiB) nibble table of H^64
-// so a lookup address is  x << 8 | fixed per-lane byte  and takes one v_perm_b32 to form.
+//   [0, 8 KiB)           nibble table of H^64 (entry offsets fit the 16-bit DS offset field)
+//   [8 KiB, 72 KiB)      row x (256 B): te[0][x] in dwords 0..31, te[1][x] in dwords 32..63
+//   [72 KiB, 136 KiB)    the same for te[2], te[3]
+// A round-table lookup address is  pair << 16 | x << 8 | 4 * (lane % 32)  plus a constant DS
+// offset, so lane l always reads bank l % 32: lookups never collide, whatever the data.
 namespace {
 
+constexpr uint32_t kLdsGhBytes = kNibbleTableEntries * 16;
+constexpr uint32_t kLdsTeBase = kLdsGhBytes;
 constexpr uint32_t kLdsTeBytes = 4 * 256 * 32 * 4;
-constexpr uint32_t kLdsGhBase = kLdsTeBytes;
-constexpr uint32_t kLdsBytes = kLdsTeBytes + kNibbleTableEntries * 16;
+constexpr uint32_t kLdsBytes = kLdsGhBytes + kLdsTeBytes;
 
 struct alignas(16) BulkLds {
-    uint32_t te[kLdsTeBytes / 4];
     Block gh[kNibbleTableEntries];
+    uint32_t te[kLdsTeBytes / 4];
 };
 static_assert(sizeof(BulkLds) == kLdsBytes, "LDS map");
 
 typedef __attribute__((address_space(3))) const uint32_t* lds_u32_ptr;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) const u32x4* lds_u128_ptr;
+typedef __attribute__((address_space(1))) const u32x4* global_u128_cptr;
+typedef __attribute__((address_space(1))) u32x4* global_u128_ptr;
+
+// payload accesses go through global (not flat) instructions, so that waiting for LDS results
+// never waits for them
+__device__ __forceinline__ u32x4 global_read128(const uint8_t* p) {
+    return *reinterpret_cast<global_u128_cptr>(reinterpret_cast<uintptr_t>(p));
+}
+__device__ __forceinline__ void global_write128(uint8_t* p, u32x4 v) {
+    *reinterpret_cast<global_u128_ptr>(reinterpret_cast<uintptr_t>(p)) = v;
+}
 
 __device__ __forceinline__ uint32_t lds_read32(uint32_t addr) {
     return *reinterpret_cast<lds_u32_ptr>(addr);
@@ -269,91 +284,209 @@ __device__ __forceinline__ u32x4 lds_read128(uint32_t addr) {
     return *reinterpret_cast<lds_u128_ptr>(addr);
 }
 
-// byte k of w placed in byte 1, over the lane's fixed bytes 0 and 2
-template <int K>
-__device__ __forceinline__ uint32_t te_addr_lo(uint32_t w, uint32_t lane_bytes) {
-    return __builtin_amdgcn_perm(w, lane_bytes, 0x0c0c0000u | ((4u + K) << 8));
-}
-template <int K>
-__device__ __forceinline__ uint32_t te_addr_hi(uint32_t w, uint32_t lane_bytes) {
-    return __builtin_amdgcn_perm(w, lane_bytes, 0x0c020000u | ((4u + K) << 8));
+// Round-table reads.  `a` already is pair << 16 | x << 8 | lane byte; T selects the table of the
+// pair through the constant part of the address.
+template <int T>
+__device__ __forceinline__ uint32_t te_read(uint32_t a) {
+    return lds_read32(a + kLdsTeBase + 128u * (T & 1));
 }
 
-struct AesLane {
-    uint32_t lo;  // (lane % 32) * 4
-    uint32_t hi;  // same, plus 64 KiB in byte 2
+// a.byte1 = rk.byte[KS] ^ v.byte[KV], every other byte of a kept: one SDWA instruction folds the
+// AddRoundKey of a state byte into forming its next lookup address.
+template <int KS, int KV>
+__device__ __forceinline__ void key_xor_into_addr(uint32_t& a, uint32_t rk, uint32_t v) {
+    static_assert(KS >= 0 && KS < 4 && KV >= 0 && KV < 4, "byte index");
+    if constexpr (KS == 0 && KV == 0)
+        asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_0 src1_sel:BYTE_0" : "+v"(a) : "s"(rk), "v"(v));
+    else if constexpr (KS == 1 && KV == 1)
+        asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_1 src1_sel:BYTE_1" : "+v"(a) : "s"(rk), "v"(v));
+    else if constexpr (KS == 2 && KV == 2)
+        asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_2 src1_sel:BYTE_2" : "+v"(a) : "s"(rk), "v"(v));
+    else if constexpr (KS == 3 && KV == 3)
+        asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_3 src1_sel:BYTE_3" : "+v"(a) : "s"(rk), "v"(v));
+    else if constexpr (KS == 3 && KV == 0)
+        asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_3 src1_sel:BYTE_0" : "+v"(a) : "s"(rk), "v"(v));
+    else if constexpr (KS == 2 && KV == 1)
+        asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_2 src1_sel:BYTE_1" : "+v"(a) : "s"(rk), "v"(v));
+    else if constexpr (KS == 1 && KV == 2)
+        asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_1 src1_sel:BYTE_2" : "+v"(a) : "s"(rk), "v"(v));
+    else if constexpr (KS == 0 && KV == 3)
+        asm("v_xor_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_0 src1_sel:BYTE_3" : "+v"(a) : "s"(rk), "v"(v));
+    else
+        static_assert(KS == KV, "unsupported byte pairing");
+}
+
+// Sixteen lookup-address registers, one per state byte: a[j][k] serves byte k (row k) of column
+// j and always reads table k.  Bytes 0 and 2 hold the lane's constants for the whole kernel;
+// byte 1 is rewritten every round.
+struct AesAddr {
+    uint32_t a[4][4];
 };
 
-#define PGCM_TE0(w, k) lds_read32(te_addr_lo<k>(w, L.lo))
-#define PGCM_TE1(w, k) lds_read32(te_addr_lo<k>(w, L.lo) + 128u)
-#define PGCM_TE2(w, k) lds_read32(te_addr_hi<k>(w, L.hi))
-#define PGCM_TE3(w, k) lds_read32(te_addr_hi<k>(w, L.hi) + 128u)
-
-// E_K of one block per lane; rk is wave-uniform (scalar registers)
-__device__ __forceinline__ void aes256_lds(const uint32_t* __restrict__ rk, const AesLane L,
-                                           uint32_t& s0, uint32_t& s1, uint32_t& s2,
-                                           uint32_t& s3) {
-    s0 ^= rk[0];
-    s1 ^= rk[1];
-    s2 ^= rk[2];
-    s3 ^= rk[3];
+__device__ __forceinline__ void aes_addr_init(AesAddr& A, uint32_t lane) {
+    const uint32_t lo = (lane & 31) * 4, hi = lo | 0x10000u;
 #pragma unroll
-    for (int r = 1; r < 14; ++r) {
-        uint32_t t0 = PGCM_TE0(s0, 0) ^ PGCM_TE1(s1, 1) ^ PGCM_TE2(s2, 2) ^ PGCM_TE3(s3, 3) ^
-                      rk[4 * r + 0];
-        uint32_t t1 = PGCM_TE0(s1, 0) ^ PGCM_TE1(s2, 1) ^ PGCM_TE2(s3, 2) ^ PGCM_TE3(s0, 3) ^
-                      rk[4 * r + 1];
-        uint32_t t2 = PGCM_TE0(s2, 0) ^ PGCM_TE1(s3, 1) ^ PGCM_TE2(s0, 2) ^ PGCM_TE3(s1, 3) ^
-                      rk[4 * r + 2];
-        uint32_t t3 = PGCM_TE0(s3, 0) ^ PGCM_TE1(s0, 1) ^ PGCM_TE2(s1, 2) ^ PGCM_TE3(s2, 3) ^
-                      rk[4 * r + 3];
-        s0 = t0, s1 = t1, s2 = t2, s3 = t3;
+    for (int j = 0; j < 4; ++j) {
+        A.a[j][0] = lo;
+        A.a[j][1] = lo;
+        A.a[j][2] = hi;
+        A.a[j][3] = hi;
     }
-    // last round: S(x) sits in byte 0 of te[2], bytes 1 and 2 of te[0], byte 3 of te[1]
-    auto last = [&](uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
-        uint32_t b0 = PGCM_TE2(c0, 0), b1 = PGCM_TE0(c1, 1), b2 = PGCM_TE0(c2, 2),
-                 b3 = PGCM_TE1(c3, 3);
-        uint32_t lo = __builtin_amdgcn_perm(b1, b0, 0x0c0c0500u);  // byte0 of b0, byte1 of b1
-        uint32_t hi = __builtin_amdgcn_perm(b3, b2, 0x07020c0cu);  // byte2 of b2, byte3 of b3
-        return lo | hi;
-    };
-    uint32_t o0 = last(s0, s1, s2, s3) ^ rk[56];
-    uint32_t o1 = last(s1, s2, s3, s0) ^ rk[57];
-    uint32_t o2 = last(s2, s3, s0, s1) ^ rk[58];
-    uint32_t o3 = last(s3, s0, s1, s2) ^ rk[59];
-    s0 = o0, s1 = o1, s2 = o2, s3 = o3;
 }
 
-// Y * H^64 from the nibble table in LDS
-__device__ __forceinline__ void ghash_mul_row_lds(uint32_t y[4]) {
-    uint32_t z0 = 0, z1 = 0, z2 = 0, z3 = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint32_t hi = y[i] & 0xF0F0F0F0u;
-        uint32_t lo = (y[i] << 4) & 0xF0F0F0F0u;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            uint32_t pos = 2 * (4 * i + k);
-            u32x4 a = lds_read128(kLdsGhBase + pos * 256 + ((hi >> (8 * k)) & 0xFF));
-            u32x4 b = lds_read128(kLdsGhBase + (pos + 1) * 256 + ((lo >> (8 * k)) & 0xFF));
-            z0 ^= a.x ^ b.x;
-            z1 ^= a.y ^ b.y;
-            z2 ^= a.z ^ b.z;
-            z3 ^= a.w ^ b.w;
-        }
+// The first three words of every counter block of a chunk are its IV, so in round 1 three of the
+// four lookups of each column do not depend on the block: their sums are formed once per segment.
+struct CtrConsts {
+    uint32_t k[4];
+};
+
+__device__ __forceinline__ CtrConsts ctr_consts(const uint32_t* __restrict__ rk, uint32_t lane,
+                                                uint32_t iv0, uint32_t iv1, uint32_t iv2) {
+    const uint32_t lo = (lane & 31) * 4, hi = lo | 0x10000u;
+    const uint32_t s0 = iv0 ^ rk[0], s1 = iv1 ^ rk[1], s2 = iv2 ^ rk[2];
+    auto at = [&](uint32_t w, int k, uint32_t lane_bytes) {
+        return (((w >> (8 * k)) & 0xFFu) << 8) | lane_bytes;
+    };
+    CtrConsts c;
+    c.k[0] = te_read<0>(at(s0, 0, lo)) ^ te_read<1>(at(s1, 1, lo)) ^ te_read<2>(at(s2, 2, hi));
+    c.k[1] = te_read<0>(at(s1, 0, lo)) ^ te_read<1>(at(s2, 1, lo)) ^ te_read<3>(at(s0, 3, hi));
+    c.k[2] = te_read<0>(at(s2, 0, lo)) ^ te_read<2>(at(s0, 2, hi)) ^ te_read<3>(at(s1, 3, hi));
+    c.k[3] = te_read<1>(at(s0, 1, lo)) ^ te_read<2>(at(s1, 2, hi)) ^ te_read<3>(at(s2, 3, hi));
+    return c;
+}
+
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
     }
-    y[0] = z0, y[1] = z1, y[2] = z2, y[3] = z3;
+}
+
+// (v.byte[K]) & 0xF0: the table offset of a high nibble, in one instruction
+template <int K>
+__device__ __forceinline__ uint32_t nibble_offset(uint32_t v, uint32_t mask_f0) {
+    uint32_t r;
+    if constexpr (K == 0)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "s"(mask_f0), "v"(v));
+    else if constexpr (K == 1)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "s"(mask_f0), "v"(v));
+    else if constexpr (K == 2)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "s"(mask_f0), "v"(v));
+    else
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "s"(mask_f0), "v"(v));
+    return r;
+}
+
+// Y * H^64 from the nibble table in LDS, cut into sixteen byte steps (two 16-byte lookups and
+// eight XORs each) so that the steps can be spread over the AES rounds of the same row: the
+// hash arithmetic then fills the time the wavefront would wait for round-table lookups.
+struct GhashRowMul {
+    uint32_t w[4];  // the multiplicand
+    uint32_t t;     // current word << 4: its byte k carries the low nibble of byte k
+    uint32_t z0 = 0, z1 = 0, z2 = 0, z3 = 0;
+    u32x4 ra, rb;
+
+    template <int S>
+    __device__ __forceinline__ void issue() {
+        constexpr int i = S / 4, k = S % 4;
+        constexpr uint32_t pos = 2 * S;
+        const uint32_t f0 = 0xF0u;
+        if constexpr (k == 0) t = w[i] << 4;
+        ra = lds_read128(nibble_offset<k>(w[i], f0) + pos * 256);
+        rb = lds_read128(nibble_offset<k>(t, f0) + (pos + 1) * 256);
+    }
+    __device__ __forceinline__ void consume() {
+        z0 ^= ra.x ^ rb.x;
+        z1 ^= ra.y ^ rb.y;
+        z2 ^= ra.z ^ rb.z;
+        z3 ^= ra.w ^ rb.w;
+    }
+    template <int S>
+    __device__ __forceinline__ void step() {
+        issue<S>();
+        consume();
+    }
+};
+
+// E_K(IV || be32(ctr)) for this lane's counter, with the row's GHASH multiplication G riding
+// along; rk is wave-uniform (scalar registers).  Between rounds the state is carried without its
+// round key: the key bytes are added while the next round's addresses are formed.
+__device__ __forceinline__ void aes256_ctr_lds(const uint32_t* __restrict__ rk, AesAddr& A,
+                                               const CtrConsts& C, uint32_t ctr, GhashRowMul& G,
+                                               uint32_t& o0, uint32_t& o1, uint32_t& o2,
+                                               uint32_t& o3) {
+    // round 1: the counter is the last word, big endian: state byte k is counter byte 3 - k
+    key_xor_into_addr<3, 0>(A.a[3][3], rk[3], ctr);
+    key_xor_into_addr<2, 1>(A.a[3][2], rk[3], ctr);
+    key_xor_into_addr<1, 2>(A.a[3][1], rk[3], ctr);
+    key_xor_into_addr<0, 3>(A.a[3][0], rk[3], ctr);
+    uint32_t l0 = te_read<3>(A.a[3][3]), l1 = te_read<2>(A.a[3][2]), l2 = te_read<1>(A.a[3][1]),
+             l3 = te_read<0>(A.a[3][0]);
+    G.issue<0>();
+    uint32_t u0 = C.k[0] ^ l0, u1 = C.k[1] ^ l1, u2 = C.k[2] ^ l2, u3 = C.k[3] ^ l3;
+    G.consume();
+    G.step<1>();
+    G.step<2>();
+    static_for<2, 15>([&](auto round) __attribute__((always_inline)) {
+        constexpr int r = decltype(round)::value;
+        const uint32_t* k = rk + 4 * (r - 1);
+        key_xor_into_addr<0, 0>(A.a[0][0], k[0], u0);
+        key_xor_into_addr<1, 1>(A.a[0][1], k[0], u0);
+        key_xor_into_addr<2, 2>(A.a[0][2], k[0], u0);
+        key_xor_into_addr<3, 3>(A.a[0][3], k[0], u0);
+        key_xor_into_addr<0, 0>(A.a[1][0], k[1], u1);
+        key_xor_into_addr<1, 1>(A.a[1][1], k[1], u1);
+        key_xor_into_addr<2, 2>(A.a[1][2], k[1], u1);
+        key_xor_into_addr<3, 3>(A.a[1][3], k[1], u1);
+        key_xor_into_addr<0, 0>(A.a[2][0], k[2], u2);
+        key_xor_into_addr<1, 1>(A.a[2][1], k[2], u2);
+        key_xor_into_addr<2, 2>(A.a[2][2], k[2], u2);
+        key_xor_into_addr<3, 3>(A.a[2][3], k[2], u2);
+        key_xor_into_addr<0, 0>(A.a[3][0], k[3], u3);
+        key_xor_into_addr<1, 1>(A.a[3][1], k[3], u3);
+        key_xor_into_addr<2, 2>(A.a[3][2], k[3], u3);
+        key_xor_into_addr<3, 3>(A.a[3][3], k[3], u3);
+        uint32_t t00 = te_read<0>(A.a[0][0]), t11 = te_read<1>(A.a[1][1]),
+                 t22 = te_read<2>(A.a[2][2]), t33 = te_read<3>(A.a[3][3]);
+        uint32_t t10 = te_read<0>(A.a[1][0]), t21 = te_read<1>(A.a[2][1]),
+                 t32 = te_read<2>(A.a[3][2]), t03 = te_read<3>(A.a[0][3]);
+        uint32_t t20 = te_read<0>(A.a[2][0]), t31 = te_read<1>(A.a[3][1]),
+                 t02 = te_read<2>(A.a[0][2]), t13 = te_read<3>(A.a[1][3]);
+        uint32_t t30 = te_read<0>(A.a[3][0]), t01 = te_read<1>(A.a[0][1]),
+                 t12 = te_read<2>(A.a[1][2]), t23 = te_read<3>(A.a[2][3]);
+        // one GHASH byte step per round: steps 3 .. 15 in rounds 2 .. 14
+        G.template issue<r + 1>();
+        if constexpr (r < 14) {
+            u0 = t00 ^ t11 ^ t22 ^ t33;
+            u1 = t10 ^ t21 ^ t32 ^ t03;
+            u2 = t20 ^ t31 ^ t02 ^ t13;
+            u3 = t30 ^ t01 ^ t12 ^ t23;
+        } else {
+            // last round, no MixColumns: S(x) is byte 1 of te[0], byte 2 of te[1], byte 0 of
+            // te[2] and te[3]
+            auto last = [&](uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3, uint32_t key) {
+                uint32_t lo = __builtin_amdgcn_perm(v0, v1, 0x0c0c0205u);  // [v0.b1, v1.b2, 0, 0]
+                uint32_t hi = __builtin_amdgcn_perm(v2, v3, 0x00040c0cu);  // [0, 0, v2.b0, v3.b0]
+                return lo ^ hi ^ key;
+            };
+            o0 = last(t00, t11, t22, t33, rk[56]);
+            o1 = last(t10, t21, t32, t03, rk[57]);
+            o2 = last(t20, t31, t02, t13, rk[58]);
+            o3 = last(t30, t01, t12, t23, rk[59]);
+        }
+        G.consume();
+    });
 }
 
 // One row of a segment: block `blk` of the chunk in this lane (if `active`).
 // kEdge rows may have idle lanes, the chunk's ragged last block and the AAD state to fold in;
 // interior rows are full and take the short path.
 template <bool kDecrypt, bool kEdge>
-__device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, const AesLane L,
-                                         const ChunkDesc& cd, uint32_t iv0, uint32_t iv1,
-                                         uint32_t iv2, int64_t blk, int64_t first_blk,
-                                         const Block* __restrict__ aad_state, uint32_t chunk,
-                                         uint32_t y[4]) {
+__device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAddr& A,
+                                         const CtrConsts& C, const ChunkDesc& cd, int64_t blk,
+                                         int64_t first_blk, const Block* __restrict__ aad_state,
+                                         uint32_t chunk, uint32_t y[4]) {
     bool active = true;
     uint32_t tail = 0;  // bytes in a ragged block, 0 = whole block
     if (kEdge) {
@@ -370,13 +503,16 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, const 
         for (uint32_t b = 0; b < tail; ++b) t[b / 4] |= (uint32_t)sp[b] << (8 * (b % 4));
         x0 = t[0], x1 = t[1], x2 = t[2], x3 = t[3];
     } else {
-        uint4 v = *reinterpret_cast<const uint4*>(sp);
+        u32x4 v = global_read128(sp);
         x0 = v.x, x1 = v.y, x2 = v.z, x3 = v.w;
     }
 
     // counter block IV || be32(blk + 2) (SP 800-38D 7.1 step 3 with J0 = IV || 0^31 1)
-    uint32_t s0 = iv0, s1 = iv1, s2 = iv2, s3 = bswap32((uint32_t)blk + 2u);
-    aes256_lds(rk, L, s0, s1, s2, s3);
+    // ... while the hash state moves one row along: Y <- Y * H^64
+    GhashRowMul G;
+    G.w[0] = y[0], G.w[1] = y[1], G.w[2] = y[2], G.w[3] = y[3];
+    uint32_t s0, s1, s2, s3;
+    aes256_ctr_lds(rk, A, C, (uint32_t)blk + 2u, G, s0, s1, s2, s3);
     uint32_t o0 = x0 ^ s0, o1 = x1 ^ s1, o2 = x2 ^ s2, o3 = x3 ^ s3;
 
     if (kEdge && tail) {
@@ -386,7 +522,8 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, const 
         for (uint32_t b = tail; b < 16; ++b) o[b / 4] &= ~(0xFFu << (8 * (b % 4)));
         o0 = o[0], o1 = o[1], o2 = o[2], o3 = o[3];
     } else {
-        *reinterpret_cast<uint4*>(dp) = make_uint4(o0, o1, o2, o3);
+        u32x4 o = {o0, o1, o2, o3};
+        global_write128(dp, o);
     }
 
     // the ciphertext is what gets hashed: the output when encrypting, the input when decrypting
@@ -396,7 +533,7 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, const 
         const Block a = aad_state[chunk];
         c0 ^= a.w[0], c1 ^= a.w[1], c2 ^= a.w[2], c3 ^= a.w[3];
     }
-    y[0] ^= c0, y[1] ^= c1, y[2] ^= c2, y[3] ^= c3;
+    y[0] = G.z0 ^ c0, y[1] = G.z1 ^ c1, y[2] = G.z2 ^ c2, y[3] = G.z3 ^ c3;
 }
 
 }  // namespace
@@ -422,10 +559,12 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
 
     const uint32_t lane = tid & 63;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    AesLane L;
-    L.lo = (lane & 31) * 4;
-    L.hi = L.lo | 0x10000u;
-    const uint32_t* __restrict__ rk = kt->rk;
+    AesAddr A;
+    aes_addr_init(A, lane);
+    // the round keys stay in scalar registers for the whole kernel
+    uint32_t rk[60];
+#pragma unroll
+    for (int i = 0; i < 60; ++i) rk[i] = kt->rk[i];
 
     for (uint32_t item = blockIdx.x * kWavesPerGroup + wave; item < nitems;
          item += gridDim.x * kWavesPerGroup) {
@@ -443,19 +582,19 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
             iv[i] = (uint32_t)ivp[4 * i] | ((uint32_t)ivp[4 * i + 1] << 8) |
                     ((uint32_t)ivp[4 * i + 2] << 16) | ((uint32_t)ivp[4 * i + 3] << 24);
 
+        const CtrConsts C = ctr_consts(rk, lane, iv[0], iv[1], iv[2]);
+
         uint32_t y[4] = {0, 0, 0, 0};
         // rows are aligned to the segment's end; the first may start with idle lanes
         int64_t blk = b1 - (int64_t)nrows * kRowBlocks + lane;
-        bulk_row<kDecrypt, true>(rk, L, cd, iv[0], iv[1], iv[2], blk, b0, aad_state, chunk, y);
+        bulk_row<kDecrypt, true>(rk, A, C, cd, blk, b0, aad_state, chunk, y);
         for (uint32_t r = 1; r + 1 < nrows; ++r) {
             blk += kRowBlocks;
-            ghash_mul_row_lds(y);
-            bulk_row<kDecrypt, false>(rk, L, cd, iv[0], iv[1], iv[2], blk, b0, aad_state, chunk, y);
+            bulk_row<kDecrypt, false>(rk, A, C, cd, blk, b0, aad_state, chunk, y);
         }
         if (nrows > 1) {
             blk += kRowBlocks;
-            ghash_mul_row_lds(y);
-            bulk_row<kDecrypt, true>(rk, L, cd, iv[0], iv[1], iv[2], blk, b0, aad_state, chunk, y);
+            bulk_row<kDecrypt, true>(rk, A, C, cd, blk, b0, aad_state, chunk, y);
         }
 
         // lanes -> one value: lane j's sum still lacks H^(63 - j); fold halves, then one more H
