@@ -100,18 +100,21 @@ int pgcm_last_hip_error(void);
 
 /*
  * Host-only view of the chunk-to-wavefront schedule (section 5.1: requests arrive as batches of
- * copies of differing sizes).  Every chunk is cut into segments of pgcm_segment_bytes() bytes
- * counted back from its end, so only a chunk's first segment can be short; each segment is one
- * work item.  Fills, for chunk i, nseg[i] (number of segments, 0 for an empty chunk),
- * first_blocks[i] (16-byte blocks in its first segment) and part_base[i] (index of its first
- * segment among all work items).  Any output pointer may be NULL.  Returns the total number of
- * work items, or a negative pgcm_status.  Touches no GPU state.
+ * copies of differing sizes).  Every chunk is cut into units of pgcm_unit_bytes() bytes counted
+ * back from its end, so only a chunk's first unit can be short; wavefronts take units one at a
+ * time from a shared counter.  Every unit leaves 64 partial hash sums; a chunk's sums are folded
+ * 32 units at a time, level by level, until at most 32 remain for the chunk's final step.
+ * Fills, for chunk i: nunits[i] (0 for an empty chunk), first_blocks[i] (16-byte blocks in its
+ * first unit), unit_base[i] (index of its first unit among all units of the batch),
+ * final_count[i] (partial sets left for the final step, 0..32) and final_power[i] (log2 of the
+ * distance in blocks between them).  Any output pointer may be NULL.  Returns the total number
+ * of units, or a negative pgcm_status.  Touches no GPU state.
  */
-int64_t pgcm_plan_segments(size_t n, const uint64_t *len, uint32_t *nseg, uint32_t *first_blocks,
-                           uint32_t *part_base);
+int64_t pgcm_plan_units(size_t n, const uint64_t *len, uint32_t *nunits, uint32_t *first_blocks,
+                        uint32_t *unit_base, uint32_t *final_count, uint32_t *final_power);
 
-/* Bytes per full segment (a multiple of the 1 KiB a wavefront handles per step). */
-uint32_t pgcm_segment_bytes(void);
+/* Bytes per full unit (a multiple of the 1 KiB a wavefront handles per step). */
+uint32_t pgcm_unit_bytes(void);
 
 /*
  * Measurement aid.  With timing enabled, every batch call also records a pair of HIP events on

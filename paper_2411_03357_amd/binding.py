@@ -9,7 +9,7 @@ _LIB_PATH = os.path.join(_HERE, "libpgcm.so")
 _lib = None
 
 EXPORTS = ("pgcm_expand_key", "pgcm_free_key", "pgcm_encrypt_batch", "pgcm_decrypt_verify_batch",
-           "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_segments", "pgcm_segment_bytes",
+           "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_units", "pgcm_unit_bytes",
            "pgcm_set_timing", "pgcm_last_bulk_kernel_ms")
 
 
@@ -47,10 +47,10 @@ def load_library():
     lib.pgcm_strerror.restype = C.c_char_p
     lib.pgcm_last_hip_error.argtypes = []
     lib.pgcm_last_hip_error.restype = C.c_int
-    lib.pgcm_plan_segments.argtypes = [sz, vp, vp, vp, vp]
-    lib.pgcm_plan_segments.restype = C.c_int64
-    lib.pgcm_segment_bytes.argtypes = []
-    lib.pgcm_segment_bytes.restype = C.c_uint32
+    lib.pgcm_plan_units.argtypes = [sz, vp, vp, vp, vp, vp, vp]
+    lib.pgcm_plan_units.restype = C.c_int64
+    lib.pgcm_unit_bytes.argtypes = []
+    lib.pgcm_unit_bytes.restype = C.c_uint32
     lib.pgcm_set_timing.argtypes = [vp, C.c_int]
     lib.pgcm_set_timing.restype = C.c_int
     lib.pgcm_last_bulk_kernel_ms.argtypes = [vp, C.POINTER(C.c_float)]
@@ -164,18 +164,21 @@ def decrypt_verify_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, ok
         _addr(dst_a), _dev_ptr(tags), _dev_ptr(ok), _stream_handle(stream)))
 
 
-def plan_segments(length):
-    """pgcm_plan_segments -> (total work items, nseg, first_blocks, part_base); host only."""
+def plan_units(length):
+    """pgcm_plan_units -> dict(total, nunits, first_blocks, unit_base, final_count, final_power);
+    host only."""
     len_a = np.ascontiguousarray(length, dtype=np.uint64)
     n = len_a.size
-    nseg = np.zeros(n, np.uint32)
-    first = np.zeros(n, np.uint32)
-    base = np.zeros(n, np.uint32)
-    total = load_library().pgcm_plan_segments(n, _addr(len_a) if n else None, nseg.ctypes.data,
-                                              first.ctypes.data, base.ctypes.data)
+    out = {k: np.zeros(n, np.uint32) for k in ("nunits", "first_blocks", "unit_base",
+                                                "final_count", "final_power")}
+    total = load_library().pgcm_plan_units(n, _addr(len_a) if n else None,
+                                           *[out[k].ctypes.data for k in
+                                             ("nunits", "first_blocks", "unit_base", "final_count",
+                                              "final_power")])
     if total < 0:
         raise PgcmError(int(total))
-    return int(total), nseg, first, base
+    out["total"] = int(total)
+    return out
 
 
 def set_timing(key: Key, enable: bool):
@@ -190,5 +193,5 @@ def last_bulk_kernel_ms(key: Key) -> float:
     return float(ms.value)
 
 
-def segment_bytes() -> int:
-    return int(load_library().pgcm_segment_bytes())
+def unit_bytes() -> int:
+    return int(load_library().pgcm_unit_bytes())

@@ -29,20 +29,31 @@ inline bool hip_failed(hipError_t e) {
 
 constexpr int kStages = 2;
 
-// Per-chunk schedule: segments are counted back from the chunk's end, so that every segment but
-// the first is full and all row boundaries line up with the end of the chunk.
-struct SegPlan {
-    uint32_t nseg, first_blocks;
+// Per-chunk schedule: units are counted back from the chunk's end, so that every unit but the
+// first is full and all row boundaries line up with the end of the chunk.
+struct UnitPlan {
+    uint32_t nunits, first_blocks;
 };
 
-inline SegPlan plan_chunk(uint64_t len) {
+inline UnitPlan plan_chunk(uint64_t len) {
     uint64_t nblk = (len + 15) / 16;
-    SegPlan p{0, 0};
+    UnitPlan p{0, 0};
     if (nblk == 0) return p;
-    uint64_t nseg = (nblk + kSegBlocks - 1) / kSegBlocks;
-    p.nseg = (uint32_t)nseg;
-    p.first_blocks = (uint32_t)(nblk - (nseg - 1) * kSegBlocks);
+    uint64_t nunits = (nblk + kUnitBlocks - 1) / kUnitBlocks;
+    p.nunits = (uint32_t)nunits;
+    p.first_blocks = (uint32_t)(nblk - (nunits - 1) * kUnitBlocks);
     return p;
+}
+
+// Partial sets of a chunk are folded kFan at a time until at most kFan remain for the final
+// step.  Returns the number of fold levels and, per level, the number of sets it produces.
+inline uint32_t fold_levels(uint32_t nunits, uint32_t out_counts[kMaxLevels]) {
+    uint32_t levels = 0, c = nunits;
+    while (c > kFan) {
+        c = (c + kFan - 1) / kFan;
+        out_counts[levels++] = c;
+    }
+    return levels;
 }
 
 }  // namespace
@@ -58,9 +69,12 @@ struct pgcm_key {
     hipEvent_t stage_done[kStages] = {nullptr, nullptr};
     bool stage_used[kStages] = {false, false};
     int next_stage = 0;
-    // device workspace: descriptors, item map, per-segment partial hashes, per-chunk AAD states
+    // device workspace: descriptors, unit maps, fold lists, unit counter, per-chunk AAD states,
+    // partial sets
     uint8_t* work = nullptr;
     size_t work_cap = 0;
+    uint32_t* counter_at = nullptr;  // where the unit counter was last known to be zero
+    bool counter_dirty = true;
     // optional timing of the bulk kernel alone (pgcm_set_timing)
     bool timing = false;
     bool timed = false;
@@ -119,7 +133,8 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     if (n > 0x7FFFFFFFull) return PGCM_ERR_ARG;
 
     // validate everything before touching any state
-    uint64_t nitems64 = 0;
+    uint64_t nunits64 = 0, nslots64 = 0;
+    uint64_t fold_items64[kMaxLevels] = {0, 0, 0, 0};
     bool any_aad = false;
     for (size_t i = 0; i < n; ++i) {
         if (len[i] > PGCM_MAX_CHUNK_BYTES) return PGCM_ERR_LEN;
@@ -131,24 +146,43 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
             if (aad[i] == nullptr) return PGCM_ERR_ARG;
             any_aad = true;
         }
-        nitems64 += plan_chunk(len[i]).nseg;
+        const uint32_t nu = plan_chunk(len[i]).nunits;
+        uint32_t outs[kMaxLevels];
+        const uint32_t levels = fold_levels(nu, outs);
+        nunits64 += nu;
+        nslots64 += nu;
+        for (uint32_t l = 0; l < levels; ++l) {
+            fold_items64[l] += outs[l];
+            nslots64 += outs[l];
+        }
     }
-    if (nitems64 > 0xFFFFFFF0ull) return PGCM_ERR_ARG;
-    const uint32_t nitems = (uint32_t)nitems64;
+    if (nslots64 > 0xFFFFFFF0ull / 64) return PGCM_ERR_ARG;  // set indices are 32-bit
+    const uint32_t nunits = (uint32_t)nunits64;
+    const uint32_t nslots = (uint32_t)nslots64;
     const uint32_t nchunks = (uint32_t)n;
+    uint32_t fold_count[kMaxLevels], fold_first[kMaxLevels], nfold = 0;
+    for (uint32_t l = 0; l < kMaxLevels; ++l) {
+        fold_count[l] = (uint32_t)fold_items64[l];
+        fold_first[l] = nfold;
+        nfold += fold_count[l];
+    }
+    const uint32_t ncoarse = (nunits >> kCoarseShift) + 1;
 
     hipStream_t stream = (hipStream_t)hip_stream;
-    int prev_device = -1;
-    PGCM_HIP(hipGetDevice(&prev_device));
-    if (prev_device != key->device) return PGCM_ERR_ARG;  // the key lives on another GPU
+    int cur_device = -1;
+    PGCM_HIP(hipGetDevice(&cur_device));
+    if (cur_device != key->device) return PGCM_ERR_ARG;  // the key lives on another GPU
 
-    // workspace layout (device and staging share the first two regions)
+    // workspace layout; the regions up to upload_bytes are written by the host and uploaded
     const size_t off_desc = 0;
-    const size_t off_items = round_up(off_desc + sizeof(ChunkDesc) * n, 256);
-    const size_t upload_bytes = round_up(off_items + sizeof(uint32_t) * (size_t)nitems, 256);
-    const size_t off_partials = upload_bytes;
-    const size_t off_aad = round_up(off_partials + sizeof(Block) * (size_t)nitems, 256);
-    const size_t work_bytes = off_aad + sizeof(Block) * n;
+    const size_t off_ubase = round_up(off_desc + sizeof(ChunkDesc) * n, 256);
+    const size_t off_coarse = round_up(off_ubase + sizeof(uint32_t) * (n + 1), 256);
+    const size_t off_fold = round_up(off_coarse + sizeof(uint32_t) * (size_t)ncoarse, 256);
+    const size_t upload_bytes = round_up(off_fold + sizeof(FoldItem) * (size_t)nfold, 256);
+    const size_t off_counter = upload_bytes;
+    const size_t off_aad = off_counter + 256;
+    const size_t off_sets = round_up(off_aad + sizeof(Block) * n, 1024);
+    const size_t work_bytes = off_sets + sizeof(Block) * 64 * (size_t)nslots;
 
     const int s = key->next_stage;
     int rc = ensure_stage(key, s, upload_bytes);
@@ -157,21 +191,54 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     if (rc != PGCM_OK) return rc;
 
     ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(key->stage[s] + off_desc);
-    uint32_t* h_items = reinterpret_cast<uint32_t*>(key->stage[s] + off_items);
-    uint32_t item = 0;
+    uint32_t* h_ubase = reinterpret_cast<uint32_t*>(key->stage[s] + off_ubase);
+    uint32_t* h_coarse = reinterpret_cast<uint32_t*>(key->stage[s] + off_coarse);
+    FoldItem* h_fold = reinterpret_cast<FoldItem*>(key->stage[s] + off_fold);
+    uint32_t unit = 0, slot = nunits, coarse_next = 0;
+    uint32_t fold_fill[kMaxLevels] = {0, 0, 0, 0};
     for (size_t i = 0; i < n; ++i) {
-        SegPlan p = plan_chunk(len[i]);
+        const UnitPlan p = plan_chunk(len[i]);
         ChunkDesc& d = h_desc[i];
         d.src = (const uint8_t*)src[i];
         d.dst = (uint8_t*)dst[i];
         d.len = len[i];
         d.aad_len = aad_len ? aad_len[i] : 0;
         d.aad = d.aad_len ? (const uint8_t*)aad[i] : nullptr;
-        d.part_base = item;
-        d.nseg = p.nseg;
+        d.unit_base = unit;
+        d.nunits = p.nunits;
         d.first_blocks = p.first_blocks;
-        for (uint32_t k = 0; k < p.nseg; ++k) h_items[item++] = (uint32_t)i;
+        d.pad_ = 0;
+        h_ubase[i] = unit;
+        // coarse map: for every 2^kCoarseShift-th unit, the chunk that holds it
+        while (coarse_next < ncoarse && ((uint64_t)coarse_next << kCoarseShift) < (uint64_t)unit + p.nunits) {
+            h_coarse[coarse_next++] = (uint32_t)i;
+        }
+        // fold levels: groups of kFan sets counted back from the end, the first one short
+        uint32_t base = unit, count = p.nunits, power = kUnitPower, level = 0;
+        while (count > kFan) {
+            const uint32_t groups = (count + kFan - 1) / kFan;
+            const uint32_t first = count - (groups - 1) * kFan;
+            FoldItem* items = h_fold + fold_first[level] + fold_fill[level];
+            for (uint32_t g = 0; g < groups; ++g) {
+                items[g].in_base = base + (g == 0 ? 0 : first + (g - 1) * kFan);
+                items[g].in_count = g == 0 ? first : kFan;
+                items[g].out_slot = slot + g;
+                items[g].pad_ = 0;
+            }
+            fold_fill[level] += groups;
+            base = slot;
+            slot += groups;
+            count = groups;
+            power += kFanPower;
+            ++level;
+        }
+        d.final_base = base;
+        d.final_count = count;
+        d.final_power = power;
+        unit += p.nunits;
     }
+    h_ubase[n] = unit;
+    while (coarse_next < ncoarse) h_coarse[coarse_next++] = nchunks ? nchunks - 1 : 0;
 
     PGCM_HIP(hipMemcpyAsync(key->work, key->stage[s], upload_bytes, hipMemcpyHostToDevice, stream));
     PGCM_HIP(hipEventRecord(key->stage_done[s], stream));
@@ -179,40 +246,59 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     key->next_stage = (s + 1) % kStages;
 
     const ChunkDesc* d_desc = reinterpret_cast<const ChunkDesc*>(key->work + off_desc);
-    const uint32_t* d_items = reinterpret_cast<const uint32_t*>(key->work + off_items);
-    Block* d_partials = reinterpret_cast<Block*>(key->work + off_partials);
+    const uint32_t* d_ubase = reinterpret_cast<const uint32_t*>(key->work + off_ubase);
+    const uint32_t* d_coarse = reinterpret_cast<const uint32_t*>(key->work + off_coarse);
+    const FoldItem* d_fold = reinterpret_cast<const FoldItem*>(key->work + off_fold);
+    uint32_t* d_counter = reinterpret_cast<uint32_t*>(key->work + off_counter);
     Block* d_aad = any_aad ? reinterpret_cast<Block*>(key->work + off_aad) : nullptr;
+    Block* d_sets = reinterpret_cast<Block*>(key->work + off_sets);
+
+    // the unit counter is left at zero by the last kernel of every batch; it only needs clearing
+    // when the workspace is new (or has moved) or an earlier batch was cut short
+    if (key->counter_at != d_counter || key->counter_dirty) {
+        PGCM_HIP(hipMemsetAsync(d_counter, 0, sizeof(uint32_t), stream));
+        key->counter_at = d_counter;
+    }
+    key->counter_dirty = true;
 
     if (any_aad) {
         hipLaunchKernelGGL(aad_state_kernel, dim3((nchunks + 63) / 64), dim3(64), 0, stream,
                            key->tables, d_desc, nchunks, d_aad);
     }
-    if (nitems > 0) {
-        uint32_t groups = (nitems + kWavesPerGroup - 1) / kWavesPerGroup;
+    if (nunits > 0) {
+        uint32_t groups = (nunits + kWavesPerGroup - 1) / kWavesPerGroup;
         if (groups > (uint32_t)key->num_cu) groups = (uint32_t)key->num_cu;
         if (key->timing) PGCM_HIP(hipEventRecord(key->bulk_start, stream));
         if (decrypt)
             hipLaunchKernelGGL(bulk_kernel<true>, dim3(groups), dim3(kGroupThreads), 0, stream,
-                               key->tables, d_desc, d_items, nitems, ivs, d_aad, d_partials);
+                               key->tables, d_desc, d_ubase, d_coarse, nunits, d_counter, ivs,
+                               d_aad, d_sets);
         else
             hipLaunchKernelGGL(bulk_kernel<false>, dim3(groups), dim3(kGroupThreads), 0, stream,
-                               key->tables, d_desc, d_items, nitems, ivs, d_aad, d_partials);
+                               key->tables, d_desc, d_ubase, d_coarse, nunits, d_counter, ivs,
+                               d_aad, d_sets);
         if (key->timing) {
             PGCM_HIP(hipEventRecord(key->bulk_stop, stream));
             key->timed = true;
         }
     }
+    for (uint32_t l = 0; l < kMaxLevels; ++l) {
+        if (fold_count[l] == 0) continue;
+        hipLaunchKernelGGL(fold_kernel, dim3(fold_count[l]), dim3(64), 0, stream, key->tables,
+                           d_fold + fold_first[l], kUnitPower + kFanPower * l, d_sets);
+    }
     if (decrypt) {
-        hipLaunchKernelGGL(finalize_kernel<true>, dim3((nchunks + 63) / 64), dim3(64), 0, stream,
-                           key->tables, d_desc, nchunks, ivs, d_aad, d_partials, tags, ok);
+        hipLaunchKernelGGL(final_kernel<true>, dim3(nchunks), dim3(64), 0, stream, key->tables,
+                           d_desc, ivs, d_aad, d_sets, tags, ok, d_counter);
         uint32_t wipers = nchunks < 1024 ? nchunks : 1024;
         hipLaunchKernelGGL(wipe_rejected_kernel, dim3(wipers), dim3(256), 0, stream, d_desc,
                            nchunks, ok);
     } else {
-        hipLaunchKernelGGL(finalize_kernel<false>, dim3((nchunks + 63) / 64), dim3(64), 0, stream,
-                           key->tables, d_desc, nchunks, ivs, d_aad, d_partials, tags, nullptr);
+        hipLaunchKernelGGL(final_kernel<false>, dim3(nchunks), dim3(64), 0, stream, key->tables,
+                           d_desc, ivs, d_aad, d_sets, tags, nullptr, d_counter);
     }
     PGCM_HIP(hipGetLastError());
+    key->counter_dirty = false;
     return PGCM_OK;
 }
 
@@ -302,23 +388,27 @@ const char* pgcm_strerror(int status) {
 
 int pgcm_last_hip_error(void) { return g_last_hip_error; }
 
-int64_t pgcm_plan_segments(size_t n, const uint64_t* len, uint32_t* nseg, uint32_t* first_blocks,
-                           uint32_t* part_base) {
+int64_t pgcm_plan_units(size_t n, const uint64_t* len, uint32_t* nunits, uint32_t* first_blocks,
+                        uint32_t* unit_base, uint32_t* final_count, uint32_t* final_power) {
     if (n != 0 && len == nullptr) return PGCM_ERR_ARG;
     uint64_t total = 0;
     for (size_t i = 0; i < n; ++i) {
         if (len[i] > PGCM_MAX_CHUNK_BYTES) return PGCM_ERR_LEN;
-        SegPlan p = plan_chunk(len[i]);
-        if (nseg) nseg[i] = p.nseg;
+        UnitPlan p = plan_chunk(len[i]);
+        uint32_t outs[kMaxLevels];
+        const uint32_t levels = fold_levels(p.nunits, outs);
+        if (nunits) nunits[i] = p.nunits;
         if (first_blocks) first_blocks[i] = p.first_blocks;
-        if (part_base) part_base[i] = (uint32_t)total;
-        total += p.nseg;
-        if (total > 0xFFFFFFF0ull) return PGCM_ERR_ARG;
+        if (unit_base) unit_base[i] = (uint32_t)total;
+        if (final_count) final_count[i] = levels ? outs[levels - 1] : p.nunits;
+        if (final_power) final_power[i] = kUnitPower + kFanPower * levels;
+        total += p.nunits;
+        if (total > 0xFFFFFFF0ull / 64) return PGCM_ERR_ARG;
     }
     return (int64_t)total;
 }
 
-uint32_t pgcm_segment_bytes(void) { return kSegBytes; }
+uint32_t pgcm_unit_bytes(void) { return kUnitBytes; }
 
 int pgcm_set_timing(pgcm_key_t* key, int enable) {
     if (key == nullptr) return PGCM_ERR_ARG;

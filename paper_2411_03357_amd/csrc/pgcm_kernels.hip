@@ -277,6 +277,11 @@ __device__ __forceinline__ void global_write128(uint8_t* p, u32x4 v) {
     *reinterpret_cast<global_u128_ptr>(reinterpret_cast<uintptr_t>(p)) = v;
 }
 
+// LDS byte address of a __shared__ object
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
 __device__ __forceinline__ uint32_t lds_read32(uint32_t addr) {
     return *reinterpret_cast<lds_u32_ptr>(addr);
 }
@@ -401,6 +406,9 @@ struct GhashRowMul {
         z1 ^= ra.y ^ rb.y;
         z2 ^= ra.z ^ rb.z;
         z3 ^= ra.w ^ rb.w;
+        // pin the running sums here: otherwise the optimizer moves the whole XOR chain to where
+        // its result is used and keeps all thirty-two table entries alive until then
+        asm volatile("" : "+v"(z0), "+v"(z1), "+v"(z2), "+v"(z3));
     }
     template <int S>
     __device__ __forceinline__ void step() {
@@ -428,6 +436,7 @@ __device__ __forceinline__ void aes256_ctr_lds(const uint32_t* __restrict__ rk, 
     G.consume();
     G.step<1>();
     G.step<2>();
+    __builtin_amdgcn_sched_barrier(0);
     static_for<2, 15>([&](auto round) __attribute__((always_inline)) {
         constexpr int r = decltype(round)::value;
         const uint32_t* k = rk + 4 * (r - 1);
@@ -476,38 +485,68 @@ __device__ __forceinline__ void aes256_ctr_lds(const uint32_t* __restrict__ rk, 
             o3 = last(t30, t01, t12, t23, rk[59]);
         }
         G.consume();
+        // keep every round's hash step with its round: without this the compiler sinks the
+        // hash XORs to the end of the block and spills the table entries they wait for
+        __builtin_amdgcn_sched_barrier(0);
     });
 }
 
-// One row of a segment: block `blk` of the chunk in this lane (if `active`).
-// kEdge rows may have idle lanes, the chunk's ragged last block and the AAD state to fold in;
-// interior rows are full and take the short path.
-template <bool kDecrypt, bool kEdge>
+// Y * C from C's nibble table at LDS address `base` (not interleaved with anything)
+__device__ __forceinline__ void ghash_mul_lds(uint32_t base, uint32_t y[4]) {
+    GhashRowMul G;
+    G.w[0] = y[0], G.w[1] = y[1], G.w[2] = y[2], G.w[3] = y[3];
+    static_for<0, 16>([&](auto step) __attribute__((always_inline)) {
+        constexpr int S = decltype(step)::value;
+        constexpr int i = S / 4, k = S % 4;
+        const uint32_t f0 = 0xF0u;
+        if constexpr (k == 0) G.t = G.w[i] << 4;
+        G.ra = lds_read128(base + nibble_offset<k>(G.w[i], f0) + 2 * S * 256);
+        G.rb = lds_read128(base + nibble_offset<k>(G.t, f0) + (2 * S + 1) * 256);
+        G.consume();
+    });
+    y[0] = G.z0, y[1] = G.z1, y[2] = G.z2, y[3] = G.z3;
+}
+
+// One row of a unit: block `blk` of the chunk in this lane.  On `edge` rows (the first and the
+// last row of a chunk; a wave-uniform flag) some lanes may lie before the chunk's start and stay
+// idle, the last lane may hold the chunk's ragged last block, and the lane of block 0 folds in
+// the AAD state.  One code path serves both kinds: idle lanes run the cipher on a dummy counter,
+// touch no memory and keep a zero hash state.
+template <bool kDecrypt>
 __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAddr& A,
-                                         const CtrConsts& C, const ChunkDesc& cd, int64_t blk,
-                                         int64_t first_blk, const Block* __restrict__ aad_state,
-                                         uint32_t chunk, uint32_t y[4]) {
+                                         const CtrConsts& C, const uint8_t* src, uint8_t* dst,
+                                         uint64_t len, int64_t blk, bool edge,
+                                         const Block* __restrict__ aad_state, uint32_t chunk,
+                                         uint32_t y[4]) {
     bool active = true;
     uint32_t tail = 0;  // bytes in a ragged block, 0 = whole block
-    if (kEdge) {
-        active = blk >= first_blk;
-        if (active && (uint64_t)blk * 16 + 16 > cd.len) tail = (uint32_t)(cd.len & 15);
+    if (edge) {
+        active = blk >= 0;
+        if (active && (uint64_t)blk * 16 + 16 > len) tail = (uint32_t)(len & 15);
     }
-    if (!active) return;
+    const bool whole = active && tail == 0;
 
-    uint32_t x0, x1, x2, x3;
-    const uint8_t* sp = cd.src + (uint64_t)blk * 16;
-    uint8_t* dp = cd.dst + (uint64_t)blk * 16;
-    if (kEdge && tail) {
-        uint32_t t[4] = {0, 0, 0, 0};
-        for (uint32_t b = 0; b < tail; ++b) t[b / 4] |= (uint32_t)sp[b] << (8 * (b % 4));
-        x0 = t[0], x1 = t[1], x2 = t[2], x3 = t[3];
-    } else {
+    uint32_t x0 = 0, x1 = 0, x2 = 0, x3 = 0;
+    const uint8_t* sp = src + blk * 16;
+    uint8_t* dp = dst + blk * 16;
+    if (whole) {
         u32x4 v = global_read128(sp);
         x0 = v.x, x1 = v.y, x2 = v.z, x3 = v.w;
     }
+    if (edge && tail) {
+#pragma unroll
+        for (uint32_t b = 0; b < 15; ++b) {
+            if (b < tail) {
+                const uint32_t v = (uint32_t)sp[b] << (8 * (b % 4));
+                if (b / 4 == 0) x0 |= v;
+                if (b / 4 == 1) x1 |= v;
+                if (b / 4 == 2) x2 |= v;
+                if (b / 4 == 3) x3 |= v;
+            }
+        }
+    }
 
-    // counter block IV || be32(blk + 2) (SP 800-38D 7.1 step 3 with J0 = IV || 0^31 1)
+    // counter block IV || be32(blk + 2) (SP 800-38D 7.1 step 3 with J0 = IV || 0^31 1) ...
     // ... while the hash state moves one row along: Y <- Y * H^64
     GhashRowMul G;
     G.w[0] = y[0], G.w[1] = y[1], G.w[2] = y[2], G.w[3] = y[3];
@@ -515,37 +554,57 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
     aes256_ctr_lds(rk, A, C, (uint32_t)blk + 2u, G, s0, s1, s2, s3);
     uint32_t o0 = x0 ^ s0, o1 = x1 ^ s1, o2 = x2 ^ s2, o3 = x3 ^ s3;
 
-    if (kEdge && tail) {
-        uint32_t o[4] = {o0, o1, o2, o3};
-        for (uint32_t b = 0; b < tail; ++b) dp[b] = (uint8_t)(o[b / 4] >> (8 * (b % 4)));
-        // bytes past the end count as zero in the hash
-        for (uint32_t b = tail; b < 16; ++b) o[b / 4] &= ~(0xFFu << (8 * (b % 4)));
-        o0 = o[0], o1 = o[1], o2 = o[2], o3 = o[3];
-    } else {
+    if (whole) {
         u32x4 o = {o0, o1, o2, o3};
         global_write128(dp, o);
+    }
+    if (edge && tail) {
+#pragma unroll
+        for (uint32_t b = 0; b < 15; ++b) {
+            if (b < tail) {
+                const uint32_t w = b / 4 == 0 ? o0 : b / 4 == 1 ? o1 : b / 4 == 2 ? o2 : o3;
+                dp[b] = (uint8_t)(w >> (8 * (b % 4)));
+            }
+        }
+        // bytes past the end count as zero in the hash
+        const uint32_t keep = tail % 4 ? (1u << (8 * (tail % 4))) - 1u : 0u;  // in the partial word
+        const uint32_t q = tail / 4;
+        o0 = q > 0 ? o0 : (q == 0 ? o0 & keep : 0u);
+        o1 = q > 1 ? o1 : (q == 1 ? o1 & keep : 0u);
+        o2 = q > 2 ? o2 : (q == 2 ? o2 & keep : 0u);
+        o3 = q == 3 ? o3 & keep : 0u;
     }
 
     // the ciphertext is what gets hashed: the output when encrypting, the input when decrypting
     uint32_t c0 = kDecrypt ? x0 : o0, c1 = kDecrypt ? x1 : o1, c2 = kDecrypt ? x2 : o2,
              c3 = kDecrypt ? x3 : o3;
-    if (kEdge && blk == 0 && aad_state != nullptr) {
-        const Block a = aad_state[chunk];
-        c0 ^= a.w[0], c1 ^= a.w[1], c2 ^= a.w[2], c3 ^= a.w[3];
+    if (edge) {
+        if (blk == 0 && aad_state != nullptr) {
+            // GHASH continues from the state the AAD left: same as adding it to the first block
+            const Block a = aad_state[chunk];
+            c0 ^= a.w[0], c1 ^= a.w[1], c2 ^= a.w[2], c3 ^= a.w[3];
+        }
+        if (!active) c0 = c1 = c2 = c3 = 0;  // idle lanes only occur in a chunk's first row: Y = 0
     }
     y[0] = G.z0 ^ c0, y[1] = G.z1 ^ c1, y[2] = G.z2 ^ c2, y[3] = G.z3 ^ c3;
 }
 
 }  // namespace
 
-// item_chunk[i] = chunk of work item i; partials[i] receives the segment's GHASH contribution
-//   P = sum over its blocks C_b * H^(blocks from b to the segment's end, inclusive).
+// The schedule: wavefronts take units from `counter` until none is left.  Unit i belongs to the
+// chunk c with unit_base[c] <= i < unit_base[c + 1] (unit_base has one entry more than there are
+// chunks); coarse_map[i >> kCoarseShift] is a chunk at or before the right one.
+// sets[i * 64 + lane] receives lane's GHASH sum over the unit's rows:
+//   sum over rows r of C(r, lane) * (H^64)^(rows after r).
 template <bool kDecrypt>
 __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks,
-    const uint32_t* __restrict__ item_chunk, uint32_t nitems, const uint8_t* __restrict__ ivs,
-    const Block* __restrict__ aad_state, Block* __restrict__ partials) {
+    const uint32_t* __restrict__ unit_base, const uint32_t* __restrict__ coarse_map,
+    uint32_t nunits_total, uint32_t* __restrict__ counter, const uint8_t* __restrict__ ivs,
+    const Block* __restrict__ aad_state, Block* __restrict__ sets) {
     __shared__ BulkLds lds;
+    // lookup addresses are formed as raw LDS addresses that assume this object starts at 0
+    if (lds_offset(&lds) != 0) return;
 
     const uint32_t tid = threadIdx.x;
     // fill: 32 copies of every table entry, lane-interleaved
@@ -558,7 +617,6 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     __syncthreads();
 
     const uint32_t lane = tid & 63;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     AesAddr A;
     aes_addr_init(A, lane);
     // the round keys stay in scalar registers for the whole kernel
@@ -566,14 +624,24 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
 #pragma unroll
     for (int i = 0; i < 60; ++i) rk[i] = kt->rk[i];
 
-    for (uint32_t item = blockIdx.x * kWavesPerGroup + wave; item < nitems;
-         item += gridDim.x * kWavesPerGroup) {
-        const uint32_t chunk = item_chunk[item];
-        const ChunkDesc cd = chunks[chunk];
-        const uint32_t seg = item - cd.part_base;
-        // segment bounds in blocks of the chunk
-        const int64_t b0 = seg == 0 ? 0 : (int64_t)cd.first_blocks + (int64_t)(seg - 1) * kSegBlocks;
-        const int64_t b1 = seg == 0 ? (int64_t)cd.first_blocks : b0 + kSegBlocks;
+    for (;;) {
+        uint32_t item = 0;
+        if (lane == 0)
+            item = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        item = __builtin_amdgcn_readfirstlane(item);
+        if (item >= nunits_total) break;  // every wavefront gets here: the counter only grows
+
+        uint32_t chunk = coarse_map[item >> kCoarseShift];
+        while (unit_base[chunk + 1] <= item) ++chunk;  // ends: unit_base[nchunks] > item
+        const ChunkDesc* __restrict__ cd = chunks + chunk;
+        const uint8_t* src = cd->src;
+        uint8_t* dst = cd->dst;
+        const uint64_t len = cd->len;
+        const uint32_t unit = item - cd->unit_base, nunits = cd->nunits;
+        const uint32_t first_blocks = cd->first_blocks;
+        // the unit's blocks [b0, b1) of the chunk
+        const int64_t b0 = unit == 0 ? 0 : (int64_t)first_blocks + (int64_t)(unit - 1) * kUnitBlocks;
+        const int64_t b1 = unit == 0 ? (int64_t)first_blocks : b0 + kUnitBlocks;
         const uint32_t nrows = (uint32_t)((b1 - b0 + kRowBlocks - 1) / kRowBlocks);
 
         const uint8_t* ivp = ivs + (uint64_t)chunk * 12;
@@ -581,24 +649,94 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
         for (int i = 0; i < 3; ++i)
             iv[i] = (uint32_t)ivp[4 * i] | ((uint32_t)ivp[4 * i + 1] << 8) |
                     ((uint32_t)ivp[4 * i + 2] << 16) | ((uint32_t)ivp[4 * i + 3] << 24);
-
         const CtrConsts C = ctr_consts(rk, lane, iv[0], iv[1], iv[2]);
 
         uint32_t y[4] = {0, 0, 0, 0};
-        // rows are aligned to the segment's end; the first may start with idle lanes
+        // rows are aligned to the unit's end; only the chunk's very first row can start with idle
+        // lanes (block index below 0), only its very last row can hold a ragged block
         int64_t blk = b1 - (int64_t)nrows * kRowBlocks + lane;
-        bulk_row<kDecrypt, true>(rk, A, C, cd, blk, b0, aad_state, chunk, y);
-        for (uint32_t r = 1; r + 1 < nrows; ++r) {
-            blk += kRowBlocks;
-            bulk_row<kDecrypt, false>(rk, A, C, cd, blk, b0, aad_state, chunk, y);
+        for (uint32_t r = 0; r < nrows; ++r, blk += kRowBlocks) {
+            const bool edge = (unit == 0 && r == 0) || (unit + 1 == nunits && r + 1 == nrows);
+            bulk_row<kDecrypt>(rk, A, C, src, dst, len, blk, edge, aad_state, chunk, y);
         }
-        if (nrows > 1) {
-            blk += kRowBlocks;
-            bulk_row<kDecrypt, true>(rk, A, C, cd, blk, b0, aad_state, chunk, y);
-        }
+        sets[(uint64_t)item * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
+    }
+}
 
-        // lanes -> one value: lane j's sum still lacks H^(63 - j); fold halves, then one more H
-        Block acc{{y[0], y[1], y[2], y[3]}};
+template __global__ void bulk_kernel<false>(const KeyTables*, const ChunkDesc*, const uint32_t*,
+                                            const uint32_t*, uint32_t, uint32_t*, const uint8_t*,
+                                            const Block*, Block*);
+template __global__ void bulk_kernel<true>(const KeyTables*, const ChunkDesc*, const uint32_t*,
+                                           const uint32_t*, uint32_t, uint32_t*, const uint8_t*,
+                                           const Block*, Block*);
+
+// ------------------------------------------------------------------------------------------
+// Folding partial sets.  Consecutive sets of a chunk lie 2^power blocks apart, so, lane by lane,
+//   folded = (..(set_0 * G + set_1) * G + ..) + set_last   with G = H^(2^power).
+namespace {
+
+// one wavefront: copies the nibble table of H^(2^power) into LDS
+__device__ __forceinline__ void load_power_table(Block* lds_table, const KeyTables* __restrict__ kt,
+                                                 uint32_t power, uint32_t lane) {
+    for (uint32_t i = lane; i < kNibbleTableEntries; i += 64) lds_table[i] = kt->ghash[power][i];
+    __syncthreads();
+}
+
+__device__ __forceinline__ void fold_sets(const Block* __restrict__ sets, uint32_t base,
+                                          uint32_t count, uint32_t lane, uint32_t table_addr,
+                                          uint32_t y[4]) {
+    Block first = sets[(uint64_t)base * 64 + lane];
+    y[0] = first.w[0], y[1] = first.w[1], y[2] = first.w[2], y[3] = first.w[3];
+    for (uint32_t s = 1; s < count; ++s) {
+        const Block next = sets[(uint64_t)(base + s) * 64 + lane];
+        ghash_mul_lds(table_addr, y);
+        y[0] ^= next.w[0], y[1] ^= next.w[1], y[2] ^= next.w[2], y[3] ^= next.w[3];
+    }
+}
+
+}  // namespace
+
+// One wavefront (= one workgroup) per fold item of one level.
+__global__ __launch_bounds__(64) void fold_kernel(const KeyTables* __restrict__ kt,
+                                                  const FoldItem* __restrict__ items,
+                                                  uint32_t power, Block* __restrict__ sets) {
+    __shared__ Block table[kNibbleTableEntries];
+    const uint32_t lane = threadIdx.x;
+    const FoldItem it = items[blockIdx.x];
+    load_power_table(table, kt, power, lane);
+    uint32_t y[4];
+    fold_sets(sets, it.in_base, it.in_count, lane, lds_offset(table), y);
+    sets[(uint64_t)it.out_slot * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
+}
+
+// Per chunk (one wavefront each): fold the remaining sets, fold the 64 lanes, add the length
+// block, mask with E_K(J0) (SP 800-38D 7.1 steps 5-6); then write the tag, or compare it and write
+// the verdict (7.2).  The last workgroup's duty of clearing `counter` readies the next batch.
+template <bool kDecrypt>
+__global__ __launch_bounds__(64) void final_kernel(const KeyTables* __restrict__ kt,
+                                                   const ChunkDesc* __restrict__ chunks,
+                                                   const uint8_t* __restrict__ ivs,
+                                                   const Block* __restrict__ aad_state,
+                                                   const Block* __restrict__ sets,
+                                                   uint8_t* __restrict__ tags,
+                                                   uint8_t* __restrict__ ok,
+                                                   uint32_t* __restrict__ counter) {
+    __shared__ Block table[kNibbleTableEntries];
+    const uint32_t lane = threadIdx.x;
+    const uint32_t i = blockIdx.x;
+    if (i == 0 && lane == 0) *counter = 0;
+    const ChunkDesc cd = chunks[i];
+
+    Block acc{{0, 0, 0, 0}};
+    if (cd.final_count == 0) {
+        // no ciphertext: the hash state is what the AAD left
+        if (aad_state != nullptr) acc = aad_state[i];
+    } else {
+        if (cd.final_count > 1) load_power_table(table, kt, cd.final_power, lane);
+        uint32_t y[4];
+        fold_sets(sets, cd.final_base, cd.final_count, lane, lds_offset(table), y);
+        // lanes -> one value: lane j's sum still lacks H^(64 - j): fold halves, then one more H
+        acc = Block{{y[0], y[1], y[2], y[3]}};
 #pragma unroll 1
         for (int k = 5; k >= 0; --k) {
             Block m = gf_mul_table(kt->ghash[k], acc);
@@ -609,39 +747,10 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
             m.w[3] ^= __shfl_down(acc.w[3], s, 64);
             acc = m;
         }
-        if (lane == 0) partials[item] = gf_mul_table(kt->ghash[0], acc);
+        acc = gf_mul_table(kt->ghash[0], acc);
     }
-}
+    if (lane != 0) return;
 
-template __global__ void bulk_kernel<false>(const KeyTables*, const ChunkDesc*, const uint32_t*,
-                                            uint32_t, const uint8_t*, const Block*, Block*);
-template __global__ void bulk_kernel<true>(const KeyTables*, const ChunkDesc*, const uint32_t*,
-                                           uint32_t, const uint8_t*, const Block*, Block*);
-
-// ------------------------------------------------------------------------------------------
-// Per chunk: combine segment contributions, add the length block, mask with E_K(J0)
-// (SP 800-38D 7.1 steps 5-6); then write the tag, or compare it and write the verdict (7.2).
-template <bool kDecrypt>
-__global__ __launch_bounds__(64) void finalize_kernel(const KeyTables* __restrict__ kt,
-                                const ChunkDesc* __restrict__ chunks, uint32_t n,
-                                const uint8_t* __restrict__ ivs,
-                                const Block* __restrict__ aad_state,
-                                const Block* __restrict__ partials, uint8_t* __restrict__ tags,
-                                uint8_t* __restrict__ ok) {
-    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const ChunkDesc cd = chunks[i];
-    Block acc{{0, 0, 0, 0}};
-    if (cd.nseg == 0) {
-        if (aad_state != nullptr) acc = aad_state[i];
-    } else {
-        // every segment after the first is full, so each step moves the sum kSegBlocks further
-        acc = partials[cd.part_base];
-        for (uint32_t s = 1; s < cd.nseg; ++s) {
-            acc = gf_mul_table(kt->ghash[kSegPower], acc);
-            block_xor(acc, partials[cd.part_base + s]);
-        }
-    }
     // [8 |A|]_64 || [8 |C|]_64, big endian
     uint64_t abits = (uint64_t)cd.aad_len * 8, cbits = cd.len * 8;
     Block lens{{bswap32((uint32_t)(abits >> 32)), bswap32((uint32_t)abits),
@@ -669,12 +778,12 @@ __global__ __launch_bounds__(64) void finalize_kernel(const KeyTables* __restric
     }
 }
 
-template __global__ void finalize_kernel<false>(const KeyTables*, const ChunkDesc*, uint32_t,
-                                                const uint8_t*, const Block*, const Block*,
-                                                uint8_t*, uint8_t*);
-template __global__ void finalize_kernel<true>(const KeyTables*, const ChunkDesc*, uint32_t,
-                                               const uint8_t*, const Block*, const Block*,
-                                               uint8_t*, uint8_t*);
+template __global__ void final_kernel<false>(const KeyTables*, const ChunkDesc*, const uint8_t*,
+                                             const Block*, const Block*, uint8_t*, uint8_t*,
+                                             uint32_t*);
+template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, const uint8_t*,
+                                            const Block*, const Block*, uint8_t*, uint8_t*,
+                                            uint32_t*);
 
 // Overwrites the output of every rejected chunk with zeros; one workgroup walks chunks.
 __global__ __launch_bounds__(256) void wipe_rejected_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n,

@@ -5,22 +5,30 @@
 namespace pgcm {
 
 // A wavefront handles 64 consecutive 16-byte blocks (one 1 KiB "row") per step, one block per
-// lane.  A segment is the unit of scheduling: one wavefront walks it row by row.
+// lane.  A unit is the piece of a chunk one wavefront walks in one go, and the granule of the
+// dynamic schedule; units are counted back from the chunk's end, so only a chunk's first unit
+// can be short.
 constexpr uint32_t kRowBlocks = 64;
-constexpr uint32_t kSegBlocks = 4096;  // 64 KiB
-constexpr uint32_t kSegBytes = kSegBlocks * 16;
+constexpr uint32_t kRowPower = 6;      // H^64: one row further along a lane's stripe
+constexpr uint32_t kUnitPower = 10;    // 1024 blocks = 16 KiB per unit
+constexpr uint32_t kUnitBlocks = 1u << kUnitPower;
+constexpr uint32_t kUnitBytes = kUnitBlocks * 16;
 constexpr uint32_t kWavesPerGroup = 16;
 constexpr uint32_t kGroupThreads = kWavesPerGroup * 64;
+static_assert((1u << kRowPower) == kRowBlocks, "row power");
+
+// Every unit leaves a "partial set": the 64 per-lane GHASH sums of its rows (1 KiB).  Sets of one
+// chunk are folded 32 at a time (again counted back from the end), level by level, until at most
+// 32 remain; the per-chunk final step folds those and the 64 lanes.
+constexpr uint32_t kFanPower = 5;
+constexpr uint32_t kFan = 1u << kFanPower;
+constexpr uint32_t kMaxLevels = 4;     // 2^22 units (the GCM length limit) / 32^4 <= 32
 
 // GHASH tables hold, for one constant C = H^(2^k), the products of C with every value of every
 // nibble position of a block: entry [2 * byte + (0: high nibble, 1: low nibble)][value], 16 bytes
 // each, 8 KiB per constant.
 constexpr uint32_t kNibbleTableEntries = 32 * 16;
-constexpr uint32_t kNumPowers = 19;   // H^(2^0) .. H^(2^18)
-constexpr uint32_t kRowPower = 6;     // H^64: one row further along a lane's stripe
-constexpr uint32_t kSegPower = 12;    // H^4096: one full segment further along a chunk
-static_assert((1u << kRowPower) == kRowBlocks, "row power");
-static_assert((1u << kSegPower) == kSegBlocks, "segment power");
+constexpr uint32_t kNumPowers = kUnitPower + kFanPower * kMaxLevels + 1;  // H^(2^0) .. H^(2^30)
 
 struct alignas(16) Block {
     uint32_t w[4];  // bytes 4i..4i+3 of the block, loaded little-endian into w[i]
@@ -34,15 +42,32 @@ struct alignas(16) KeyTables {
     Block ghash[kNumPowers][kNibbleTableEntries];
 };
 
-struct ChunkDesc {
+struct alignas(16) ChunkDesc {
     const uint8_t* src;
     uint8_t* dst;
     const uint8_t* aad;
     uint64_t len;
     uint32_t aad_len;
-    uint32_t part_base;     // index of this chunk's first segment among all work items
-    uint32_t nseg;          // number of segments (0 for an empty chunk)
-    uint32_t first_blocks;  // blocks in segment 0; every later segment has kSegBlocks
+    uint32_t unit_base;     // index of this chunk's first unit among all units = its set slot
+    uint32_t nunits;        // 0 for an empty chunk
+    uint32_t first_blocks;  // blocks in unit 0; every later unit has kUnitBlocks
+    uint32_t final_base;    // first set slot the final step folds
+    uint32_t final_count;   // number of sets it folds: 1..32, or 0 for an empty chunk
+    uint32_t final_power;   // log2 of the distance, in blocks, between consecutive such sets
+    uint32_t pad_;
 };
+static_assert(sizeof(ChunkDesc) == 64, "descriptor layout");
+
+// One fold of up to 32 consecutive sets of a chunk into one set of the next level.
+struct alignas(16) FoldItem {
+    uint32_t in_base;   // first input slot
+    uint32_t in_count;  // 1..32
+    uint32_t out_slot;
+    uint32_t pad_;
+};
+
+// Items of the dynamic schedule are grabbed from a counter; to find an item's chunk a wavefront
+// starts at coarse_map[item >> kCoarseShift] and walks unit_base[] forward.
+constexpr uint32_t kCoarseShift = 4;
 
 }  // namespace pgcm

@@ -15,8 +15,14 @@ class DeviceBatch:
         self.w = w
         self.device = device
         self.plain = plain
-        self.cipher = torch.empty_like(plain)
-        self.back = torch.empty_like(plain)
+        # bytes between chunks (alignment padding) are zero in all three buffers, so that whole
+        # buffers can be compared
+        ends = (w.offsets + w.lens).astype(np.int64)
+        nxt = np.append(w.offsets[1:].astype(np.int64), w.total_bytes) if w.n else ends
+        for i in np.flatnonzero(nxt > ends):
+            plain[int(ends[i]):int(nxt[i])] = 0
+        self.cipher = torch.zeros_like(plain)
+        self.back = torch.zeros_like(plain)
         self.ivs = torch.from_numpy(w.ivs.reshape(-1).copy()).to(device)
         self.tags = torch.zeros(16 * w.n, dtype=torch.uint8, device=device)
         self.ok = torch.full((w.n,), 0x55, dtype=torch.uint8, device=device)

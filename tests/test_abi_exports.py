@@ -40,28 +40,37 @@ def test_strerror_and_null_arguments_without_gpu():
     assert lib.pgcm_last_hip_error() == 0
 
 
-def test_segment_plan():
-    seg = pgcm.segment_bytes()
-    assert seg % 1024 == 0 and seg >= 1024
-    sb = seg // 16
-    lens = [0, 1, 15, 16, 17, seg - 1, seg, seg + 1, 3 * seg, 3 * seg + 16 * 7 + 3, 8 << 20]
-    total, nseg, first, base = pgcm.plan_segments(lens)
+def test_unit_plan():
+    unit = pgcm.unit_bytes()
+    assert unit % 1024 == 0 and unit >= 1024
+    ub = unit // 16
+    lens = [0, 1, 15, 16, 17, unit - 1, unit, unit + 1, 3 * unit, 3 * unit + 16 * 7 + 3,
+            32 * unit, 32 * unit + 1, 33 * unit, 1024 * unit, 1024 * unit + 5, 1025 * unit,
+            (1 << 36) - 32]
+    p = pgcm.plan_units(lens)
     run = 0
-    for ln, ns, fb, pb in zip(lens, nseg, first, base):
+    for i, ln in enumerate(lens):
         nblk = (ln + 15) // 16
-        assert ns == (nblk + sb - 1) // sb
-        assert pb == run
-        run += ns
+        nu, fb = int(p["nunits"][i]), int(p["first_blocks"][i])
+        assert nu == (nblk + ub - 1) // ub
+        assert int(p["unit_base"][i]) == run
+        run += nu
         if nblk == 0:
-            assert (ns, fb) == (0, 0)
+            assert (nu, fb) == (0, 0) and int(p["final_count"][i]) == 0
         else:
-            # only the first segment may be short, and never empty
-            assert 1 <= fb <= sb and fb + (ns - 1) * sb == nblk
-    assert total == run
+            # only the first unit may be short, and never empty
+            assert 1 <= fb <= ub and fb + (nu - 1) * ub == nblk
+        # folding 32 sets at a time leaves 1..32 sets, spaced unit * 32^levels blocks apart
+        c, levels = nu, 0
+        while c > 32:
+            c, levels = (c + 31) // 32, levels + 1
+        assert int(p["final_count"][i]) == c and levels <= 4
+        assert int(p["final_power"][i]) == (ub.bit_length() - 1) + 5 * levels
+    assert p["total"] == run
     with pytest.raises(pgcm.PgcmError) as e:
-        pgcm.plan_segments([1 << 36])
+        pgcm.plan_units([1 << 36])
     assert e.value.status == -3
-    assert pgcm.plan_segments([])[0] == 0
+    assert pgcm.plan_units([])["total"] == 0
 
 
 def test_workload_generators_are_seeded_and_shaped():
