@@ -69,7 +69,7 @@ struct pgcm_key {
     hipEvent_t stage_done[kStages] = {nullptr, nullptr};
     bool stage_used[kStages] = {false, false};
     int next_stage = 0;
-    // device workspace: descriptors, unit maps, fold lists, unit counter, per-chunk AAD states,
+    // device workspace: descriptors, unit maps, fold lists, unit counter, per-chunk E_K(J0),
     // partial sets
     uint8_t* work = nullptr;
     size_t work_cap = 0;
@@ -135,17 +135,13 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     // validate everything before touching any state
     uint64_t nunits64 = 0, nslots64 = 0;
     uint64_t fold_items64[kMaxLevels] = {0, 0, 0, 0};
-    bool any_aad = false;
     for (size_t i = 0; i < n; ++i) {
         if (len[i] > PGCM_MAX_CHUNK_BYTES) return PGCM_ERR_LEN;
         if (len[i] != 0) {
             if (src[i] == nullptr || dst[i] == nullptr) return PGCM_ERR_ARG;
             if (((uintptr_t)src[i] | (uintptr_t)dst[i]) & 15) return PGCM_ERR_ALIGN;
         }
-        if (aad_len != nullptr && aad_len[i] != 0) {
-            if (aad[i] == nullptr) return PGCM_ERR_ARG;
-            any_aad = true;
-        }
+        if (aad_len != nullptr && aad_len[i] != 0 && aad[i] == nullptr) return PGCM_ERR_ARG;
         const uint32_t nu = plan_chunk(len[i]).nunits;
         uint32_t outs[kMaxLevels];
         const uint32_t levels = fold_levels(nu, outs);
@@ -180,8 +176,8 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     const size_t off_fold = round_up(off_coarse + sizeof(uint32_t) * (size_t)ncoarse, 256);
     const size_t upload_bytes = round_up(off_fold + sizeof(FoldItem) * (size_t)nfold, 256);
     const size_t off_counter = upload_bytes;
-    const size_t off_aad = off_counter + 256;
-    const size_t off_sets = round_up(off_aad + sizeof(Block) * n, 1024);
+    const size_t off_ekj0 = off_counter + 256;
+    const size_t off_sets = round_up(off_ekj0 + sizeof(Block) * n, 1024);
     const size_t work_bytes = off_sets + sizeof(Block) * 64 * (size_t)nslots;
 
     const int s = key->next_stage;
@@ -250,7 +246,7 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     const uint32_t* d_coarse = reinterpret_cast<const uint32_t*>(key->work + off_coarse);
     const FoldItem* d_fold = reinterpret_cast<const FoldItem*>(key->work + off_fold);
     uint32_t* d_counter = reinterpret_cast<uint32_t*>(key->work + off_counter);
-    Block* d_aad = any_aad ? reinterpret_cast<Block*>(key->work + off_aad) : nullptr;
+    Block* d_ekj0 = reinterpret_cast<Block*>(key->work + off_ekj0);
     Block* d_sets = reinterpret_cast<Block*>(key->work + off_sets);
 
     // the unit counter is left at zero by the last kernel of every batch; it only needs clearing
@@ -261,10 +257,6 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     }
     key->counter_dirty = true;
 
-    if (any_aad) {
-        hipLaunchKernelGGL(aad_state_kernel, dim3((nchunks + 63) / 64), dim3(64), 0, stream,
-                           key->tables, d_desc, nchunks, d_aad);
-    }
     if (nunits > 0) {
         uint32_t groups = (nunits + kWavesPerGroup - 1) / kWavesPerGroup;
         if (groups > (uint32_t)key->num_cu) groups = (uint32_t)key->num_cu;
@@ -272,11 +264,11 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
         if (decrypt)
             hipLaunchKernelGGL(bulk_kernel<true>, dim3(groups), dim3(kGroupThreads), 0, stream,
                                key->tables, d_desc, d_ubase, d_coarse, nunits, d_counter, ivs,
-                               d_aad, d_sets);
+                               d_ekj0, d_sets);
         else
             hipLaunchKernelGGL(bulk_kernel<false>, dim3(groups), dim3(kGroupThreads), 0, stream,
                                key->tables, d_desc, d_ubase, d_coarse, nunits, d_counter, ivs,
-                               d_aad, d_sets);
+                               d_ekj0, d_sets);
         if (key->timing) {
             PGCM_HIP(hipEventRecord(key->bulk_stop, stream));
             key->timed = true;
@@ -287,15 +279,17 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
         hipLaunchKernelGGL(fold_kernel, dim3(fold_count[l]), dim3(64), 0, stream, key->tables,
                            d_fold + fold_first[l], kUnitPower + kFanPower * l, d_sets);
     }
+    const uint32_t final_groups = (nchunks + 15) / 16;
     if (decrypt) {
-        hipLaunchKernelGGL(final_kernel<true>, dim3(nchunks), dim3(64), 0, stream, key->tables,
-                           d_desc, ivs, d_aad, d_sets, tags, ok, d_counter);
+        hipLaunchKernelGGL(final_kernel<true>, dim3(final_groups), dim3(1024), 0, stream,
+                           key->tables, d_desc, nchunks, ivs, d_ekj0, d_sets, tags, ok, d_counter);
         uint32_t wipers = nchunks < 1024 ? nchunks : 1024;
         hipLaunchKernelGGL(wipe_rejected_kernel, dim3(wipers), dim3(256), 0, stream, d_desc,
                            nchunks, ok);
     } else {
-        hipLaunchKernelGGL(final_kernel<false>, dim3(nchunks), dim3(64), 0, stream, key->tables,
-                           d_desc, ivs, d_aad, d_sets, tags, nullptr, d_counter);
+        hipLaunchKernelGGL(final_kernel<false>, dim3(final_groups), dim3(1024), 0, stream,
+                           key->tables, d_desc, nchunks, ivs, d_ekj0, d_sets, tags, nullptr,
+                           d_counter);
     }
     PGCM_HIP(hipGetLastError());
     key->counter_dirty = false;

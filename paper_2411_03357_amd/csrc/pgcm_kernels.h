@@ -8,22 +8,19 @@ namespace pgcm {
 
 __global__ void expand_key_kernel(KeyTables* kt, const uint32_t* key_words);
 
-__global__ void aad_state_kernel(const KeyTables* kt, const ChunkDesc* chunks, uint32_t n,
-                                 Block* aad_state);
-
 template <bool kDecrypt>
 __global__ void bulk_kernel(const KeyTables* kt, const ChunkDesc* chunks,
                             const uint32_t* unit_base, const uint32_t* coarse_map,
                             uint32_t nunits_total, uint32_t* counter, const uint8_t* ivs,
-                            const Block* aad_state, Block* sets);
+                            Block* ekj0, Block* sets);
 
 __global__ void fold_kernel(const KeyTables* kt, const FoldItem* items, uint32_t power,
                             Block* sets);
 
 template <bool kDecrypt>
-__global__ void final_kernel(const KeyTables* kt, const ChunkDesc* chunks, const uint8_t* ivs,
-                             const Block* aad_state, const Block* sets, uint8_t* tags,
-                             uint8_t* ok, uint32_t* counter);
+__global__ void final_kernel(const KeyTables* kt, const ChunkDesc* chunks, uint32_t nchunks,
+                             const uint8_t* ivs, const Block* ekj0, const Block* sets,
+                             uint8_t* tags, uint8_t* ok, uint32_t* counter);
 
 __global__ void wipe_rejected_kernel(const ChunkDesc* chunks, uint32_t n, const uint8_t* ok);
 

@@ -224,23 +224,26 @@ __global__ __launch_bounds__(1024) void expand_key_kernel(KeyTables* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------
-// GHASH state after the AAD of each chunk (SP 800-38D 6.4 over A || 0-pad); one thread a chunk.
-__global__ __launch_bounds__(64) void aad_state_kernel(const KeyTables* __restrict__ kt,
-                                 const ChunkDesc* __restrict__ chunks, uint32_t n,
-                                 Block* __restrict__ aad_state) {
-    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const ChunkDesc cd = chunks[i];
+// GHASH state after the AAD of a chunk (SP 800-38D 6.4 over A || 0-pad), hashed serially with the
+// table of H in global memory: meant for the short headers AAD is used for.  All lanes that call
+// it with the same arguments compute the same value.
+namespace {
+__device__ Block aad_hash(const KeyTables* __restrict__ kt, const uint8_t* __restrict__ aad,
+                          uint32_t aad_len) {
     Block y{{0, 0, 0, 0}};
-    for (uint32_t off = 0; off < cd.aad_len; off += 16) {
-        uint32_t m = cd.aad_len - off < 16 ? cd.aad_len - off : 16;
-        Block x{{0, 0, 0, 0}};
-        for (uint32_t b = 0; b < m; ++b) x.w[b / 4] |= (uint32_t)cd.aad[off + b] << (8 * (b % 4));
-        block_xor(y, x);
+    for (uint32_t off = 0; off < aad_len; off += 16) {
+        uint32_t m = aad_len - off < 16 ? aad_len - off : 16;
+        uint32_t x[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (uint32_t b = 0; b < 16; ++b) {
+            if (b < m) x[b / 4] |= (uint32_t)aad[off + b] << (8 * (b % 4));
+        }
+        y.w[0] ^= x[0], y.w[1] ^= x[1], y.w[2] ^= x[2], y.w[3] ^= x[3];
         y = gf_mul_table(kt->ghash[0], y);
     }
-    aad_state[i] = y;
+    return y;
 }
+}  // namespace
 
 // ------------------------------------------------------------------------------------------
 // The bulk kernel.  LDS map (byte addresses; the object below is the kernel's only LDS):
@@ -511,13 +514,12 @@ __device__ __forceinline__ void ghash_mul_lds(uint32_t base, uint32_t y[4]) {
 // last row of a chunk; a wave-uniform flag) some lanes may lie before the chunk's start and stay
 // idle, the last lane may hold the chunk's ragged last block, and the lane of block 0 folds in
 // the AAD state.  One code path serves both kinds: idle lanes run the cipher on a dummy counter,
-// touch no memory and keep a zero hash state.
+// touch no payload and keep a zero hash state.
 template <bool kDecrypt>
 __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAddr& A,
                                          const CtrConsts& C, const uint8_t* src, uint8_t* dst,
-                                         uint64_t len, int64_t blk, bool edge,
-                                         const Block* __restrict__ aad_state, uint32_t chunk,
-                                         uint32_t y[4]) {
+                                         uint64_t len, int64_t blk, bool edge, const Block& aad_y,
+                                         Block* __restrict__ ekj0_out, uint32_t y[4]) {
     bool active = true;
     uint32_t tail = 0;  // bytes in a ragged block, 0 = whole block
     if (edge) {
@@ -579,12 +581,16 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
     uint32_t c0 = kDecrypt ? x0 : o0, c1 = kDecrypt ? x1 : o1, c2 = kDecrypt ? x2 : o2,
              c3 = kDecrypt ? x3 : o3;
     if (edge) {
-        if (blk == 0 && aad_state != nullptr) {
+        if (blk == 0) {
             // GHASH continues from the state the AAD left: same as adding it to the first block
-            const Block a = aad_state[chunk];
-            c0 ^= a.w[0], c1 ^= a.w[1], c2 ^= a.w[2], c3 ^= a.w[3];
+            c0 ^= aad_y.w[0], c1 ^= aad_y.w[1], c2 ^= aad_y.w[2], c3 ^= aad_y.w[3];
         }
-        if (!active) c0 = c1 = c2 = c3 = 0;  // idle lanes only occur in a chunk's first row: Y = 0
+        if (blk == -1) {
+            // the counter of "block -1" is 1: this idle lane has just computed E_K(J0), the
+            // mask of the chunk's tag (SP 800-38D 7.1 steps 2 and 6)
+            *ekj0_out = Block{{s0, s1, s2, s3}};
+        }
+        if (!active) c0 = c1 = c2 = c3 = 0;  // idle lanes only occur before a chunk's start: Y = 0
     }
     y[0] = G.z0 ^ c0, y[1] = G.z1 ^ c1, y[2] = G.z2 ^ c2, y[3] = G.z3 ^ c3;
 }
@@ -601,7 +607,7 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks,
     const uint32_t* __restrict__ unit_base, const uint32_t* __restrict__ coarse_map,
     uint32_t nunits_total, uint32_t* __restrict__ counter, const uint8_t* __restrict__ ivs,
-    const Block* __restrict__ aad_state, Block* __restrict__ sets) {
+    Block* __restrict__ ekj0, Block* __restrict__ sets) {
     __shared__ BulkLds lds;
     // lookup addresses are formed as raw LDS addresses that assume this object starts at 0
     if (lds_offset(&lds) != 0) return;
@@ -640,7 +646,8 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
         const uint32_t unit = item - cd->unit_base, nunits = cd->nunits;
         const uint32_t first_blocks = cd->first_blocks;
         // the unit's blocks [b0, b1) of the chunk
-        const int64_t b0 = unit == 0 ? 0 : (int64_t)first_blocks + (int64_t)(unit - 1) * kUnitBlocks;
+        // unit 0 also takes "block -1", whose counter block is J0
+        const int64_t b0 = unit == 0 ? -1 : (int64_t)first_blocks + (int64_t)(unit - 1) * kUnitBlocks;
         const int64_t b1 = unit == 0 ? (int64_t)first_blocks : b0 + kUnitBlocks;
         const uint32_t nrows = (uint32_t)((b1 - b0 + kRowBlocks - 1) / kRowBlocks);
 
@@ -651,13 +658,17 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
                     ((uint32_t)ivp[4 * i + 2] << 16) | ((uint32_t)ivp[4 * i + 3] << 24);
         const CtrConsts C = ctr_consts(rk, lane, iv[0], iv[1], iv[2]);
 
+        Block aad_y{{0, 0, 0, 0}};
+        if (unit == 0 && cd->aad_len != 0) aad_y = aad_hash(kt, cd->aad, cd->aad_len);
+
         uint32_t y[4] = {0, 0, 0, 0};
-        // rows are aligned to the unit's end; only the chunk's very first row can start with idle
-        // lanes (block index below 0), only its very last row can hold a ragged block
-        int64_t blk = b1 - (int64_t)nrows * kRowBlocks + lane;
-        for (uint32_t r = 0; r < nrows; ++r, blk += kRowBlocks) {
-            const bool edge = (unit == 0 && r == 0) || (unit + 1 == nunits && r + 1 == nrows);
-            bulk_row<kDecrypt>(rk, A, C, src, dst, len, blk, edge, aad_state, chunk, y);
+        // rows are aligned to the unit's end; only rows at the chunk's start can have idle lanes
+        // (block index below 0) or block 0, only its very last row can hold a ragged block
+        int64_t row_blk = b1 - (int64_t)nrows * kRowBlocks;
+        for (uint32_t r = 0; r < nrows; ++r, row_blk += kRowBlocks) {
+            const bool edge = row_blk <= 0 || (unit + 1 == nunits && r + 1 == nrows);
+            bulk_row<kDecrypt>(rk, A, C, src, dst, len, row_blk + lane, edge, aad_y, ekj0 + chunk,
+                               y);
         }
         sets[(uint64_t)item * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
     }
@@ -665,33 +676,44 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
 
 template __global__ void bulk_kernel<false>(const KeyTables*, const ChunkDesc*, const uint32_t*,
                                             const uint32_t*, uint32_t, uint32_t*, const uint8_t*,
-                                            const Block*, Block*);
+                                            Block*, Block*);
 template __global__ void bulk_kernel<true>(const KeyTables*, const ChunkDesc*, const uint32_t*,
                                            const uint32_t*, uint32_t, uint32_t*, const uint8_t*,
-                                           const Block*, Block*);
+                                           Block*, Block*);
 
 // ------------------------------------------------------------------------------------------
 // Folding partial sets.  Consecutive sets of a chunk lie 2^power blocks apart, so, lane by lane,
 //   folded = (..(set_0 * G + set_1) * G + ..) + set_last   with G = H^(2^power).
 namespace {
 
-// one wavefront: copies the nibble table of H^(2^power) into LDS
-__device__ __forceinline__ void load_power_table(Block* lds_table, const KeyTables* __restrict__ kt,
-                                                 uint32_t power, uint32_t lane) {
-    for (uint32_t i = lane; i < kNibbleTableEntries; i += 64) lds_table[i] = kt->ghash[power][i];
-    __syncthreads();
+__device__ __forceinline__ void copy_power_table(Block* lds_table, const KeyTables* __restrict__ kt,
+                                                 uint32_t power, uint32_t tid, uint32_t nthreads) {
+    for (uint32_t i = tid; i < kNibbleTableEntries; i += nthreads) lds_table[i] = kt->ghash[power][i];
 }
 
-__device__ __forceinline__ void fold_sets(const Block* __restrict__ sets, uint32_t base,
-                                          uint32_t count, uint32_t lane, uint32_t table_addr,
-                                          uint32_t y[4]) {
+// table_addr: LDS address of G's nibble table, or 0xFFFFFFFF to read it from global memory
+__device__ __forceinline__ void fold_sets(const KeyTables* __restrict__ kt,
+                                          const Block* __restrict__ sets, uint32_t base,
+                                          uint32_t count, uint32_t power, uint32_t lane,
+                                          uint32_t table_addr, uint32_t y[4]) {
     Block first = sets[(uint64_t)base * 64 + lane];
     y[0] = first.w[0], y[1] = first.w[1], y[2] = first.w[2], y[3] = first.w[3];
     for (uint32_t s = 1; s < count; ++s) {
         const Block next = sets[(uint64_t)(base + s) * 64 + lane];
-        ghash_mul_lds(table_addr, y);
+        if (table_addr != 0xFFFFFFFFu) {
+            ghash_mul_lds(table_addr, y);
+        } else {
+            Block m = gf_mul_table(kt->ghash[power], Block{{y[0], y[1], y[2], y[3]}});
+            y[0] = m.w[0], y[1] = m.w[1], y[2] = m.w[2], y[3] = m.w[3];
+        }
         y[0] ^= next.w[0], y[1] ^= next.w[1], y[2] ^= next.w[2], y[3] ^= next.w[3];
     }
+}
+
+// value of lane (l + S) for S = 1, 2, 4, 8 inside each row of 16 lanes, by DPP
+template <int S>
+__device__ __forceinline__ uint32_t row_shift_down(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x100 + S, 0xF, 0xF, true);
 }
 
 }  // namespace
@@ -703,69 +725,91 @@ __global__ __launch_bounds__(64) void fold_kernel(const KeyTables* __restrict__ 
     __shared__ Block table[kNibbleTableEntries];
     const uint32_t lane = threadIdx.x;
     const FoldItem it = items[blockIdx.x];
-    load_power_table(table, kt, power, lane);
+    copy_power_table(table, kt, power, lane, 64);
+    __syncthreads();
     uint32_t y[4];
-    fold_sets(sets, it.in_base, it.in_count, lane, lds_offset(table), y);
+    fold_sets(kt, sets, it.in_base, it.in_count, power, lane, lds_offset(table), y);
     sets[(uint64_t)it.out_slot * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
 }
 
-// Per chunk (one wavefront each): fold the remaining sets, fold the 64 lanes, add the length
-// block, mask with E_K(J0) (SP 800-38D 7.1 steps 5-6); then write the tag, or compare it and write
-// the verdict (7.2).  The last workgroup's duty of clearing `counter` readies the next batch.
+// Per chunk (one wavefront each, sixteen chunks a workgroup): fold the remaining sets, fold the 64
+// lanes with a reduction tree (DPP inside rows of 16 lanes, LDS permutes across them), add the
+// length block, mask with E_K(J0) (SP 800-38D 7.1 steps 5-6); then write the tag, or compare it
+// and write the verdict (7.2).  Workgroup 0 also clears `counter` for the next batch.
+// LDS: nibble tables of H^1 .. H^32 (tree), and of the two most common fold distances.
+constexpr uint32_t kFinalChunksPerGroup = 16;
+constexpr uint32_t kFinalTables = 8;
+
 template <bool kDecrypt>
-__global__ __launch_bounds__(64) void final_kernel(const KeyTables* __restrict__ kt,
-                                                   const ChunkDesc* __restrict__ chunks,
-                                                   const uint8_t* __restrict__ ivs,
-                                                   const Block* __restrict__ aad_state,
-                                                   const Block* __restrict__ sets,
-                                                   uint8_t* __restrict__ tags,
-                                                   uint8_t* __restrict__ ok,
-                                                   uint32_t* __restrict__ counter) {
-    __shared__ Block table[kNibbleTableEntries];
-    const uint32_t lane = threadIdx.x;
-    const uint32_t i = blockIdx.x;
-    if (i == 0 && lane == 0) *counter = 0;
+__global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
+    const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks, uint32_t nchunks,
+    const uint8_t* __restrict__ ivs, const Block* __restrict__ ekj0,
+    const Block* __restrict__ sets, uint8_t* __restrict__ tags, uint8_t* __restrict__ ok,
+    uint32_t* __restrict__ counter) {
+    __shared__ Block tables[kFinalTables][kNibbleTableEntries];
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    if (blockIdx.x == 0 && tid == 0) *counter = 0;
+    // tables 0..5: H^(2^k) for the lane tree; 6, 7: H^(2^10), H^(2^15) for folding
+    for (uint32_t k = 0; k < 6; ++k) copy_power_table(tables[k], kt, k, tid, blockDim.x);
+    copy_power_table(tables[6], kt, kUnitPower, tid, blockDim.x);
+    copy_power_table(tables[7], kt, kUnitPower + kFanPower, tid, blockDim.x);
+    __syncthreads();
+
+    const uint32_t i = blockIdx.x * kFinalChunksPerGroup + (tid >> 6);
+    if (i >= nchunks) return;
     const ChunkDesc cd = chunks[i];
 
-    Block acc{{0, 0, 0, 0}};
+    uint32_t y[4] = {0, 0, 0, 0};
+    Block mask;
     if (cd.final_count == 0) {
-        // no ciphertext: the hash state is what the AAD left
-        if (aad_state != nullptr) acc = aad_state[i];
+        // no ciphertext, so no unit ran for this chunk: the hash state is what the AAD leaves,
+        // and E_K(J0) is still to be computed
+        const Block a = aad_hash(kt, cd.aad, cd.aad_len);
+        y[0] = a.w[0], y[1] = a.w[1], y[2] = a.w[2], y[3] = a.w[3];
+        const uint8_t* ivp = ivs + (uint64_t)i * 12;
+        uint32_t j0[4];
+        for (int w = 0; w < 3; ++w)
+            j0[w] = (uint32_t)ivp[4 * w] | ((uint32_t)ivp[4 * w + 1] << 8) |
+                    ((uint32_t)ivp[4 * w + 2] << 16) | ((uint32_t)ivp[4 * w + 3] << 24);
+        j0[3] = 0x01000000u;  // be32(1)
+        aes256_block_global(kt, j0);
+        mask = Block{{j0[0], j0[1], j0[2], j0[3]}};
     } else {
-        if (cd.final_count > 1) load_power_table(table, kt, cd.final_power, lane);
-        uint32_t y[4];
-        fold_sets(sets, cd.final_base, cd.final_count, lane, lds_offset(table), y);
-        // lanes -> one value: lane j's sum still lacks H^(64 - j): fold halves, then one more H
-        acc = Block{{y[0], y[1], y[2], y[3]}};
-#pragma unroll 1
-        for (int k = 5; k >= 0; --k) {
-            Block m = gf_mul_table(kt->ghash[k], acc);
-            const int s = 1 << k;
-            m.w[0] ^= __shfl_down(acc.w[0], s, 64);
-            m.w[1] ^= __shfl_down(acc.w[1], s, 64);
-            m.w[2] ^= __shfl_down(acc.w[2], s, 64);
-            m.w[3] ^= __shfl_down(acc.w[3], s, 64);
-            acc = m;
-        }
-        acc = gf_mul_table(kt->ghash[0], acc);
+        uint32_t fold_table = 0xFFFFFFFFu;
+        if (cd.final_power == kUnitPower) fold_table = lds_offset(tables[6]);
+        if (cd.final_power == kUnitPower + kFanPower) fold_table = lds_offset(tables[7]);
+        fold_sets(kt, sets, cd.final_base, cd.final_count, cd.final_power, lane, fold_table, y);
+        // lanes -> one value: lane j's sum still lacks H^(64 - j).  Tree: with s = 32, 16, .., 1
+        // lane j takes Y_j * H^s + Y_(j+s); lane 0 ends with sum_j Y_j * H^(63 - j); then one more H.
+        auto tree_step = [&](uint32_t k, uint32_t n0, uint32_t n1, uint32_t n2, uint32_t n3) {
+            ghash_mul_lds(lds_offset(tables[k]), y);
+            y[0] ^= n0, y[1] ^= n1, y[2] ^= n2, y[3] ^= n3;
+        };
+        tree_step(5, __shfl_down(y[0], 32, 64), __shfl_down(y[1], 32, 64),
+                  __shfl_down(y[2], 32, 64), __shfl_down(y[3], 32, 64));
+        tree_step(4, __shfl_down(y[0], 16, 64), __shfl_down(y[1], 16, 64),
+                  __shfl_down(y[2], 16, 64), __shfl_down(y[3], 16, 64));
+        tree_step(3, row_shift_down<8>(y[0]), row_shift_down<8>(y[1]), row_shift_down<8>(y[2]),
+                  row_shift_down<8>(y[3]));
+        tree_step(2, row_shift_down<4>(y[0]), row_shift_down<4>(y[1]), row_shift_down<4>(y[2]),
+                  row_shift_down<4>(y[3]));
+        tree_step(1, row_shift_down<2>(y[0]), row_shift_down<2>(y[1]), row_shift_down<2>(y[2]),
+                  row_shift_down<2>(y[3]));
+        tree_step(0, row_shift_down<1>(y[0]), row_shift_down<1>(y[1]), row_shift_down<1>(y[2]),
+                  row_shift_down<1>(y[3]));
+        ghash_mul_lds(lds_offset(tables[0]), y);
+        mask = ekj0[i];
     }
-    if (lane != 0) return;
 
     // [8 |A|]_64 || [8 |C|]_64, big endian
-    uint64_t abits = (uint64_t)cd.aad_len * 8, cbits = cd.len * 8;
-    Block lens{{bswap32((uint32_t)(abits >> 32)), bswap32((uint32_t)abits),
-                bswap32((uint32_t)(cbits >> 32)), bswap32((uint32_t)cbits)}};
-    block_xor(acc, lens);
-    acc = gf_mul_table(kt->ghash[0], acc);
-
-    const uint8_t* ivp = ivs + (uint64_t)i * 12;
-    uint32_t j0[4];
-    for (int w = 0; w < 3; ++w)
-        j0[w] = (uint32_t)ivp[4 * w] | ((uint32_t)ivp[4 * w + 1] << 8) |
-                ((uint32_t)ivp[4 * w + 2] << 16) | ((uint32_t)ivp[4 * w + 3] << 24);
-    j0[3] = 0x01000000u;  // be32(1)
-    aes256_block_global(kt, j0);
-    uint32_t t[4] = {acc.w[0] ^ j0[0], acc.w[1] ^ j0[1], acc.w[2] ^ j0[2], acc.w[3] ^ j0[3]};
+    const uint64_t abits = (uint64_t)cd.aad_len * 8, cbits = cd.len * 8;
+    y[0] ^= bswap32((uint32_t)(abits >> 32));
+    y[1] ^= bswap32((uint32_t)abits);
+    y[2] ^= bswap32((uint32_t)(cbits >> 32));
+    y[3] ^= bswap32((uint32_t)cbits);
+    ghash_mul_lds(lds_offset(tables[0]), y);
+    if (lane != 0) return;
+    const uint32_t t[4] = {y[0] ^ mask.w[0], y[1] ^ mask.w[1], y[2] ^ mask.w[2], y[3] ^ mask.w[3]};
 
     uint8_t* tp = tags + (uint64_t)i * 16;
     if (!kDecrypt) {
@@ -778,12 +822,12 @@ __global__ __launch_bounds__(64) void final_kernel(const KeyTables* __restrict__
     }
 }
 
-template __global__ void final_kernel<false>(const KeyTables*, const ChunkDesc*, const uint8_t*,
-                                             const Block*, const Block*, uint8_t*, uint8_t*,
-                                             uint32_t*);
-template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, const uint8_t*,
-                                            const Block*, const Block*, uint8_t*, uint8_t*,
-                                            uint32_t*);
+template __global__ void final_kernel<false>(const KeyTables*, const ChunkDesc*, uint32_t,
+                                             const uint8_t*, const Block*, const Block*, uint8_t*,
+                                             uint8_t*, uint32_t*);
+template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, uint32_t,
+                                            const uint8_t*, const Block*, const Block*, uint8_t*,
+                                            uint8_t*, uint32_t*);
 
 // Overwrites the output of every rejected chunk with zeros; one workgroup walks chunks.
 __global__ __launch_bounds__(256) void wipe_rejected_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n,
