@@ -236,7 +236,14 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     h_ubase[n] = unit;
     while (coarse_next < ncoarse) h_coarse[coarse_next++] = nchunks ? nchunks - 1 : 0;
 
-    PGCM_HIP(hipMemcpyAsync(key->work, key->stage[s], upload_bytes, hipMemcpyHostToDevice, stream));
+    {
+        const uint32_t n16 = (uint32_t)(upload_bytes / 16);
+        uint32_t groups = (n16 + 255) / 256;
+        if (groups > 1024) groups = 1024;
+        hipLaunchKernelGGL(upload_kernel, dim3(groups), dim3(256), 0, stream,
+                           reinterpret_cast<uint4*>(key->work),
+                           reinterpret_cast<const uint4*>(key->stage[s]), n16);
+    }
     PGCM_HIP(hipEventRecord(key->stage_done[s], stream));
     key->stage_used[s] = true;
     key->next_stage = (s + 1) % kStages;

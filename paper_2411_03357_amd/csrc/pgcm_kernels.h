@@ -22,6 +22,8 @@ __global__ void final_kernel(const KeyTables* kt, const ChunkDesc* chunks, uint3
                              const uint8_t* ivs, const Block* ekj0, const Block* sets,
                              uint8_t* tags, uint8_t* ok, uint32_t* counter);
 
+__global__ void upload_kernel(uint4* dst, const uint4* src_host, uint32_t n16);
+
 __global__ void wipe_rejected_kernel(const ChunkDesc* chunks, uint32_t n, const uint8_t* ok);
 
 }  // namespace pgcm

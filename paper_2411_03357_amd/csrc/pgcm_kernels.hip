@@ -494,20 +494,32 @@ __device__ __forceinline__ void aes256_ctr_lds(const uint32_t* __restrict__ rk, 
     });
 }
 
-// Y * C from C's nibble table at LDS address `base` (not interleaved with anything)
+// Y * C from C's nibble table at LDS address `base`, on its own (not riding along with AES):
+// the eight lookups of each word are issued together.
 __device__ __forceinline__ void ghash_mul_lds(uint32_t base, uint32_t y[4]) {
-    GhashRowMul G;
-    G.w[0] = y[0], G.w[1] = y[1], G.w[2] = y[2], G.w[3] = y[3];
-    static_for<0, 16>([&](auto step) __attribute__((always_inline)) {
-        constexpr int S = decltype(step)::value;
-        constexpr int i = S / 4, k = S % 4;
-        const uint32_t f0 = 0xF0u;
-        if constexpr (k == 0) G.t = G.w[i] << 4;
-        G.ra = lds_read128(base + nibble_offset<k>(G.w[i], f0) + 2 * S * 256);
-        G.rb = lds_read128(base + nibble_offset<k>(G.t, f0) + (2 * S + 1) * 256);
-        G.consume();
-    });
-    y[0] = G.z0, y[1] = G.z1, y[2] = G.z2, y[3] = G.z3;
+    uint32_t z0 = 0, z1 = 0, z2 = 0, z3 = 0;
+    const uint32_t f0 = 0xF0u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t w = y[i], t = y[i] << 4;
+        u32x4 e[8];
+        e[0] = lds_read128(base + nibble_offset<0>(w, f0) + (8 * i + 0) * 256);
+        e[1] = lds_read128(base + nibble_offset<0>(t, f0) + (8 * i + 1) * 256);
+        e[2] = lds_read128(base + nibble_offset<1>(w, f0) + (8 * i + 2) * 256);
+        e[3] = lds_read128(base + nibble_offset<1>(t, f0) + (8 * i + 3) * 256);
+        e[4] = lds_read128(base + nibble_offset<2>(w, f0) + (8 * i + 4) * 256);
+        e[5] = lds_read128(base + nibble_offset<2>(t, f0) + (8 * i + 5) * 256);
+        e[6] = lds_read128(base + nibble_offset<3>(w, f0) + (8 * i + 6) * 256);
+        e[7] = lds_read128(base + nibble_offset<3>(t, f0) + (8 * i + 7) * 256);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            z0 ^= e[k].x;
+            z1 ^= e[k].y;
+            z2 ^= e[k].z;
+            z3 ^= e[k].w;
+        }
+    }
+    y[0] = z0, y[1] = z1, y[2] = z2, y[3] = z3;
 }
 
 // One row of a unit: block `blk` of the chunk in this lane.  On `edge` rows (the first and the
@@ -691,15 +703,14 @@ __device__ __forceinline__ void copy_power_table(Block* lds_table, const KeyTabl
     for (uint32_t i = tid; i < kNibbleTableEntries; i += nthreads) lds_table[i] = kt->ghash[power][i];
 }
 
-// table_addr: LDS address of G's nibble table, or 0xFFFFFFFF to read it from global memory
+// table_addr: LDS address of G's nibble table, or 0xFFFFFFFF to read it from global memory.
+// Sets are fetched eight at a time so that their load latencies overlap.
 __device__ __forceinline__ void fold_sets(const KeyTables* __restrict__ kt,
                                           const Block* __restrict__ sets, uint32_t base,
                                           uint32_t count, uint32_t power, uint32_t lane,
                                           uint32_t table_addr, uint32_t y[4]) {
-    Block first = sets[(uint64_t)base * 64 + lane];
-    y[0] = first.w[0], y[1] = first.w[1], y[2] = first.w[2], y[3] = first.w[3];
-    for (uint32_t s = 1; s < count; ++s) {
-        const Block next = sets[(uint64_t)(base + s) * 64 + lane];
+    const Block* __restrict__ p = sets + (uint64_t)base * 64 + lane;
+    auto absorb = [&](const Block& next) {
         if (table_addr != 0xFFFFFFFFu) {
             ghash_mul_lds(table_addr, y);
         } else {
@@ -707,7 +718,18 @@ __device__ __forceinline__ void fold_sets(const KeyTables* __restrict__ kt,
             y[0] = m.w[0], y[1] = m.w[1], y[2] = m.w[2], y[3] = m.w[3];
         }
         y[0] ^= next.w[0], y[1] ^= next.w[1], y[2] ^= next.w[2], y[3] ^= next.w[3];
+    };
+    const Block first = p[0];
+    y[0] = first.w[0], y[1] = first.w[1], y[2] = first.w[2], y[3] = first.w[3];
+    uint32_t s = 1;
+    for (; s + 8 <= count; s += 8) {
+        Block n[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) n[k] = p[(uint64_t)(s + k) * 64];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) absorb(n[k]);
     }
+    for (; s < count; ++s) absorb(p[(uint64_t)s * 64]);
 }
 
 // value of lane (l + S) for S = 1, 2, 4, 8 inside each row of 16 lanes, by DPP
@@ -828,6 +850,16 @@ template __global__ void final_kernel<false>(const KeyTables*, const ChunkDesc*,
 template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, uint32_t,
                                             const uint8_t*, const Block*, const Block*, uint8_t*,
                                             uint8_t*, uint32_t*);
+
+// Brings a batch's descriptors from pinned host memory into the device workspace.  Done by a
+// kernel so that the batch stays on one hardware queue: a DMA copy between kernels costs two
+// cross-queue hand-overs.
+__global__ __launch_bounds__(256) void upload_kernel(uint4* __restrict__ dst,
+                                                     const uint4* __restrict__ src_host,
+                                                     uint32_t n16) {
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += gridDim.x * blockDim.x)
+        dst[i] = src_host[i];
+}
 
 // Overwrites the output of every rejected chunk with zeros; one workgroup walks chunks.
 __global__ __launch_bounds__(256) void wipe_rejected_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n,
