@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-chunks", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of the payload buffer (a kernel of known "
+                         "traffic to scale hardware byte counters by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (chunks are independent; a multi-GPU "
@@ -76,6 +79,11 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        scratch = torch.empty_like(b.plain)
+        scratch.copy_(b.plain)          # reads and writes w.total_bytes each
+        torch.cuda.synchronize()
+        del scratch
 
     # whole-path timing: host clock around K steps, synchronised on both sides
     t0 = time.perf_counter()

@@ -119,7 +119,7 @@ uint32_t pgcm_unit_bytes(void);
 /*
  * Measurement aid.  With timing enabled, every batch call also records a pair of HIP events on
  * its stream around the bulk kernel (the one launch that touches the payload: keystream, XOR
- * and GHASH of every segment).  pgcm_last_bulk_kernel_ms waits for the most recent batch's
+ * and GHASH of every unit).  pgcm_last_bulk_kernel_ms waits for the most recent batch's
  * bulk kernel and returns its duration in milliseconds; PGCM_ERR_ARG when nothing was timed.
  */
 int pgcm_set_timing(pgcm_key_t *key, int enable);

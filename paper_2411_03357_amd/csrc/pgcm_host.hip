@@ -290,9 +290,6 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     if (decrypt) {
         hipLaunchKernelGGL(final_kernel<true>, dim3(final_groups), dim3(1024), 0, stream,
                            key->tables, d_desc, nchunks, ivs, d_ekj0, d_sets, tags, ok, d_counter);
-        uint32_t wipers = nchunks < 1024 ? nchunks : 1024;
-        hipLaunchKernelGGL(wipe_rejected_kernel, dim3(wipers), dim3(256), 0, stream, d_desc,
-                           nchunks, ok);
     } else {
         hipLaunchKernelGGL(final_kernel<false>, dim3(final_groups), dim3(1024), 0, stream,
                            key->tables, d_desc, nchunks, ivs, d_ekj0, d_sets, tags, nullptr,

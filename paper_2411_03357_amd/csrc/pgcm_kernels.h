@@ -24,6 +24,4 @@ __global__ void final_kernel(const KeyTables* kt, const ChunkDesc* chunks, uint3
 
 __global__ void upload_kernel(uint4* dst, const uint4* src_host, uint32_t n16);
 
-__global__ void wipe_rejected_kernel(const ChunkDesc* chunks, uint32_t n, const uint8_t* ok);
-
 }  // namespace pgcm

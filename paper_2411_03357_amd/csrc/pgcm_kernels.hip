@@ -4,11 +4,14 @@
 // (paper sections 2.2 and 4.1), i.e. FIPS-197 AES-256 in the GCM mode of NIST SP 800-38D with a
 // 96-bit IV.  How it is computed here:
 //   * AES rounds read four 1 KiB round tables, each replicated 32 times in LDS so that lane l
-//     always reads bank l % 32: table lookups never collide, whatever the data.
-//   * GHASH multiplies by fixed powers of H with 4-bit tables (Shoup): the row power H^64 sits in
-//     LDS; the lane-combining tree uses H^32 .. H^1 from global memory once per segment.
-//   * One wavefront walks one segment (<= 64 KiB of one chunk) in rows of 64 blocks, one block
-//     per lane, 16-byte coalesced loads and stores, ciphertext hashed from registers.
+//     always reads bank l % 32: table lookups never collide, whatever the data.  AddRoundKey is
+//     folded into forming the next round's lookup addresses (one SDWA XOR per state byte).
+//   * GHASH multiplies by fixed powers of H with 4-bit tables (Shoup).  In the bulk kernel the
+//     row power H^64 sits in LDS and its thirty-two lookups are spread over the AES rounds.
+//   * One wavefront walks one unit (<= 16 KiB of one chunk) in rows of 64 blocks, one block per
+//     lane, 16-byte coalesced loads and stores, ciphertext hashed from registers; units are
+//     handed out by a device-side counter.  Each unit leaves 64 per-lane hash sums; fold and
+//     final kernels combine them per chunk (powers H^(2^k) from tables, DPP reduction tree).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -343,7 +346,7 @@ __device__ __forceinline__ void aes_addr_init(AesAddr& A, uint32_t lane) {
 }
 
 // The first three words of every counter block of a chunk are its IV, so in round 1 three of the
-// four lookups of each column do not depend on the block: their sums are formed once per segment.
+// four lookups of each column do not depend on the block: their sums are formed once per unit.
 struct CtrConsts {
     uint32_t k[4];
 };
@@ -820,6 +823,8 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
         tree_step(0, row_shift_down<1>(y[0]), row_shift_down<1>(y[1]), row_shift_down<1>(y[2]),
                   row_shift_down<1>(y[3]));
         ghash_mul_lds(lds_offset(tables[0]), y);
+        // only lane 0 holds the chunk's sum: hand it to every lane
+        for (int k = 0; k < 4; ++k) y[k] = __builtin_amdgcn_readfirstlane(y[k]);
         mask = ekj0[i];
     }
 
@@ -830,17 +835,26 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
     y[2] ^= bswap32((uint32_t)(cbits >> 32));
     y[3] ^= bswap32((uint32_t)cbits);
     ghash_mul_lds(lds_offset(tables[0]), y);
-    if (lane != 0) return;
     const uint32_t t[4] = {y[0] ^ mask.w[0], y[1] ^ mask.w[1], y[2] ^ mask.w[2], y[3] ^ mask.w[3]};
 
     uint8_t* tp = tags + (uint64_t)i * 16;
     if (!kDecrypt) {
-        for (int b = 0; b < 16; ++b) tp[b] = (uint8_t)(t[b / 4] >> (8 * (b % 4)));
+        if (lane == 0)
+            for (int b = 0; b < 16; ++b) tp[b] = (uint8_t)(t[b / 4] >> (8 * (b % 4)));
     } else {
-        // all 16 bytes, no data-dependent exit
+        // all 16 bytes, no data-dependent exit (every lane holds the same values)
         uint32_t diff = 0;
         for (int b = 0; b < 16; ++b) diff |= (uint32_t)tp[b] ^ ((t[b / 4] >> (8 * (b % 4))) & 0xFF);
-        ok[i] = diff == 0 ? 1 : 0;
+        diff = __builtin_amdgcn_readfirstlane(diff);
+        if (lane == 0) ok[i] = diff == 0 ? 1 : 0;
+        if (diff != 0) {
+            // rejected: unauthenticated plaintext must not stay behind; the wavefront zero-fills
+            // exactly len bytes
+            const uint64_t whole = cd.len / 16;
+            uint4* d = reinterpret_cast<uint4*>(cd.dst);
+            for (uint64_t b = lane; b < whole; b += 64) d[b] = make_uint4(0, 0, 0, 0);
+            for (uint64_t b = whole * 16 + lane; b < cd.len; b += 64) cd.dst[b] = 0;
+        }
     }
 }
 
@@ -859,19 +873,6 @@ __global__ __launch_bounds__(256) void upload_kernel(uint4* __restrict__ dst,
                                                      uint32_t n16) {
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += gridDim.x * blockDim.x)
         dst[i] = src_host[i];
-}
-
-// Overwrites the output of every rejected chunk with zeros; one workgroup walks chunks.
-__global__ __launch_bounds__(256) void wipe_rejected_kernel(const ChunkDesc* __restrict__ chunks, uint32_t n,
-                                     const uint8_t* __restrict__ ok) {
-    for (uint32_t i = blockIdx.x; i < n; i += gridDim.x) {
-        if (ok[i] != 0) continue;
-        const ChunkDesc cd = chunks[i];
-        const uint64_t whole = cd.len / 16;
-        uint4* d = reinterpret_cast<uint4*>(cd.dst);
-        for (uint64_t b = threadIdx.x; b < whole; b += blockDim.x) d[b] = make_uint4(0, 0, 0, 0);
-        for (uint64_t b = whole * 16 + threadIdx.x; b < cd.len; b += blockDim.x) cd.dst[b] = 0;
-    }
 }
 
 }  // namespace pgcm
