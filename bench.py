@@ -19,6 +19,29 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit op per lane-clock
 
+# Hardware counters of one bulk_kernel launch on the default workload, taken with
+# `rocprofv3 --pmc` (summaries and commands: profiles/).  They describe the kernel sources whose
+# hash is given; once the sources change they no longer apply and bench.py reports null.
+COUNTERS = {
+    "sources_sha256": "6e1f2dba67caea57360b7e9755d1e53307e248f19f8d3d4019478b617b54b1e9",
+    "workload": "c2_opt13b_kv_4096x320KiB",
+    "fetch_size_kib": 658152.6,     # FETCH_SIZE per launch
+    "fetch_scale": 1310720.0 / 655382.5,   # a 1 310 720 KiB device copy reads 655 382.5
+    "write_size_kib": 1395449.7,    # WRITE_SIZE per launch
+    "write_scale": 1310720.0 / 1310720.0,  # the same copy writes 1 310 720.0
+    "valu_wave_instructions": 753166336.0,  # SQ_INSTS_VALU per launch
+    "lds_wave_instructions": 321931264.0,   # SQ_INSTS_LDS per launch
+}
+
+
+def sources_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("pgcm_types.h", "pgcm_kernels.h", "pgcm_kernels.hip", "pgcm_host.hip"):
+        with open(os.path.join(ROOT, "paper_2411_03357_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
 
 def cpu_baseline(w, chunks, threads):
     """the oracle as it stands, timed on this host's cores over a bounded sample of the batch"""
@@ -128,6 +151,17 @@ def main():
     aad_total = 0 if w.aad is None else int(w.aad.size)
     algo_bytes = 2 * payload + w.n * (12 + 16 + 64) + aad_total
     achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
+    traffic = None
+    alu = None
+    if COUNTERS["workload"] == w.name and COUNTERS["sources_sha256"] == sources_sha256():
+        traffic = int(1024 * (COUNTERS["fetch_size_kib"] * COUNTERS["fetch_scale"] +
+                              COUNTERS["write_size_kib"] * COUNTERS["write_scale"]))
+        lane_ops = COUNTERS["valu_wave_instructions"] * 64
+        alu_achieved = lane_ops / (kern_avg_ms * 1e-3) / 1e12
+        alu = {"bound": "alu", "achieved": round(alu_achieved, 2), "peak": round(VALU_PEAK_TOPS, 2),
+               "unit": "T 32-bit lane-ops/s", "frac": round(alu_achieved / VALU_PEAK_TOPS, 4),
+               "valu_ops_per_payload_byte": round(lane_ops / payload, 2),
+               "lds_lookups_per_payload_byte": round(COUNTERS["lds_wave_instructions"] * 64 / payload, 2)}
 
     out = {
         "metric": "AES-256-GCM enc / dec+verify GB/s on 1 MI355X; % of HBM roofline",
@@ -149,11 +183,13 @@ def main():
         "pct_hbm_roofline": round(100.0 * 2.0 * value / HBM_PEAK_GBS, 2),
         "roofline": {"bound": "hbm", "kernel": "bulk_kernel (CTR keystream + XOR + GHASH)",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "algorithmic_bytes": algo_bytes,
                      "avg_launch_ms": round(kern_avg_ms, 4),
                      "enc_launch_ms": round(sum(kern["enc"]) / reps, 4),
                      "dec_launch_ms": round(sum(kern["dec"]) / reps, 4)},
     }
+    out["roofline_alu"] = alu
     if not args.no_cpu_baseline:
         chunks = args.cpu_chunks or max(1, int(40e6 // max(1, int(w.lens.mean()))))
         threads = min(16, os.cpu_count() or 1)
