@@ -11,28 +11,29 @@ import numpy as np
 
 from . import build as _build
 
-_lib = C.CDLL(_build.build())
+def _bind(lib):
+    """declares the argument types of the oracle's C entry points on a loaded library"""
+    lib.orc_sbox.argtypes = [C.c_void_p]
+    lib.orc_aes256_key_expand.argtypes = [C.c_void_p, C.c_void_p]
+    lib.orc_aes256_encrypt_block.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.orc_gf128_mul.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.orc_ghash_update.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.orc_gctr.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
+    lib.orc_gcm_encrypt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
+                                    C.c_uint64, C.c_void_p, C.c_void_p]
+    lib.orc_gcm_decrypt_verify.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
+                                           C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
+    lib.orc_gcm_decrypt_verify.restype = C.c_int
+    common = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+              C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.orc_gcm_encrypt_batch.argtypes = common + [C.c_int]
+    lib.orc_gcm_encrypt_batch.restype = C.c_int
+    lib.orc_gcm_decrypt_verify_batch.argtypes = common + [C.c_void_p, C.c_int]
+    lib.orc_gcm_decrypt_verify_batch.restype = C.c_int
+    return lib
 
-_u8p = C.POINTER(C.c_uint8)
-_pp = C.POINTER(C.c_void_p)
 
-_lib.orc_sbox.argtypes = [C.c_void_p]
-_lib.orc_aes256_key_expand.argtypes = [C.c_void_p, C.c_void_p]
-_lib.orc_aes256_encrypt_block.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
-_lib.orc_gf128_mul.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
-_lib.orc_ghash_update.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
-_lib.orc_gctr.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
-_lib.orc_gcm_encrypt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
-                                 C.c_uint64, C.c_void_p, C.c_void_p]
-_lib.orc_gcm_decrypt_verify.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
-                                        C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
-_lib.orc_gcm_decrypt_verify.restype = C.c_int
-_batch_common = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                 C.c_void_p, C.c_void_p, C.c_void_p]
-_lib.orc_gcm_encrypt_batch.argtypes = _batch_common + [C.c_int]
-_lib.orc_gcm_encrypt_batch.restype = C.c_int
-_lib.orc_gcm_decrypt_verify_batch.argtypes = _batch_common + [C.c_void_p, C.c_int]
-_lib.orc_gcm_decrypt_verify_batch.restype = C.c_int
+_lib = _bind(C.CDLL(_build.build()))
 
 
 def _in(b, n=None):

@@ -1,0 +1,78 @@
+"""Chunks long enough to need two and three fold levels (more than 32^2 and 32^3 units of
+16 KiB), with ragged ends so that every level has a short first group.
+
+The 16 MiB+ chunk is checked against the oracle on every byte.  The oracle would need minutes for
+the 512 MiB+ chunk, so that one is checked against libcrypto (an independent implementation the
+oracle itself is pinned to) plus the round-trip identity."""
+import numpy as np
+import pytest
+import torch
+
+import openssl_ref
+import oracle
+import workloads
+from gpu_harness import DeviceBatch
+
+import paper_2411_03357_amd as pgcm
+
+pytestmark = pytest.mark.gpu
+
+
+def _workload(lens, seed_shift, aad_len):
+    seed, rng, key, iv0 = workloads._base(7, seed_shift)
+    lens = np.array(lens, np.uint64)
+    offsets, total = workloads._layout(lens)
+    aad = rng.integers(0, 256, aad_len * lens.size, dtype=np.uint8)
+    aad_off = np.arange(lens.size + 1, dtype=np.uint64) * aad_len
+    return workloads.Workload("fold_levels", seed, key, workloads.iv_sequence(iv0, lens.size),
+                              lens, offsets, total, "u8", aad, aad_off)
+
+
+def test_two_fold_levels_against_the_oracle():
+    unit = pgcm.unit_bytes()
+    # 1024 units + 3 blocks + 5 bytes: level 1 has 33 groups (first one short), level 2 folds 33 -> 2
+    big = 1024 * unit + 3 * 16 + 5
+    w = _workload([big, 33 * unit + 1, 40], 0, 20)
+    plan = pgcm.plan_units(w.lens)
+    assert int(plan["final_power"][0]) == 20 and int(plan["final_power"][1]) == 15
+    key = pgcm.expand_key(w.key)
+    b = DeviceBatch(w, w.payload_device())
+    b.encrypt(key)
+    b.decrypt(key)
+    torch.cuda.synchronize()
+    srcs = [b.chunk_host(b.plain, i) for i in range(w.n)]
+    aads = [np.frombuffer(w.aad_of(i), np.uint8) for i in range(w.n)]
+    cts, tags, _ = oracle.encrypt_batch(w.key, w.ivs, aads, srcs, nthreads=3)
+    got = b.tags.cpu().numpy().reshape(-1, 16)
+    for i in range(w.n):
+        assert np.array_equal(b.chunk_host(b.cipher, i), cts[i]), i
+        assert np.array_equal(got[i], tags[i]), i
+    assert bool((b.ok == 1).all()) and torch.equal(b.back, b.plain)
+    # a flipped bit deep inside the long chunk is noticed and the chunk wiped
+    bad = b.cipher.clone()
+    bad[int(w.offsets[0]) + 7 * 1024 * 1024 + 3] ^= 0x20
+    b.decrypt(key, src=bad)
+    torch.cuda.synchronize()
+    assert b.ok.cpu().tolist() == [0, 1, 1]
+    assert int(b.chunk_host(b.back, 0).max()) == 0
+    assert np.array_equal(b.chunk_host(b.back, 1), srcs[1])
+    key.free()
+
+
+def test_three_fold_levels_against_libcrypto():
+    unit = pgcm.unit_bytes()
+    big = (32 * 32 * 32 + 40) * unit + 16 * 9 + 11      # 512 MiB + 640 KiB + ...
+    w = _workload([big], 1, 13)
+    plan = pgcm.plan_units(w.lens)
+    assert int(plan["final_power"][0]) == 25
+    key = pgcm.expand_key(w.key)
+    b = DeviceBatch(w, w.payload_device())
+    b.encrypt(key)
+    b.decrypt(key)
+    torch.cuda.synchronize()
+    assert bool((b.ok == 1).all()) and torch.equal(b.back, b.plain)
+    pt = b.chunk_host(b.plain, 0).tobytes()
+    c, t = openssl_ref.encrypt(w.key.tobytes(), w.ivs[0].tobytes(), w.aad_of(0), pt)
+    assert b.tags.cpu().numpy().tobytes() == t
+    assert b.chunk_host(b.cipher, 0).tobytes() == c
+    key.free()
