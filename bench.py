@@ -72,6 +72,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-chunks", type=int, default=0)
+    ap.add_argument("--host-bounce", action="store_true",
+                    help="keep the ciphertext in pinned host memory (encrypt into / decrypt out of "
+                         "a host bounce buffer over PCIe); not the headline configuration")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of the payload buffer (a kernel of known "
                          "traffic to scale hardware byte counters by)")
@@ -92,6 +95,8 @@ def main():
     w = workloads.FULL[args.config]()
     key = pgcm.expand_key(w.key)
     b = DeviceBatch(w, w.payload_device())
+    if args.host_bounce:
+        b.cipher = torch.zeros(w.total_bytes, dtype=torch.uint8, pin_memory=True)
     payload = w.payload_bytes
     stream = torch.cuda.current_stream()
 
@@ -153,7 +158,8 @@ def main():
     achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
     traffic = None
     alu = None
-    if COUNTERS["workload"] == w.name and COUNTERS["sources_sha256"] == sources_sha256():
+    if (COUNTERS["workload"] == w.name and COUNTERS["sources_sha256"] == sources_sha256()
+            and not args.host_bounce):
         traffic = int(1024 * (COUNTERS["fetch_size_kib"] * COUNTERS["fetch_scale"] +
                               COUNTERS["write_size_kib"] * COUNTERS["write_scale"]))
         lane_ops = COUNTERS["valu_wave_instructions"] * 64
@@ -177,7 +183,8 @@ def main():
         "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": w.name, "chunks": w.n, "payload_bytes": payload,
-                   "step": "encrypt batch + decrypt-verify batch", "unit_bytes": pgcm.unit_bytes()},
+                   "step": "encrypt batch + decrypt-verify batch", "unit_bytes": pgcm.unit_bytes(),
+                   "ciphertext": "pinned host memory" if args.host_bounce else "device memory"},
         "enc_GBps": round(payload / (enc_ms[len(enc_ms) // 2] * 1e-3) / 1e9, 2),
         "dec_verify_GBps": round(payload / (dec_ms[len(dec_ms) // 2] * 1e-3) / 1e9, 2),
         "pct_hbm_roofline": round(100.0 * 2.0 * value / HBM_PEAK_GBS, 2),

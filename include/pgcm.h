@@ -11,8 +11,10 @@
  * The cipher is AES-256 (FIPS-197) in GCM (NIST SP 800-38D) with 96-bit IVs and full 16-byte tags.
  *
  * Conventions for every call
- *   - "DEVICE" pointers address GPU memory of the current HIP device; "HOST" pointers address
- *     ordinary process memory.  Host arrays are consumed before the call returns.
+ *   - "DEVICE" pointers address memory the current HIP device can access: its own memory, or
+ *     pinned host memory mapped for it (hipHostMalloc), e.g. a bounce buffer that receives the
+ *     ciphertext directly.  "HOST" pointers address ordinary process memory; host arrays are
+ *     consumed before the call returns.
  *   - Work is enqueued on `hip_stream` (a hipStream_t cast to void*, NULL = the null stream) and
  *     the call returns without synchronising.  Device outputs are valid once the stream has
  *     reached the end of the batch; device inputs must stay alive and unchanged until then.
