@@ -105,6 +105,11 @@ __device__ Gf gf_mul_bits(const Gf& x, const Gf& y) {
     return z;
 }
 
+// a ^ b ^ c in one instruction (gfx950's three-input bitwise op, truth table 0x96)
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 __device__ __forceinline__ void block_xor(Block& a, const Block& b) {
     a.w[0] ^= b.w[0];
     a.w[1] ^= b.w[1];
@@ -408,10 +413,10 @@ struct GhashRowMul {
         rb = lds_read128(nibble_offset<k>(t, f0) + (pos + 1) * 256);
     }
     __device__ __forceinline__ void consume() {
-        z0 ^= ra.x ^ rb.x;
-        z1 ^= ra.y ^ rb.y;
-        z2 ^= ra.z ^ rb.z;
-        z3 ^= ra.w ^ rb.w;
+        z0 = xor3(z0, ra.x, rb.x);
+        z1 = xor3(z1, ra.y, rb.y);
+        z2 = xor3(z2, ra.z, rb.z);
+        z3 = xor3(z3, ra.w, rb.w);
         // pin the running sums here: otherwise the optimizer moves the whole XOR chain to where
         // its result is used and keeps all thirty-two table entries alive until then
         asm volatile("" : "+v"(z0), "+v"(z1), "+v"(z2), "+v"(z3));
@@ -473,17 +478,17 @@ __device__ __forceinline__ void aes256_ctr_lds(const uint32_t* __restrict__ rk, 
         // one GHASH byte step per round: steps 3 .. 15 in rounds 2 .. 14
         G.template issue<r + 1>();
         if constexpr (r < 14) {
-            u0 = t00 ^ t11 ^ t22 ^ t33;
-            u1 = t10 ^ t21 ^ t32 ^ t03;
-            u2 = t20 ^ t31 ^ t02 ^ t13;
-            u3 = t30 ^ t01 ^ t12 ^ t23;
+            u0 = xor3(t00, t11, t22) ^ t33;
+            u1 = xor3(t10, t21, t32) ^ t03;
+            u2 = xor3(t20, t31, t02) ^ t13;
+            u3 = xor3(t30, t01, t12) ^ t23;
         } else {
             // last round, no MixColumns: S(x) is byte 1 of te[0], byte 2 of te[1], byte 0 of
             // te[2] and te[3]
             auto last = [&](uint32_t v0, uint32_t v1, uint32_t v2, uint32_t v3, uint32_t key) {
                 uint32_t lo = __builtin_amdgcn_perm(v0, v1, 0x0c0c0205u);  // [v0.b1, v1.b2, 0, 0]
                 uint32_t hi = __builtin_amdgcn_perm(v2, v3, 0x00040c0cu);  // [0, 0, v2.b0, v3.b0]
-                return lo ^ hi ^ key;
+                return xor3(lo, hi, key);
             };
             o0 = last(t00, t11, t22, t33, rk[56]);
             o1 = last(t10, t21, t32, t03, rk[57]);
@@ -515,11 +520,11 @@ __device__ __forceinline__ void ghash_mul_lds(uint32_t base, uint32_t y[4]) {
         e[6] = lds_read128(base + nibble_offset<3>(w, f0) + (8 * i + 6) * 256);
         e[7] = lds_read128(base + nibble_offset<3>(t, f0) + (8 * i + 7) * 256);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            z0 ^= e[k].x;
-            z1 ^= e[k].y;
-            z2 ^= e[k].z;
-            z3 ^= e[k].w;
+        for (int k = 0; k < 8; k += 2) {
+            z0 = xor3(z0, e[k].x, e[k + 1].x);
+            z1 = xor3(z1, e[k].y, e[k + 1].y);
+            z2 = xor3(z2, e[k].z, e[k + 1].z);
+            z3 = xor3(z3, e[k].w, e[k + 1].w);
         }
     }
     y[0] = z0, y[1] = z1, y[2] = z2, y[3] = z3;
