@@ -348,9 +348,16 @@ void pgcm_free_key(pgcm_key_t* k) {
         (void)hipMemset(k->tables, 0, sizeof(KeyTables));
         (void)hipFree(k->tables);
     }
-    if (k->work) (void)hipFree(k->work);
+    if (k->work) {
+        // the workspace holds key-dependent values (tag masks, partial hashes)
+        (void)hipMemset(k->work, 0, k->work_cap);
+        (void)hipFree(k->work);
+    }
     for (int s = 0; s < kStages; ++s) {
-        if (k->stage[s]) (void)hipHostFree(k->stage[s]);
+        if (k->stage[s]) {
+            memset(k->stage[s], 0, k->stage_cap[s]);
+            (void)hipHostFree(k->stage[s]);
+        }
         if (k->stage_done[s]) (void)hipEventDestroy(k->stage_done[s]);
     }
     if (k->bulk_start) (void)hipEventDestroy(k->bulk_start);
