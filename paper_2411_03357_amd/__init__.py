@@ -6,4 +6,4 @@ loudly when libpgcm.so has not been built (python -m paper_2411_03357_amd.build)
 """
 from .binding import (PgcmError, Key, expand_key, encrypt_batch, decrypt_verify_batch,  # noqa: F401
                       plan_units, unit_bytes, library_path, load_library, set_timing,
-                      last_bulk_kernel_ms, EXPORTS)
+                      last_bulk_kernel_ms, EXPORTS, Sequencer, seq_iv_bytes, SEQ_EXPORTS)

@@ -195,3 +195,100 @@ def last_bulk_kernel_ms(key: Key) -> float:
 
 def unit_bytes() -> int:
     return int(load_library().pgcm_unit_bytes())
+
+
+# ---------------------------------------------------------------------------------------------
+# include/pgcm_seq.h: the speculative-pipeline state machine (host only)
+
+SEQ_EXPORTS = ("pgcm_seq_create", "pgcm_seq_destroy", "pgcm_seq_swap_out", "pgcm_seq_notify_write",
+               "pgcm_seq_request", "pgcm_seq_sync", "pgcm_seq_take_actions", "pgcm_seq_current_iv",
+               "pgcm_seq_iv_bytes")
+SEQ_KINDS = {1: "pre", 2: "send", 3: "now", 4: "nop", 5: "drop"}
+
+
+class _SeqAction(C.Structure):
+    _fields_ = [("kind", C.c_uint32), ("reserved", C.c_uint32), ("addr", C.c_uint64),
+                ("len", C.c_uint64), ("iv", C.c_uint64)]
+
+
+def _seq_lib():
+    lib = load_library()
+    if not getattr(lib, "_seq_bound", False):
+        vp = C.c_void_p
+        lib.pgcm_seq_create.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint32,
+                                        C.POINTER(vp)]
+        lib.pgcm_seq_create.restype = C.c_int
+        lib.pgcm_seq_destroy.argtypes = [vp]
+        lib.pgcm_seq_destroy.restype = None
+        for name in ("pgcm_seq_swap_out", "pgcm_seq_notify_write", "pgcm_seq_request"):
+            getattr(lib, name).argtypes = [vp, C.c_uint64, C.c_uint64]
+            getattr(lib, name).restype = C.c_int
+        lib.pgcm_seq_sync.argtypes = [vp]
+        lib.pgcm_seq_sync.restype = C.c_int
+        lib.pgcm_seq_take_actions.argtypes = [vp, C.POINTER(_SeqAction), C.c_size_t]
+        lib.pgcm_seq_take_actions.restype = C.c_size_t
+        lib.pgcm_seq_current_iv.argtypes = [vp]
+        lib.pgcm_seq_current_iv.restype = C.c_uint64
+        lib.pgcm_seq_iv_bytes.argtypes = [vp, C.c_uint64, vp]
+        lib.pgcm_seq_iv_bytes.restype = None
+        lib._seq_bound = True
+    return lib
+
+
+class Sequencer:
+    """pgcm_seq_t: events in, actions out (tuples (kind, (addr, len), iv); NOPs are (kind, iv))"""
+
+    def __init__(self, iv_start=0, depth=4, leeway=0, threshold=128 * 1024, history_limit=512):
+        self._lib = _seq_lib()
+        h = C.c_void_p()
+        _check(self._lib.pgcm_seq_create(iv_start, depth, leeway, threshold, history_limit,
+                                         C.byref(h)))
+        self._h = h.value
+
+    def close(self):
+        if self._h is not None:
+            self._lib.pgcm_seq_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def swap_out(self, chunk):
+        _check(self._lib.pgcm_seq_swap_out(self._h, chunk[0], chunk[1]))
+
+    def notify_write(self, chunk):
+        _check(self._lib.pgcm_seq_notify_write(self._h, chunk[0], chunk[1]))
+
+    def request(self, chunk):
+        _check(self._lib.pgcm_seq_request(self._h, chunk[0], chunk[1]))
+
+    def sync(self):
+        _check(self._lib.pgcm_seq_sync(self._h))
+
+    @property
+    def iv_cur(self):
+        return int(self._lib.pgcm_seq_current_iv(self._h))
+
+    def take_actions(self):
+        out = []
+        buf = (_SeqAction * 64)()
+        while True:
+            n = self._lib.pgcm_seq_take_actions(self._h, buf, 64)
+            for a in buf[:n]:
+                kind = SEQ_KINDS[a.kind]
+                out.append((kind, a.iv) if kind == "nop" else (kind, (a.addr, a.len), a.iv))
+            if n < 64:
+                return out
+
+
+def seq_iv_bytes(iv0, n) -> bytes:
+    """pgcm_seq_iv_bytes: iv0 + n as 12 big-endian bytes"""
+    a = np.frombuffer(bytes(iv0), dtype=np.uint8).copy()
+    if a.size != 12:
+        raise ValueError("IVs are 12 bytes")
+    out = np.zeros(12, np.uint8)
+    _seq_lib().pgcm_seq_iv_bytes(a.ctypes.data, n, out.ctypes.data)
+    return out.tobytes()

@@ -12,8 +12,8 @@ import paper_2411_03357_amd as pgcm
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "pgcm.h")).read()
+def _declared(header="pgcm.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(pgcm_[a-z_0-9]+)\s*\(", text)))
 
@@ -25,6 +25,10 @@ def test_every_declared_symbol_is_exported():
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(pgcm.EXPORTS) == names
+    seq_names = _declared("pgcm_seq.h")
+    assert len(seq_names) == 9 and sorted(pgcm.SEQ_EXPORTS) == seq_names
+    for n in seq_names:
+        assert hasattr(lib, n), n
 
 
 def test_strerror_and_null_arguments_without_gpu():

@@ -238,3 +238,65 @@ def mini(cfg: int) -> Workload:
     if cfg == 5:
         return config5(n=4, frac=0.5)
     raise ValueError(cfg)
+
+
+# ---------------------------------------------------------------------------------------------
+# Swap traces for the speculative-pipeline state machine: lists of events
+#   ("out", chunk) | ("req", chunk) | ("write", chunk) | ("sync",)   with chunk = (address, bytes).
+# They imitate the swapping patterns the paper names (section 5.1): repetitive weight offloading,
+# FIFO layer-wise and LIFO request-wise KV-cache swapping, with small transfers in between.
+
+def swap_trace(kind: str, seed: int = 0, rounds: int = 6, noise: float = 0.0):
+    rng = np.random.default_rng([BASE_SEED, 77, seed])
+    ev = []
+    small = lambda: ("req", (0x7000_0000 + int(rng.integers(0, 1 << 20)) * 64,
+                             int(rng.integers(1, 8192))))
+    if kind == "repetitive":
+        # FlexGen-like: the same offloaded layers come back in the same order every iteration
+        layers = [(0x1000_0000 + i * (4 << 20), 2 << 20) for i in sorted(
+            rng.choice(24, size=int(rng.integers(3, 9)), replace=False))]
+        for _ in range(rounds):
+            for i in range(0, len(layers), 2):
+                for c in layers[i:i + 2]:
+                    ev.append(("req", c))
+                    if rng.random() < noise:
+                        ev.append(small())
+                ev.append(("sync",))
+    elif kind in ("fifo", "lifo"):
+        # vLLM-like: KV blocks leave in some order and return in the same (FIFO) or the
+        # reverse (LIFO) order
+        nxt = 0
+        for _ in range(rounds):
+            n = int(rng.integers(2, 7))
+            blocks = [(0x2000_0000 + (nxt + i) * 327680, 327680) for i in range(n)]
+            nxt += n
+            for c in blocks:
+                ev.append(("out", c))
+            ev.append(("sync",))
+            back = blocks if kind == "fifo" else blocks[::-1]
+            for c in back:
+                ev.append(("req", c))
+                if rng.random() < noise:
+                    ev.append(small())
+            ev.append(("sync",))
+    elif kind == "chaos":
+        # nothing predictable: random chunks, repeats inside a batch, writes, stray syncs
+        pool = [(0x3000_0000 + i * (1 << 20), int(rng.choice([1 << 19, 1 << 20, 200_000])))
+                for i in range(10)]
+        for _ in range(rounds * 8):
+            r = rng.random()
+            c = pool[int(rng.integers(0, len(pool)))]
+            if r < 0.45:
+                ev.append(("req", c))
+            elif r < 0.65:
+                ev.append(("out", c))
+            elif r < 0.75:
+                ev.append(("write", (c[0] + int(rng.integers(0, c[1])), int(rng.integers(1, 4096)))))
+            elif r < 0.85:
+                ev.append(small())
+            else:
+                ev.append(("sync",))
+        ev.append(("sync",))
+    else:
+        raise ValueError(kind)
+    return ev
