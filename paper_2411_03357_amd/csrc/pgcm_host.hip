@@ -133,10 +133,13 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     if (n > 0x7FFFFFFFull) return PGCM_ERR_ARG;
 
     // validate everything before touching any state
+    const uint32_t nchunks = (uint32_t)n;
     uint64_t nunits64 = 0, nslots64 = 0;
     uint64_t fold_items64[kMaxLevels] = {0, 0, 0, 0};
+    bool all_small = true;
     for (size_t i = 0; i < n; ++i) {
         if (len[i] > PGCM_MAX_CHUNK_BYTES) return PGCM_ERR_LEN;
+        if (len[i] > kSmallChunkBytes) all_small = false;
         if (len[i] != 0) {
             if (src[i] == nullptr || dst[i] == nullptr) return PGCM_ERR_ARG;
             if (((uintptr_t)src[i] | (uintptr_t)dst[i]) & 15) return PGCM_ERR_ALIGN;
@@ -155,7 +158,6 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     if (nslots64 > 0xFFFFFFF0ull / 64) return PGCM_ERR_ARG;  // set indices are 32-bit
     const uint32_t nunits = (uint32_t)nunits64;
     const uint32_t nslots = (uint32_t)nslots64;
-    const uint32_t nchunks = (uint32_t)n;
     uint32_t fold_count[kMaxLevels], fold_first[kMaxLevels], nfold = 0;
     for (uint32_t l = 0; l < kMaxLevels; ++l) {
         fold_count[l] = (uint32_t)fold_items64[l];
@@ -168,6 +170,41 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     int cur_device = -1;
     PGCM_HIP(hipGetDevice(&cur_device));
     if (cur_device != key->device) return PGCM_ERR_ARG;  // the key lives on another GPU
+
+    if (all_small) {
+        // small-transfer path: one kernel, descriptors read straight from the pinned staging
+        // buffer, no device workspace
+        const int s = key->next_stage;
+        int rc = ensure_stage(key, s, sizeof(ChunkDesc) * n);
+        if (rc != PGCM_OK) return rc;
+        ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(key->stage[s]);
+        for (size_t i = 0; i < n; ++i) {
+            ChunkDesc& d = h_desc[i];
+            memset(&d, 0, sizeof(d));
+            d.src = (const uint8_t*)src[i];
+            d.dst = (uint8_t*)dst[i];
+            d.len = len[i];
+            d.aad_len = aad_len ? aad_len[i] : 0;
+            d.aad = d.aad_len ? (const uint8_t*)aad[i] : nullptr;
+        }
+        const uint32_t groups = (nchunks + kSmallChunksPerGroup - 1) / kSmallChunksPerGroup;
+        if (key->timing) PGCM_HIP(hipEventRecord(key->bulk_start, stream));
+        if (decrypt)
+            hipLaunchKernelGGL(small_kernel<true>, dim3(groups), dim3(kSmallChunksPerGroup * 64), 0,
+                               stream, key->tables, h_desc, nchunks, ivs, tags, ok);
+        else
+            hipLaunchKernelGGL(small_kernel<false>, dim3(groups), dim3(kSmallChunksPerGroup * 64), 0,
+                               stream, key->tables, h_desc, nchunks, ivs, tags, nullptr);
+        if (key->timing) {
+            PGCM_HIP(hipEventRecord(key->bulk_stop, stream));
+            key->timed = true;
+        }
+        PGCM_HIP(hipGetLastError());
+        PGCM_HIP(hipEventRecord(key->stage_done[s], stream));
+        key->stage_used[s] = true;
+        key->next_stage = (s + 1) % kStages;
+        return PGCM_OK;
+    }
 
     // workspace layout; the regions up to upload_bytes are written by the host and uploaded
     const size_t off_desc = 0;

@@ -22,6 +22,12 @@ __global__ void final_kernel(const KeyTables* kt, const ChunkDesc* chunks, uint3
                              const uint8_t* ivs, const Block* ekj0, const Block* sets,
                              uint8_t* tags, uint8_t* ok, uint32_t* counter);
 
+constexpr uint32_t kSmallChunksPerGroup = 4;
+
+template <bool kDecrypt>
+__global__ void small_kernel(const KeyTables* kt, const ChunkDesc* chunks_host, uint32_t nchunks,
+                             const uint8_t* ivs, uint8_t* tags, uint8_t* ok);
+
 __global__ void upload_kernel(uint4* dst, const uint4* src_host, uint32_t n16);
 
 }  // namespace pgcm

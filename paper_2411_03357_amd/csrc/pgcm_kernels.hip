@@ -870,6 +870,176 @@ template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, 
                                             const uint8_t*, const Block*, const Block*, uint8_t*,
                                             uint8_t*, uint32_t*);
 
+// ------------------------------------------------------------------------------------------
+// The small-transfer path: a batch whose chunks are all at most kSmallChunkBytes long (the
+// paper's "other I/O", usually < 8 KB, and the 1-byte NOPs of its error handler, sections 4.2 and
+// 5.3) is done by ONE kernel, one wavefront per chunk from the first block to the tag, reading
+// its descriptor straight from pinned host memory: what matters here is the latency of the
+// call, not bandwidth.  LDS: the four round tables once (lookups may collide; there are few),
+// nibble tables of H^1 .. H^64.
+namespace {
+
+__device__ __forceinline__ void aes256_block_lds_plain(const uint32_t* __restrict__ rk,
+                                                       const uint32_t (*te)[256], uint32_t s[4]) {
+    uint32_t a0 = s[0] ^ rk[0], a1 = s[1] ^ rk[1], a2 = s[2] ^ rk[2], a3 = s[3] ^ rk[3];
+#pragma unroll
+    for (int r = 1; r < 14; ++r) {
+        uint32_t t0 = xor3(te[0][byte_of(a0, 0)], te[1][byte_of(a1, 1)], te[2][byte_of(a2, 2)]) ^
+                      te[3][byte_of(a3, 3)] ^ rk[4 * r + 0];
+        uint32_t t1 = xor3(te[0][byte_of(a1, 0)], te[1][byte_of(a2, 1)], te[2][byte_of(a3, 2)]) ^
+                      te[3][byte_of(a0, 3)] ^ rk[4 * r + 1];
+        uint32_t t2 = xor3(te[0][byte_of(a2, 0)], te[1][byte_of(a3, 1)], te[2][byte_of(a0, 2)]) ^
+                      te[3][byte_of(a1, 3)] ^ rk[4 * r + 2];
+        uint32_t t3 = xor3(te[0][byte_of(a3, 0)], te[1][byte_of(a0, 1)], te[2][byte_of(a1, 2)]) ^
+                      te[3][byte_of(a2, 3)] ^ rk[4 * r + 3];
+        a0 = t0, a1 = t1, a2 = t2, a3 = t3;
+    }
+    // last round: S(x) is byte 1 of te[0], byte 2 of te[1], byte 0 of te[2] and te[3]
+    auto last = [&](uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
+        uint32_t lo = __builtin_amdgcn_perm(te[0][byte_of(c0, 0)], te[1][byte_of(c1, 1)], 0x0c0c0205u);
+        uint32_t hi = __builtin_amdgcn_perm(te[2][byte_of(c2, 2)], te[3][byte_of(c3, 3)], 0x00040c0cu);
+        return lo | hi;
+    };
+    s[0] = last(a0, a1, a2, a3) ^ rk[56];
+    s[1] = last(a1, a2, a3, a0) ^ rk[57];
+    s[2] = last(a2, a3, a0, a1) ^ rk[58];
+    s[3] = last(a3, a0, a1, a2) ^ rk[59];
+}
+
+}  // namespace
+
+template <bool kDecrypt>
+__global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
+    const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks_host, uint32_t nchunks,
+    const uint8_t* __restrict__ ivs, uint8_t* __restrict__ tags, uint8_t* __restrict__ ok) {
+    __shared__ uint32_t te[4][256];
+    __shared__ Block tables[7][kNibbleTableEntries];  // H^(2^k), k = 0 .. 6
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    for (uint32_t i = tid; i < 4 * 256; i += blockDim.x) te[i >> 8][i & 255] = kt->te[i >> 8][i & 255];
+    for (uint32_t k = 0; k < 7; ++k) copy_power_table(tables[k], kt, k, tid, blockDim.x);
+    __syncthreads();
+
+    const uint32_t i = blockIdx.x * kSmallChunksPerGroup + (tid >> 6);
+    if (i >= nchunks) return;
+    const ChunkDesc cd = chunks_host[i];
+    const uint32_t* __restrict__ rk = kt->rk;
+
+    uint32_t y[4] = {0, 0, 0, 0};
+    Block aad_y{{0, 0, 0, 0}};
+    if (cd.aad_len != 0) aad_y = aad_hash(kt, cd.aad, cd.aad_len);
+    const uint8_t* ivp = ivs + (uint64_t)i * 12;
+    uint32_t iv[3];
+    for (int w = 0; w < 3; ++w)
+        iv[w] = (uint32_t)ivp[4 * w] | ((uint32_t)ivp[4 * w + 1] << 8) |
+                ((uint32_t)ivp[4 * w + 2] << 16) | ((uint32_t)ivp[4 * w + 3] << 24);
+
+    // rows of 64 blocks aligned to the chunk's end; "block -1" (counter 1, i.e. J0) rides along
+    const int64_t nblk = (int64_t)((cd.len + 15) / 16);
+    const uint32_t nrows = (uint32_t)((nblk + 1 + kRowBlocks - 1) / kRowBlocks);
+    int64_t blk = nblk - (int64_t)nrows * kRowBlocks + lane;
+    uint32_t mask[4] = {0, 0, 0, 0};  // E_K(J0), valid in the lane that holds block -1
+    for (uint32_t r = 0; r < nrows; ++r, blk += kRowBlocks) {
+        const bool active = blk >= 0;
+        uint32_t tail = 0;
+        if (active && (uint64_t)blk * 16 + 16 > cd.len) tail = (uint32_t)(cd.len & 15);
+        const bool whole = active && tail == 0;
+        uint32_t x[4] = {0, 0, 0, 0};
+        const uint8_t* sp = cd.src + blk * 16;
+        uint8_t* dp = cd.dst + blk * 16;
+        if (whole) {
+            u32x4 v = global_read128(sp);
+            x[0] = v.x, x[1] = v.y, x[2] = v.z, x[3] = v.w;
+        }
+        if (tail) {
+#pragma unroll
+            for (uint32_t b = 0; b < 15; ++b)
+                if (b < tail) x[b / 4] |= (uint32_t)sp[b] << (8 * (b % 4));
+        }
+        uint32_t s[4] = {iv[0], iv[1], iv[2], bswap32((uint32_t)blk + 2u)};
+        aes256_block_lds_plain(rk, te, s);
+        if (r > 0) ghash_mul_lds(lds_offset(tables[kRowPower]), y);
+        uint32_t o[4] = {x[0] ^ s[0], x[1] ^ s[1], x[2] ^ s[2], x[3] ^ s[3]};
+        if (whole) {
+            u32x4 v = {o[0], o[1], o[2], o[3]};
+            global_write128(dp, v);
+        }
+        if (tail) {
+#pragma unroll
+            for (uint32_t b = 0; b < 15; ++b)
+                if (b < tail) dp[b] = (uint8_t)(o[b / 4] >> (8 * (b % 4)));
+            // bytes past the end count as zero in the hash
+#pragma unroll
+            for (uint32_t b = 1; b < 16; ++b)
+                if (b >= tail) o[b / 4] &= ~(0xFFu << (8 * (b % 4)));
+        }
+        uint32_t c[4];
+        for (int w = 0; w < 4; ++w) c[w] = kDecrypt ? x[w] : o[w];
+        if (blk == 0)
+            for (int w = 0; w < 4; ++w) c[w] ^= aad_y.w[w];
+        if (blk == -1)
+            for (int w = 0; w < 4; ++w) mask[w] = s[w];
+        if (!active)
+            for (int w = 0; w < 4; ++w) c[w] = 0;
+        for (int w = 0; w < 4; ++w) y[w] ^= c[w];
+    }
+    // block -1 sits in the first row, in lane (rows * 64 - nblk - 1)
+    const int mask_lane = (int)((int64_t)nrows * kRowBlocks - nblk - 1);
+    for (int w = 0; w < 4; ++w) mask[w] = __shfl(mask[w], mask_lane, 64);
+
+    if (nblk == 0) {
+        // nothing was hashed yet: the state is what the AAD left
+        for (int w = 0; w < 4; ++w) y[w] = aad_y.w[w];
+    } else {
+        auto tree_step = [&](uint32_t k, uint32_t n0, uint32_t n1, uint32_t n2, uint32_t n3) {
+            ghash_mul_lds(lds_offset(tables[k]), y);
+            y[0] ^= n0, y[1] ^= n1, y[2] ^= n2, y[3] ^= n3;
+        };
+        tree_step(5, __shfl_down(y[0], 32, 64), __shfl_down(y[1], 32, 64),
+                  __shfl_down(y[2], 32, 64), __shfl_down(y[3], 32, 64));
+        tree_step(4, __shfl_down(y[0], 16, 64), __shfl_down(y[1], 16, 64),
+                  __shfl_down(y[2], 16, 64), __shfl_down(y[3], 16, 64));
+        tree_step(3, row_shift_down<8>(y[0]), row_shift_down<8>(y[1]), row_shift_down<8>(y[2]),
+                  row_shift_down<8>(y[3]));
+        tree_step(2, row_shift_down<4>(y[0]), row_shift_down<4>(y[1]), row_shift_down<4>(y[2]),
+                  row_shift_down<4>(y[3]));
+        tree_step(1, row_shift_down<2>(y[0]), row_shift_down<2>(y[1]), row_shift_down<2>(y[2]),
+                  row_shift_down<2>(y[3]));
+        tree_step(0, row_shift_down<1>(y[0]), row_shift_down<1>(y[1]), row_shift_down<1>(y[2]),
+                  row_shift_down<1>(y[3]));
+        ghash_mul_lds(lds_offset(tables[0]), y);
+        for (int k = 0; k < 4; ++k) y[k] = __builtin_amdgcn_readfirstlane(y[k]);
+    }
+    const uint64_t abits = (uint64_t)cd.aad_len * 8, cbits = cd.len * 8;
+    y[0] ^= bswap32((uint32_t)(abits >> 32));
+    y[1] ^= bswap32((uint32_t)abits);
+    y[2] ^= bswap32((uint32_t)(cbits >> 32));
+    y[3] ^= bswap32((uint32_t)cbits);
+    ghash_mul_lds(lds_offset(tables[0]), y);
+    const uint32_t t[4] = {y[0] ^ mask[0], y[1] ^ mask[1], y[2] ^ mask[2], y[3] ^ mask[3]};
+
+    uint8_t* tp = tags + (uint64_t)i * 16;
+    if (!kDecrypt) {
+        if (lane == 0)
+            for (int b = 0; b < 16; ++b) tp[b] = (uint8_t)(t[b / 4] >> (8 * (b % 4)));
+    } else {
+        uint32_t diff = 0;
+        for (int b = 0; b < 16; ++b) diff |= (uint32_t)tp[b] ^ ((t[b / 4] >> (8 * (b % 4))) & 0xFF);
+        diff = __builtin_amdgcn_readfirstlane(diff);
+        if (lane == 0) ok[i] = diff == 0 ? 1 : 0;
+        if (diff != 0) {
+            const uint64_t whole = cd.len / 16;
+            uint4* d = reinterpret_cast<uint4*>(cd.dst);
+            for (uint64_t b = lane; b < whole; b += 64) d[b] = make_uint4(0, 0, 0, 0);
+            for (uint64_t b = whole * 16 + lane; b < cd.len; b += 64) cd.dst[b] = 0;
+        }
+    }
+}
+
+template __global__ void small_kernel<false>(const KeyTables*, const ChunkDesc*, uint32_t,
+                                             const uint8_t*, uint8_t*, uint8_t*);
+template __global__ void small_kernel<true>(const KeyTables*, const ChunkDesc*, uint32_t,
+                                            const uint8_t*, uint8_t*, uint8_t*);
+
 // Brings a batch's descriptors from pinned host memory into the device workspace.  Done by a
 // kernel so that the batch stays on one hardware queue: a DMA copy between kernels costs two
 // cross-queue hand-overs.

@@ -66,6 +66,10 @@ struct alignas(16) FoldItem {
     uint32_t pad_;
 };
 
+// A batch whose chunks are all at most this long takes the small-transfer path: one kernel, one
+// wavefront per chunk (the paper's non-swap transfers are usually < 8 KB, section 4.2).
+constexpr uint64_t kSmallChunkBytes = 8192;
+
 // Items of the dynamic schedule are grabbed from a counter; to find an item's chunk a wavefront
 // starts at coarse_map[item >> kCoarseShift] and walks unit_base[] forward.
 constexpr uint32_t kCoarseShift = 4;

@@ -93,6 +93,33 @@ def test_ragged_edge_cases_full_parity():
                           (0, 0, 0, "tag")])
 
 
+def test_small_transfer_path_full_parity():
+    """batches made only of chunks of at most 8 KiB take the one-kernel path"""
+    w = workloads.small_transfers()
+    assert int(w.lens.max()) <= 8192
+    _full_parity(w, flip=[(0, 0, 0, "ct"), (12, 1023, 7, "ct"), (27, 8191, 0, "ct"),
+                          (1, 5, 1, "tag"), (20, 3, 2, "tag")])
+    # a single 1-byte transfer (the paper's NOP) and a single empty one
+    for n_bytes in (1, 0):
+        w1 = workloads.config1(n=1, size=n_bytes)
+        _full_parity(w1)
+
+
+def test_small_transfer_path_in_place():
+    w = workloads.small_transfers(seed_shift=2)
+    host = w.payload_host()
+    key = pgcm.expand_key(w.key)
+    b = DeviceBatch(w, torch.from_numpy(host).cuda())
+    work = b.plain.clone()
+    b.encrypt(key, src=work, dst=work)
+    b.decrypt(key, src=work, dst=work)
+    torch.cuda.synchronize()
+    assert torch.equal(work, b.plain) and bool((b.ok == 1).all())
+    cts, tags = _oracle_encrypt(w, host)
+    assert np.array_equal(b.tags.cpu().numpy().reshape(-1, 16), tags)
+    key.free()
+
+
 def test_no_aad_form_and_in_place():
     w = workloads.ragged_small(seed_shift=1)
     w.aad, w.aad_off = None, None

@@ -300,3 +300,21 @@ def swap_trace(kind: str, seed: int = 0, rounds: int = 6, noise: float = 0.0):
     else:
         raise ValueError(kind)
     return ev
+
+
+def small_transfers(seed_shift: int = 0) -> Workload:
+    """Only short chunks (at most 8 KiB: the paper's non-swap traffic and its 1-byte NOPs), every
+    length class of the block and row structure, AAD of assorted lengths."""
+    seed, rng, key, iv0 = _base(8, seed_shift)
+    lens = [1, 0, 15, 16, 17, 32, 33, 100, 1007, 1008, 1009, 1023, 1024, 1025, 1039, 1040, 1041,
+            2048, 2049, 4095, 4096, 4097, 5000, 8175, 8176, 8177, 8191, 8192, 7, 64]
+    alens = [0, 3, 0, 16, 17, 0, 64, 1, 0, 15, 0, 31, 0, 32, 0, 48, 0, 5, 200, 0, 16, 0, 9, 0, 0, 2,
+             0, 20, 0, 0]
+    assert len(lens) == len(alens)
+    lens = np.array(lens, np.uint64)
+    offsets, total = _layout(lens)
+    aad_off = np.zeros(len(alens) + 1, np.uint64)
+    aad_off[1:] = np.cumsum(alens)
+    aad = rng.integers(0, 256, int(sum(alens)), dtype=np.uint8)
+    return Workload("small_transfers", seed, key, iv_sequence(iv0, lens.size), lens, offsets,
+                    total, "u8", aad, aad_off)
