@@ -1,7 +1,7 @@
 /*
- * AES-256-GCM oracle: test infrastructure, not product code.
+ * AES-GCM oracle (AES-128/192/256, any IV length): test infrastructure, not product code.
  *
- * A plain, slow, byte-at-a-time AES-256 and bit-at-a-time GHASH written from
+ * A plain, slow, byte-at-a-time AES and bit-at-a-time GHASH written from
  * the public definitions (FIPS-197 for the block cipher, NIST SP 800-38D for
  * GCM).  It is what the paper's transport computes per transfer: one AES-GCM
  * invocation with a key and a unique IV (paper section 2.2, "A closer look at
@@ -78,18 +78,23 @@ void orc_sbox(uint8_t out[256])
 }
 
 /* ------------------------------------------------------------------ */
-/* AES-256: Nk = 8 words, Nr = 14 rounds, 15 round keys (FIPS-197 5.2)  */
+/* AES key expansion for Nk = 4, 6, 8 words: Nr = Nk + 6 rounds, Nr + 1 round keys
+ * (FIPS-197 5.2).  The paper's transport uses Nk = 8.                     */
 
-/* rk receives 60 words as 240 bytes, word i at rk[4i..4i+3] in key byte order */
-void orc_aes256_key_expand(const uint8_t key[32], uint8_t rk[240])
+/* rk receives 4 (Nr + 1) words, word i at rk[4i..4i+3] in key byte order; returns Nr, or 0 when
+ * key_bytes is not 16, 24 or 32 */
+int orc_aes_key_expand(const uint8_t *key, int key_bytes, uint8_t rk[240])
 {
     const uint8_t *S = sbox();
-    memcpy(rk, key, 32);
+    if (key_bytes != 16 && key_bytes != 24 && key_bytes != 32)
+        return 0;
+    int nk = key_bytes / 4, nr = nk + 6;
+    memcpy(rk, key, (size_t)key_bytes);
     uint8_t rcon = 0x01;
-    for (int i = 8; i < 60; i++) {
+    for (int i = nk; i < 4 * (nr + 1); i++) {
         uint8_t t[4];
         memcpy(t, rk + 4 * (i - 1), 4);
-        if (i % 8 == 0) {
+        if (i % nk == 0) {
             /* RotWord then SubWord then Rcon on the first byte */
             uint8_t t0 = t[0];
             t[0] = S[t[1]] ^ rcon;
@@ -97,17 +102,23 @@ void orc_aes256_key_expand(const uint8_t key[32], uint8_t rk[240])
             t[2] = S[t[3]];
             t[3] = S[t0];
             rcon = gf8_mul(rcon, 2);
-        } else if (i % 8 == 4) {
+        } else if (nk > 6 && i % nk == 4) {
             for (int k = 0; k < 4; k++)
                 t[k] = S[t[k]];
         }
         for (int k = 0; k < 4; k++)
-            rk[4 * i + k] = rk[4 * (i - 8) + k] ^ t[k];
+            rk[4 * i + k] = rk[4 * (i - nk) + k] ^ t[k];
     }
+    return nr;
+}
+
+void orc_aes256_key_expand(const uint8_t key[32], uint8_t rk[240])
+{
+    (void)orc_aes_key_expand(key, 32, rk);
 }
 
 /* state s[r][c] = in[r + 4c] (FIPS-197 3.4) */
-void orc_aes256_encrypt_block(const uint8_t rk[240], const uint8_t in[16], uint8_t out[16])
+void orc_aes_encrypt_block(const uint8_t rk[240], int nr, const uint8_t in[16], uint8_t out[16])
 {
     const uint8_t *S = sbox();
     uint8_t s[4][4];
@@ -115,7 +126,7 @@ void orc_aes256_encrypt_block(const uint8_t rk[240], const uint8_t in[16], uint8
         for (int r = 0; r < 4; r++)
             s[r][c] = in[r + 4 * c] ^ rk[r + 4 * c];
 
-    for (int round = 1; round <= 14; round++) {
+    for (int round = 1; round <= nr; round++) {
         /* SubBytes */
         for (int r = 0; r < 4; r++)
             for (int c = 0; c < 4; c++)
@@ -129,7 +140,7 @@ void orc_aes256_encrypt_block(const uint8_t rk[240], const uint8_t in[16], uint8
                 s[r][c] = row[c];
         }
         /* MixColumns, skipped in the last round */
-        if (round != 14) {
+        if (round != nr) {
             for (int c = 0; c < 4; c++) {
                 uint8_t a0 = s[0][c], a1 = s[1][c], a2 = s[2][c], a3 = s[3][c];
                 s[0][c] = gf8_mul(a0, 2) ^ gf8_mul(a1, 3) ^ a2 ^ a3;
@@ -146,6 +157,11 @@ void orc_aes256_encrypt_block(const uint8_t rk[240], const uint8_t in[16], uint8
     for (int c = 0; c < 4; c++)
         for (int r = 0; r < 4; r++)
             out[r + 4 * c] = s[r][c];
+}
+
+void orc_aes256_encrypt_block(const uint8_t rk[240], const uint8_t in[16], uint8_t out[16])
+{
+    orc_aes_encrypt_block(rk, 14, in, out);
 }
 
 /* ------------------------------------------------------------------ */
@@ -209,78 +225,148 @@ static void be64(uint64_t v, uint8_t out[8])
 }
 
 /* ------------------------------------------------------------------ */
-/* GCM with a 96-bit IV (SP 800-38D 7.1, 7.2)                           */
+/* GCM (SP 800-38D 7.1, 7.2)                                             */
 
-/* counter block number j of the invocation: IV || [j]_32, big endian */
-static void counter_block(const uint8_t iv[12], uint32_t j, uint8_t cb[16])
+typedef struct {
+    uint8_t rk[240];
+    int nr;
+    uint8_t h[16];
+} gcm_key;
+
+static int gcm_key_init(gcm_key *k, const uint8_t *key, int key_bytes)
 {
-    memcpy(cb, iv, 12);
-    cb[12] = (uint8_t)(j >> 24);
-    cb[13] = (uint8_t)(j >> 16);
-    cb[14] = (uint8_t)(j >> 8);
-    cb[15] = (uint8_t)j;
+    uint8_t zero[16] = {0};
+    k->nr = orc_aes_key_expand(key, key_bytes, k->rk);
+    if (k->nr == 0)
+        return 0;
+    orc_aes_encrypt_block(k->rk, k->nr, zero, k->h);
+    return 1;
 }
 
-/* out = in xor keystream, keystream block b (0-based) = E_K(IV || [b+2]_32) */
-void orc_gctr(const uint8_t rk[240], const uint8_t iv[12], const uint8_t *in, uint64_t len,
-              uint8_t *out)
+/* pre-counter block J0 (7.1 step 2): IV || 0^31 1 for a 96-bit IV, otherwise
+ * GHASH_H(IV || 0-pad || 0^64 || [8 |IV|]_64) */
+static void gcm_j0(const gcm_key *k, const uint8_t *iv, uint64_t iv_bytes, uint8_t j0[16])
 {
-    uint32_t ctr = 2;
+    if (iv_bytes == 12) {
+        memcpy(j0, iv, 12);
+        j0[12] = 0, j0[13] = 0, j0[14] = 0, j0[15] = 1;
+        return;
+    }
+    uint8_t lens[16] = {0};
+    memset(j0, 0, 16);
+    ghash_padded(k->h, iv, iv_bytes, j0);
+    be64(8 * iv_bytes, lens + 8);
+    orc_ghash_update(k->h, lens, 1, j0);
+}
+
+/* inc32^n: the last 32 bits of the block, as a big-endian integer, plus n modulo 2^32 */
+static void counter_block(const uint8_t j0[16], uint32_t n, uint8_t cb[16])
+{
+    uint32_t c = ((uint32_t)j0[12] << 24) | ((uint32_t)j0[13] << 16) | ((uint32_t)j0[14] << 8) |
+                 (uint32_t)j0[15];
+    c += n; /* wraps modulo 2^32 */
+    memcpy(cb, j0, 12);
+    cb[12] = (uint8_t)(c >> 24);
+    cb[13] = (uint8_t)(c >> 16);
+    cb[14] = (uint8_t)(c >> 8);
+    cb[15] = (uint8_t)c;
+}
+
+/* GCTR from inc32(J0): out = in xor keystream, keystream block b (0-based) = E_K(inc32^(b+1)(J0)) */
+static void gctr(const gcm_key *k, const uint8_t j0[16], const uint8_t *in, uint64_t len,
+                 uint8_t *out)
+{
+    uint32_t n = 1;
     for (uint64_t off = 0; off < len; off += 16) {
         uint8_t cb[16], ks[16];
-        counter_block(iv, ctr, cb);
-        orc_aes256_encrypt_block(rk, cb, ks);
-        uint64_t n = len - off < 16 ? len - off : 16;
-        for (uint64_t k = 0; k < n; k++)
-            out[off + k] = in[off + k] ^ ks[k];
-        ctr++; /* inc32: wraps modulo 2^32 */
+        counter_block(j0, n, cb);
+        orc_aes_encrypt_block(k->rk, k->nr, cb, ks);
+        uint64_t m = len - off < 16 ? len - off : 16;
+        for (uint64_t i = 0; i < m; i++)
+            out[off + i] = in[off + i] ^ ks[i];
+        n++;
     }
 }
 
-/* T = GHASH_H(A || pad || C || pad || [8|A|]_64 || [8|C|]_64) xor E_K(IV || 0^31 1) */
-static void gcm_tag(const uint8_t rk[240], const uint8_t iv[12], const uint8_t *aad, uint64_t alen,
+/* 96-bit IV form kept for the tests that exercise the keystream alone */
+void orc_gctr(const uint8_t rk[240], const uint8_t iv[12], const uint8_t *in, uint64_t len,
+              uint8_t *out)
+{
+    gcm_key k;
+    uint8_t j0[16];
+    memcpy(k.rk, rk, 240);
+    k.nr = 14;
+    memcpy(j0, iv, 12);
+    j0[12] = 0, j0[13] = 0, j0[14] = 0, j0[15] = 1;
+    gctr(&k, j0, in, len, out);
+}
+
+/* T = GHASH_H(A || pad || C || pad || [8|A|]_64 || [8|C|]_64) xor E_K(J0) */
+static void gcm_tag(const gcm_key *k, const uint8_t j0[16], const uint8_t *aad, uint64_t alen,
                     const uint8_t *ct, uint64_t len, uint8_t tag[16])
 {
-    uint8_t zero[16] = {0}, h[16], y[16] = {0}, lens[16], j0[16], ekj0[16];
-    orc_aes256_encrypt_block(rk, zero, h);
-    ghash_padded(h, aad, alen, y);
-    ghash_padded(h, ct, len, y);
+    uint8_t y[16] = {0}, lens[16], ekj0[16];
+    ghash_padded(k->h, aad, alen, y);
+    ghash_padded(k->h, ct, len, y);
     be64(8 * alen, lens);
     be64(8 * len, lens + 8);
-    orc_ghash_update(h, lens, 1, y);
-    counter_block(iv, 1, j0);
-    orc_aes256_encrypt_block(rk, j0, ekj0);
-    for (int k = 0; k < 16; k++)
-        tag[k] = y[k] ^ ekj0[k];
+    orc_ghash_update(k->h, lens, 1, y);
+    orc_aes_encrypt_block(k->rk, k->nr, j0, ekj0);
+    for (int i = 0; i < 16; i++)
+        tag[i] = y[i] ^ ekj0[i];
+}
+
+/* returns 0 for an unsupported key length or an empty IV, else 1 */
+int orc_gcm_encrypt_ex(const uint8_t *key, int key_bytes, const uint8_t *iv, uint64_t iv_bytes,
+                       const uint8_t *aad, uint64_t alen, const uint8_t *pt, uint64_t len,
+                       uint8_t *ct, uint8_t tag[16])
+{
+    gcm_key k;
+    uint8_t j0[16];
+    if (!gcm_key_init(&k, key, key_bytes) || iv_bytes == 0)
+        return 0;
+    gcm_j0(&k, iv, iv_bytes, j0);
+    gctr(&k, j0, pt, len, ct);
+    gcm_tag(&k, j0, aad, alen, ct, len, tag);
+    return 1;
+}
+
+/* returns 1 and the plaintext when the tag matches; otherwise returns 0 and
+ * writes len zero bytes: unauthenticated plaintext is never released */
+int orc_gcm_decrypt_verify_ex(const uint8_t *key, int key_bytes, const uint8_t *iv,
+                              uint64_t iv_bytes, const uint8_t *aad, uint64_t alen,
+                              const uint8_t *ct, uint64_t len, const uint8_t tag[16], uint8_t *pt)
+{
+    gcm_key k;
+    uint8_t j0[16], expect[16];
+    if (!gcm_key_init(&k, key, key_bytes) || iv_bytes == 0) {
+        memset(pt, 0, (size_t)len);
+        return 0;
+    }
+    gcm_j0(&k, iv, iv_bytes, j0);
+    gcm_tag(&k, j0, aad, alen, ct, len, expect);
+    uint8_t diff = 0;
+    for (int i = 0; i < 16; i++) /* all 16 bytes, no early exit */
+        diff |= (uint8_t)(expect[i] ^ tag[i]);
+    if (diff != 0) {
+        memset(pt, 0, (size_t)len);
+        return 0;
+    }
+    gctr(&k, j0, ct, len, pt);
+    return 1;
 }
 
 void orc_gcm_encrypt(const uint8_t key[32], const uint8_t iv[12], const uint8_t *aad,
                      uint64_t alen, const uint8_t *pt, uint64_t len, uint8_t *ct, uint8_t tag[16])
 {
-    uint8_t rk[240];
-    orc_aes256_key_expand(key, rk);
-    orc_gctr(rk, iv, pt, len, ct);
-    gcm_tag(rk, iv, aad, alen, ct, len, tag);
+    (void)orc_gcm_encrypt_ex(key, 32, iv, 12, aad, alen, pt, len, ct, tag);
 }
 
-/* returns 1 and the plaintext when the tag matches; otherwise returns 0 and
- * writes len zero bytes: unauthenticated plaintext is never released */
 int orc_gcm_decrypt_verify(const uint8_t key[32], const uint8_t iv[12], const uint8_t *aad,
                            uint64_t alen, const uint8_t *ct, uint64_t len, const uint8_t tag[16],
                            uint8_t *pt)
 {
-    uint8_t rk[240], expect[16];
-    orc_aes256_key_expand(key, rk);
-    gcm_tag(rk, iv, aad, alen, ct, len, expect);
-    uint8_t diff = 0;
-    for (int k = 0; k < 16; k++) /* all 16 bytes, no early exit */
-        diff |= (uint8_t)(expect[k] ^ tag[k]);
-    if (diff != 0) {
-        memset(pt, 0, (size_t)len);
-        return 0;
-    }
-    orc_gctr(rk, iv, ct, len, pt);
-    return 1;
+    return orc_gcm_decrypt_verify_ex(key, 32, iv, 12, aad, alen, ct, len, tag, pt);
 }
 
 /* ------------------------------------------------------------------ */
@@ -289,8 +375,10 @@ int orc_gcm_decrypt_verify(const uint8_t key[32], const uint8_t iv[12], const ui
 typedef struct {
     int decrypt;
     const uint8_t *key;
+    int key_bytes;
+    uint64_t iv_bytes;
     size_t n;
-    const uint8_t *ivs;           /* n * 12 bytes */
+    const uint8_t *ivs;           /* n * iv_bytes bytes */
     const uint8_t *const *aad;    /* may be NULL */
     const uint32_t *aad_len;      /* may be NULL */
     const uint8_t *const *src;
@@ -313,13 +401,15 @@ static void *batch_worker(void *arg)
             return NULL;
         const uint8_t *a = job->aad_len ? job->aad[i] : NULL;
         uint64_t alen = job->aad_len ? job->aad_len[i] : 0;
+        const uint8_t *iv = job->ivs + job->iv_bytes * i;
         if (job->decrypt)
-            job->ok[i] = (uint8_t)orc_gcm_decrypt_verify(job->key, job->ivs + 12 * i, a, alen,
-                                                         job->src[i], job->len[i],
-                                                         job->tags + 16 * i, job->dst[i]);
+            job->ok[i] = (uint8_t)orc_gcm_decrypt_verify_ex(job->key, job->key_bytes, iv,
+                                                            job->iv_bytes, a, alen, job->src[i],
+                                                            job->len[i], job->tags + 16 * i,
+                                                            job->dst[i]);
         else
-            orc_gcm_encrypt(job->key, job->ivs + 12 * i, a, alen, job->src[i], job->len[i],
-                            job->dst[i], job->tags + 16 * i);
+            (void)orc_gcm_encrypt_ex(job->key, job->key_bytes, iv, job->iv_bytes, a, alen,
+                                     job->src[i], job->len[i], job->dst[i], job->tags + 16 * i);
     }
 }
 
@@ -347,14 +437,34 @@ static int run_batch(batch_job *job, int nthreads)
     return started + 1; /* threads that actually worked */
 }
 
+int orc_gcm_encrypt_batch_ex(const uint8_t *key, int key_bytes, uint64_t iv_bytes, size_t n,
+                             const uint8_t *ivs, const uint8_t *const *aad,
+                             const uint32_t *aad_len, const uint8_t *const *src,
+                             const uint64_t *len, uint8_t *const *dst, uint8_t *tags, int nthreads)
+{
+    batch_job job = {0, key, key_bytes, iv_bytes, n, ivs, aad, aad_len, src, len, dst, tags, NULL,
+                     0, PTHREAD_MUTEX_INITIALIZER};
+    return run_batch(&job, nthreads);
+}
+
+int orc_gcm_decrypt_verify_batch_ex(const uint8_t *key, int key_bytes, uint64_t iv_bytes, size_t n,
+                                    const uint8_t *ivs, const uint8_t *const *aad,
+                                    const uint32_t *aad_len, const uint8_t *const *src,
+                                    const uint64_t *len, uint8_t *const *dst, const uint8_t *tags,
+                                    uint8_t *ok, int nthreads)
+{
+    batch_job job = {1, key, key_bytes, iv_bytes, n, ivs, aad, aad_len, src, len, dst,
+                     (uint8_t *)tags, ok, 0, PTHREAD_MUTEX_INITIALIZER};
+    return run_batch(&job, nthreads);
+}
+
 int orc_gcm_encrypt_batch(const uint8_t key[32], size_t n, const uint8_t *ivs,
                           const uint8_t *const *aad, const uint32_t *aad_len,
                           const uint8_t *const *src, const uint64_t *len, uint8_t *const *dst,
                           uint8_t *tags, int nthreads)
 {
-    batch_job job = {0, key, n, ivs, aad, aad_len, src, len, dst, tags, NULL, 0,
-                     PTHREAD_MUTEX_INITIALIZER};
-    return run_batch(&job, nthreads);
+    return orc_gcm_encrypt_batch_ex(key, 32, 12, n, ivs, aad, aad_len, src, len, dst, tags,
+                                    nthreads);
 }
 
 int orc_gcm_decrypt_verify_batch(const uint8_t key[32], size_t n, const uint8_t *ivs,
@@ -363,7 +473,6 @@ int orc_gcm_decrypt_verify_batch(const uint8_t key[32], size_t n, const uint8_t 
                                  uint8_t *const *dst, const uint8_t *tags, uint8_t *ok,
                                  int nthreads)
 {
-    batch_job job = {1, key, n, ivs, aad, aad_len, src, len, dst, (uint8_t *)tags, ok, 0,
-                     PTHREAD_MUTEX_INITIALIZER};
-    return run_batch(&job, nthreads);
+    return orc_gcm_decrypt_verify_batch_ex(key, 32, 12, n, ivs, aad, aad_len, src, len, dst, tags,
+                                           ok, nthreads);
 }

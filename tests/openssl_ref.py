@@ -1,4 +1,4 @@
-"""AES-256-GCM from the host's libcrypto (EVP interface) through ctypes.
+"""AES-GCM (128-, 192-, 256-bit keys, any IV length) from the host's libcrypto (EVP interface) through ctypes.
 
 An implementation independent of both the oracle and the GPU library, used by tests as a
 second opinion.  The paper's own CPU side calls this same library (section 6).
@@ -13,8 +13,9 @@ _lc = C.CDLL(_name)
 
 _lc.EVP_CIPHER_CTX_new.restype = C.c_void_p
 _lc.EVP_CIPHER_CTX_free.argtypes = [C.c_void_p]
-_lc.EVP_aes_256_gcm.restype = C.c_void_p
-_lc.EVP_aes_256_ecb.restype = C.c_void_p
+for _bits in (128, 192, 256):
+    getattr(_lc, "EVP_aes_%d_gcm" % _bits).restype = C.c_void_p
+    getattr(_lc, "EVP_aes_%d_ecb" % _bits).restype = C.c_void_p
 for _f in ("EVP_EncryptInit_ex", "EVP_DecryptInit_ex"):
     getattr(_lc, _f).argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_char_p, C.c_char_p]
 for _f in ("EVP_EncryptUpdate", "EVP_DecryptUpdate"):
@@ -26,6 +27,10 @@ _lc.EVP_CIPHER_CTX_set_padding.argtypes = [C.c_void_p, C.c_int]
 
 _SET_IVLEN, _GET_TAG, _SET_TAG = 0x9, 0x10, 0x11
 _STEP = 1 << 30  # EVP lengths are ints
+
+
+def _cipher(key, mode):
+    return getattr(_lc, "EVP_aes_%d_%s" % (8 * len(key), mode))()
 
 
 def _check(rc, what):
@@ -49,7 +54,7 @@ def _update(fn, ctx, out_addr, data):
 def encrypt(key: bytes, iv: bytes, aad: bytes, pt: bytes):
     ctx = _lc.EVP_CIPHER_CTX_new()
     try:
-        _check(_lc.EVP_EncryptInit_ex(ctx, _lc.EVP_aes_256_gcm(), None, None, None), "init")
+        _check(_lc.EVP_EncryptInit_ex(ctx, _cipher(key, "gcm"), None, None, None), "init")
         _check(_lc.EVP_CIPHER_CTX_ctrl(ctx, _SET_IVLEN, len(iv), None), "ivlen")
         _check(_lc.EVP_EncryptInit_ex(ctx, None, None, bytes(key), bytes(iv)), "key")
         if len(aad):
@@ -71,7 +76,7 @@ def decrypt_verify(key: bytes, iv: bytes, aad: bytes, ct: bytes, tag: bytes):
     """-> (ok, plaintext or None)"""
     ctx = _lc.EVP_CIPHER_CTX_new()
     try:
-        _check(_lc.EVP_DecryptInit_ex(ctx, _lc.EVP_aes_256_gcm(), None, None, None), "init")
+        _check(_lc.EVP_DecryptInit_ex(ctx, _cipher(key, "gcm"), None, None, None), "init")
         _check(_lc.EVP_CIPHER_CTX_ctrl(ctx, _SET_IVLEN, len(iv), None), "ivlen")
         _check(_lc.EVP_DecryptInit_ex(ctx, None, None, bytes(key), bytes(iv)), "key")
         if len(aad):
@@ -89,10 +94,10 @@ def decrypt_verify(key: bytes, iv: bytes, aad: bytes, ct: bytes, tag: bytes):
         _lc.EVP_CIPHER_CTX_free(ctx)
 
 
-def aes256_ecb_block(key: bytes, block: bytes) -> bytes:
+def aes_ecb_block(key: bytes, block: bytes) -> bytes:
     ctx = _lc.EVP_CIPHER_CTX_new()
     try:
-        _check(_lc.EVP_EncryptInit_ex(ctx, _lc.EVP_aes_256_ecb(), None, bytes(key), None), "init")
+        _check(_lc.EVP_EncryptInit_ex(ctx, _cipher(key, "ecb"), None, bytes(key), None), "init")
         _lc.EVP_CIPHER_CTX_set_padding(ctx, 0)
         out = C.create_string_buffer(32)
         n = C.c_int(0)
@@ -100,3 +105,6 @@ def aes256_ecb_block(key: bytes, block: bytes) -> bytes:
         return out.raw[:16]
     finally:
         _lc.EVP_CIPHER_CTX_free(ctx)
+
+
+aes256_ecb_block = aes_ecb_block

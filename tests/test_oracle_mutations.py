@@ -19,36 +19,51 @@ MUTANTS = [
     ("sbox affine tap", "((b >> ((i + 4) % 8)) & 1)", "((b >> ((i + 3) % 8)) & 1)"),
     ("gf8 reduction polynomial", "a ^= 0x1B;", "a ^= 0x1D;"),
     ("rcon start", "uint8_t rcon = 0x01;", "uint8_t rcon = 0x02;"),
-    ("key schedule: SubWord at i%8==4 dropped", "} else if (i % 8 == 4) {", "} else if (i % 8 == 9) {"),
+    ("key schedule: SubWord at i%Nk==4 dropped", "} else if (nk > 6 && i % nk == 4) {",
+     "} else if (nk > 6 && i % nk == 9) {"),
+    ("key schedule: SubWord at i%Nk==4 for 192-bit keys too", "} else if (nk > 6 && i % nk == 4) {",
+     "} else if (nk >= 6 && i % nk == 4) {"),
+    ("key schedule: one round too few", "nr = nk + 6;", "nr = nk + 5;"),
     ("RotWord direction", "t[0] = S[t[1]] ^ rcon;\n            t[1] = S[t[2]];\n            t[2] = S[t[3]];\n            t[3] = S[t0];",
      "t[0] = S[t[3]] ^ rcon;\n            t[3] = S[t[2]];\n            t[2] = S[t[1]];\n            t[1] = S[t0];"),
     ("state is row-major", "s[r][c] = in[r + 4 * c] ^ rk[r + 4 * c];", "s[r][c] = in[4 * r + c] ^ rk[4 * r + c];"),
     ("ShiftRows rotates right", "row[c] = s[r][(c + r) % 4];", "row[c] = s[r][(c + 4 - r) % 4];"),
     ("MixColumns coefficients swapped", "s[0][c] = gf8_mul(a0, 2) ^ gf8_mul(a1, 3) ^ a2 ^ a3;",
      "s[0][c] = gf8_mul(a0, 3) ^ gf8_mul(a1, 2) ^ a2 ^ a3;"),
-    ("MixColumns in the last round too", "if (round != 14) {", "if (round != 15) {"),
-    ("thirteen rounds", "for (int round = 1; round <= 14; round++) {", "for (int round = 1; round <= 13; round++) {"),
+    ("MixColumns in the last round too", "if (round != nr) {", "if (round != nr + 1) {"),
+    ("last round missing", "for (int round = 1; round <= nr; round++) {", "for (int round = 1; round < nr; round++) {"),
     ("gf128 bit order", "return (b[i / 8] >> (7 - (i % 8))) & 1;", "return (b[i / 8] >> (i % 8)) & 1;"),
     ("gf128 reduction constant", "v[0] ^= 0xE1;", "v[0] ^= 0x87;"),
     ("gf128 shift loses the carry between bytes", "v[k] = (uint8_t)((v[k] >> 1) | ((v[k - 1] & 1) << 7));",
      "v[k] = (uint8_t)(v[k] >> 1);"),
     ("ghash multiplies before adding", "t[k] = y[k] ^ x[16 * i + k];\n        orc_gf128_mul(t, h, y);",
      "t[k] = y[k];\n        orc_gf128_mul(t, h, y);\n        for (int k = 0; k < 16; k++) y[k] ^= x[16 * i + k];"),
-    ("counter starts at 1", "uint32_t ctr = 2;", "uint32_t ctr = 1;"),
-    ("counter little endian", "cb[12] = (uint8_t)(j >> 24);\n    cb[13] = (uint8_t)(j >> 16);\n    cb[14] = (uint8_t)(j >> 8);\n    cb[15] = (uint8_t)j;",
-     "cb[15] = (uint8_t)(j >> 24);\n    cb[14] = (uint8_t)(j >> 16);\n    cb[13] = (uint8_t)(j >> 8);\n    cb[12] = (uint8_t)j;"),
-    ("J0 counter is 0", "counter_block(iv, 1, j0);", "counter_block(iv, 0, j0);"),
+    ("first data block uses J0 itself", "uint32_t n = 1;", "uint32_t n = 0;"),
+    ("counter little endian", "cb[12] = (uint8_t)(c >> 24);\n    cb[13] = (uint8_t)(c >> 16);\n    cb[14] = (uint8_t)(c >> 8);\n    cb[15] = (uint8_t)c;",
+     "cb[15] = (uint8_t)(c >> 24);\n    cb[14] = (uint8_t)(c >> 16);\n    cb[13] = (uint8_t)(c >> 8);\n    cb[12] = (uint8_t)c;"),
+    ("counter wrap carries into the rest of the block", "memcpy(cb, j0, 12);\n    cb[12]",
+     "memcpy(cb, j0, 12);\n    if (c < n) cb[11]++;\n    cb[12]"),
+    ("counter saturates instead of wrapping", "c += n; /* wraps modulo 2^32 */",
+     "c = (c + n < c) ? 0xFFFFFFFFu : c + n;"),
+    ("J0 of a 96-bit IV ends in 0", "j0[12] = 0, j0[13] = 0, j0[14] = 0, j0[15] = 1;\n        return;",
+     "j0[12] = 0, j0[13] = 0, j0[14] = 0, j0[15] = 0;\n        return;"),
+    ("J0: IV length in the wrong half of its block", "be64(8 * iv_bytes, lens + 8);", "be64(8 * iv_bytes, lens);"),
+    ("J0: IV length in bytes", "be64(8 * iv_bytes, lens + 8);", "be64(iv_bytes, lens + 8);"),
+    ("J0: length block left out", "orc_ghash_update(k->h, lens, 1, j0);", ";"),
+    ("J0: IV not padded to a block", "ghash_padded(k->h, iv, iv_bytes, j0);",
+     "orc_ghash_update(k->h, iv, (size_t)(iv_bytes / 16), j0);"),
     ("length block order", "be64(8 * alen, lens);\n    be64(8 * len, lens + 8);", "be64(8 * len, lens);\n    be64(8 * alen, lens + 8);"),
     ("lengths in bytes not bits", "be64(8 * len, lens + 8);", "be64(len, lens + 8);"),
     ("lengths little endian", "out[i] = (uint8_t)(v >> (56 - 8 * i));", "out[i] = (uint8_t)(v >> (8 * i));"),
-    ("AAD hashed after the ciphertext", "ghash_padded(h, aad, alen, y);\n    ghash_padded(h, ct, len, y);",
-     "ghash_padded(h, ct, len, y);\n    ghash_padded(h, aad, alen, y);"),
+    ("AAD hashed after the ciphertext", "ghash_padded(k->h, aad, alen, y);\n    ghash_padded(k->h, ct, len, y);",
+     "ghash_padded(k->h, ct, len, y);\n    ghash_padded(k->h, aad, alen, y);"),
     ("partial block not hashed", "if (len % 16) {\n        uint8_t last[16] = {0};", "if (len % 16 > 16) {\n        uint8_t last[16] = {0};"),
-    ("tag hashes the plaintext", "gcm_tag(rk, iv, aad, alen, ct, len, tag);\n}", "gcm_tag(rk, iv, aad, alen, pt, len, tag);\n}"),
-    ("tag not masked", "tag[k] = y[k] ^ ekj0[k];", "tag[k] = y[k];"),
-    ("compare skips the last byte", "for (int k = 0; k < 16; k++) /* all 16 bytes, no early exit */", "for (int k = 0; k < 15; k++) /* mutated */"),
-    ("rejected output not wiped", "memset(pt, 0, (size_t)len);\n        return 0;", "orc_gctr(rk, iv, ct, len, pt);\n        return 0;"),
-    ("H is E_K of ones", "uint8_t zero[16] = {0}, h[16]", "uint8_t zero[16] = {1}, h[16]"),
+    ("tag hashes the plaintext", "gcm_tag(&k, j0, aad, alen, ct, len, tag);\n    return 1;", "gcm_tag(&k, j0, aad, alen, pt, len, tag);\n    return 1;"),
+    ("tag not masked", "tag[i] = y[i] ^ ekj0[i];", "tag[i] = y[i];"),
+    ("compare skips the last byte", "for (int i = 0; i < 16; i++) /* all 16 bytes, no early exit */", "for (int i = 0; i < 15; i++) /* mutated */"),
+    ("rejected output not wiped", "if (diff != 0) {\n        memset(pt, 0, (size_t)len);\n        return 0;",
+     "if (diff != 0) {\n        gctr(&k, j0, ct, len, pt);\n        return 0;"),
+    ("H is E_K of ones", "uint8_t zero[16] = {0};\n    k->nr", "uint8_t zero[16] = {1};\n    k->nr"),
 ]
 
 PIN_TESTS = [
@@ -59,6 +74,7 @@ PIN_TESTS = [
     pins.test_ghash_is_the_polynomial_in_h,
     pins.test_gcm_published_vectors,
     pins.test_gcm_closed_forms_from_the_block_cipher,
+    pins.test_pre_counter_block_of_other_iv_lengths_and_counter_wrap,
     pins.test_every_single_bit_flip_is_rejected_and_output_is_wiped,
     pins.test_gcm_invariants,
 ]

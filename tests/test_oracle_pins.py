@@ -53,25 +53,34 @@ def test_sbox_against_log_tables_and_printed_entries():
 
 
 def test_block_cipher_and_key_schedule_worked_examples():
+    seen = set()
     for rec in _records("aes256_block_vectors.txt"):
+        key = _hex(rec[1])
+        seen.add((rec[0], len(key)))
         if rec[0] == "block":
-            assert oracle.aes256_encrypt_block(_hex(rec[1]), _hex(rec[2])) == _hex(rec[3])
+            assert oracle.aes_encrypt_block(key, _hex(rec[2])) == _hex(rec[3])
         elif rec[0] == "hzero":
-            assert oracle.aes256_encrypt_block(_hex(rec[1]), bytes(16)) == _hex(rec[2])
+            assert oracle.aes_encrypt_block(key, bytes(16)) == _hex(rec[2])
         elif rec[0] == "rkeys":
-            rk = oracle.aes256_key_expand(_hex(rec[1]))
+            rk = oracle.aes_key_expand(key)
+            assert len(rk) == 16 * (len(key) // 4 + 7)
             first = int(rec[2])
             words = _hex(rec[3])
             assert rk[4 * first:4 * first + len(words)] == words
-            assert rk[:32] == _hex(rec[1])
+            assert rk[:len(key)] == key
+        if len(key) == 32 and rec[0] == "block":
+            assert oracle.aes256_encrypt_block(key, _hex(rec[2])) == _hex(rec[3])
+            assert oracle.aes256_key_expand(key) == oracle.aes_key_expand(key)
+    assert {("block", 16), ("block", 24), ("block", 32), ("rkeys", 16), ("rkeys", 24),
+            ("rkeys", 32)} <= seen
 
 
 def test_block_cipher_against_libcrypto_ecb():
     rng = np.random.default_rng(11)
-    for _ in range(300):
-        k = rng.integers(0, 256, 32, dtype=np.uint8).tobytes()
+    for i in range(450):
+        k = rng.integers(0, 256, (16, 24, 32)[i % 3], dtype=np.uint8).tobytes()
         b = rng.integers(0, 256, 16, dtype=np.uint8).tobytes()
-        assert oracle.aes256_encrypt_block(k, b) == openssl_ref.aes256_ecb_block(k, b)
+        assert oracle.aes_encrypt_block(k, b) == openssl_ref.aes_ecb_block(k, b)
 
 
 # ---------------------------------------------------------------- GF(2^128)
@@ -170,7 +179,7 @@ def test_gcm_published_vectors():
         ok, p = oracle.decrypt_verify(_hex(key), _hex(iv), _hex(aad), _hex(ct), _hex(tag))
         assert ok and p == _hex(pt), name
         n += 1
-    assert n == 4
+    assert n == 18
 
 
 def test_gcm_closed_forms_from_the_block_cipher():
@@ -198,6 +207,56 @@ def test_gcm_closed_forms_from_the_block_cipher():
         for i in range(0, len(blocks), 16):
             s = _poly_mul(s ^ _to_poly(blocks[i:i + 16]), hp)
         assert tag == bytes(a ^ b for a, b in zip(_from_poly(s), ecb(1)))
+
+
+def test_pre_counter_block_of_other_iv_lengths_and_counter_wrap():
+    """an IV that is not 96 bits long is hashed into J0 = GHASH_H(IV pad || 0^64 || [8|IV|]_64)
+    (SP 800-38D 7.1 step 2) and the counter is the last 32 bits of J0 alone, wrapping modulo
+    2^32 (6.2).  J0 is assembled here from polynomial arithmetic and libcrypto's ECB; a 16-byte
+    IV is then solved for (J0 is linear in it) so that the counter wraps inside the message."""
+    import iv_craft
+    rng = np.random.default_rng(21)
+    for trial in range(12):
+        k = rng.integers(0, 256, (16, 24, 32)[trial % 3], dtype=np.uint8).tobytes()
+        h = openssl_ref.aes_ecb_block(k, bytes(16))
+        for ivlen in (1, 8, 11, 13, 16, 17, 60, 128):
+            iv = rng.integers(0, 256, ivlen, dtype=np.uint8).tobytes()
+            j0 = iv_craft.j0_of(h, iv)
+            ctr = int.from_bytes(j0[12:], "big")
+            ecb = lambda n: openssl_ref.aes_ecb_block(
+                k, j0[:12] + ((ctr + n) % (1 << 32)).to_bytes(4, "big"))
+            assert oracle.encrypt(k, iv, b"", b"") == (b"", ecb(0))
+            ct, _ = oracle.encrypt(k, iv, b"", bytes(50))
+            assert ct == b"".join(ecb(1 + b) for b in range(4))[:50]
+        # counter field of J0 set to 2^32 - 3: data blocks use 2^32-2, 2^32-1, 0, 1, ...
+        want = rng.integers(0, 256, 12, dtype=np.uint8).tobytes() + (2 ** 32 - 3).to_bytes(4, "big")
+        iv = iv_craft.iv_for_j0(h, want)
+        assert len(iv) == 16 and iv_craft.j0_of(h, iv) == want
+        ecb = lambda c: openssl_ref.aes_ecb_block(k, want[:12] + (c % (1 << 32)).to_bytes(4, "big"))
+        a = rng.integers(0, 256, 5, dtype=np.uint8).tobytes()
+        p = rng.integers(0, 256, 16 * 6 + 9, dtype=np.uint8).tobytes()
+        ct, tag = oracle.encrypt(k, iv, a, p)
+        ks = b"".join(ecb(2 ** 32 - 2 + b) for b in range(7))
+        assert ct == bytes(x ^ y for x, y in zip(p, ks))
+        assert (ct, tag) == openssl_ref.encrypt(k, iv, a, p)
+        assert oracle.decrypt_verify(k, iv, a, ct, tag) == (True, p)
+
+
+def test_gcm_against_libcrypto_other_key_and_iv_lengths():
+    rng = np.random.default_rng(22)
+    for i in range(600):
+        k = rng.integers(0, 256, (16, 24, 32)[i % 3], dtype=np.uint8).tobytes()
+        ivlen = int(rng.integers(1, 129)) if i % 5 else 12    # libcrypto takes IVs up to 128 bytes
+        iv = rng.integers(0, 256, ivlen, dtype=np.uint8).tobytes()
+        a = rng.integers(0, 256, int(rng.integers(0, 65)), dtype=np.uint8).tobytes()
+        p = rng.integers(0, 256, int(rng.integers(0, 1500)), dtype=np.uint8).tobytes()
+        c, t = oracle.encrypt(k, iv, a, p)
+        assert (c, t) == openssl_ref.encrypt(k, iv, a, p), (len(k), ivlen, len(p))
+        assert oracle.decrypt_verify(k, iv, a, c, t) == (True, p)
+        if len(p):
+            bad = bytearray(c)
+            bad[int(rng.integers(0, len(p)))] ^= 1 << int(rng.integers(0, 8))
+            assert oracle.decrypt_verify(k, iv, a, bytes(bad), t) == (False, bytes(len(p)))
 
 
 def test_gcm_against_libcrypto_random():
@@ -291,3 +350,14 @@ def test_batch_entry_points_equal_the_single_calls():
     for i in range(5):
         assert (cts2[i].tobytes(), tags2[i].tobytes()) == oracle.encrypt(w.key, w.ivs[i], b"",
                                                                          srcs[i])
+    # other key and IV lengths go through the same batch entry points
+    rng = np.random.default_rng(23)
+    for klen, ivlen in ((16, 8), (24, 16), (32, 60), (16, 12)):
+        key = rng.integers(0, 256, klen, dtype=np.uint8)
+        ivs = rng.integers(0, 256, (8, ivlen), dtype=np.uint8)
+        cts3, tags3, _ = oracle.encrypt_batch(key, ivs, aads[:8], srcs[:8], nthreads=3)
+        pts3, ok3, _ = oracle.decrypt_verify_batch(key, ivs, aads[:8], cts3, tags3, nthreads=3)
+        for i in range(8):
+            assert (cts3[i].tobytes(), tags3[i].tobytes()) == oracle.encrypt(key, ivs[i], aads[i],
+                                                                             srcs[i])
+            assert ok3[i] == 1 and pts3[i].tobytes() == srcs[i].tobytes()
