@@ -1,5 +1,5 @@
 /*
- * pgcm: batched AES-256-GCM on one AMD MI355X (gfx950).
+ * pgcm: batched AES-GCM (AES-256 first of all) on one AMD MI355X (gfx950).
  *
  * The operation is the one the paper's confidential-computing transport performs for every
  * host<->GPU transfer: an AES-GCM invocation over the transfer's bytes with a shared key and a
@@ -8,7 +8,10 @@
  * section 8.3 on why stale ciphertext must be rejected).  A batch is a list of such transfers
  * ("chunks": KV-cache blocks, weight chunks, adapters), each with its own 96-bit IV and 128-bit
  * tag, as issued between two synchronisation points (section 5.1, predictor input).
- * The cipher is AES-256 (FIPS-197) in GCM (NIST SP 800-38D) with 96-bit IVs and full 16-byte tags.
+ * The cipher is AES-256 (FIPS-197) in GCM (NIST SP 800-38D) with 96-bit IVs and full 16-byte tags;
+ * the entry points ending in _bytes and _iv open the cipher's other key lengths (128, 192 bits)
+ * and IV lengths (SP 800-38D 5.2.1.1, 7.1 step 2) to users of the same transport other than the
+ * paper's.  A batch uses one key; transfers under several keys are one batch per key.
  *
  * Conventions for every call
  *   - "DEVICE" pointers address memory the current HIP device can access: its own memory, or
@@ -39,7 +42,8 @@ typedef struct pgcm_key pgcm_key_t; /* opaque: device round keys, GHASH tables, 
 
 typedef enum {
     PGCM_OK = 0,
-    PGCM_ERR_ARG = -1,   /* a required pointer is NULL, or n is too large */
+    PGCM_ERR_ARG = -1,   /* a required pointer is NULL, n is too large, a key or IV length is
+                            not allowed, or the key lives on another GPU */
     PGCM_ERR_ALIGN = -2, /* a src or dst pointer is not 16-byte aligned */
     PGCM_ERR_LEN = -3,   /* a chunk is longer than 2^36 - 32 bytes (the GCM limit) */
     PGCM_ERR_NOMEM = -4, /* host or device allocation failed */
@@ -56,6 +60,13 @@ typedef enum {
  *   out        HOST, receives the new object; release it with pgcm_free_key.
  */
 int pgcm_expand_key(const uint8_t key[32], void *hip_stream, pgcm_key_t **out);
+
+/*
+ * The same for any AES key length (FIPS-197 5.2): key is HOST, key_bytes bytes, key_bytes one of
+ * 16, 24, 32; anything else is PGCM_ERR_ARG.  pgcm_expand_key(k, ..) is this call with 32.
+ */
+int pgcm_expand_key_bytes(const uint8_t *key, uint32_t key_bytes, void *hip_stream,
+                          pgcm_key_t **out);
 
 /* Wipes the device and host copies of the key material and frees them.  NULL is allowed.
  * The caller must have synchronised every stream that still uses the key. */
@@ -93,6 +104,24 @@ int pgcm_decrypt_verify_batch(pgcm_key_t *key, size_t n, const uint8_t *ivs,
                               const void *const *aad, const uint32_t *aad_len,
                               const void *const *src, const uint64_t *len, void *const *dst,
                               const uint8_t *tags, uint8_t *ok, void *hip_stream);
+
+/*
+ * The two batch calls for IVs of any one length (SP 800-38D 7.1 step 2: an IV that is not 96 bits
+ * long is hashed into the pre-counter block J0 = GHASH_H(IV || 0-pad || 0^64 || [8 |IV|]_64), and
+ * the 32-bit counter, the last word of J0, wraps modulo 2^32, section 6.2).
+ *   ivs       DEVICE, n * iv_bytes bytes; chunk i uses ivs[iv_bytes i .. iv_bytes (i + 1) - 1].
+ *   iv_bytes  length of every IV of the batch, >= 1; 0 is PGCM_ERR_ARG.  With 12 these calls are
+ *             pgcm_encrypt_batch / pgcm_decrypt_verify_batch.
+ * Everything else as above.  Long IVs are hashed by one GPU thread per chunk.
+ */
+int pgcm_encrypt_batch_iv(pgcm_key_t *key, size_t n, const uint8_t *ivs, uint32_t iv_bytes,
+                          const void *const *aad, const uint32_t *aad_len,
+                          const void *const *src, const uint64_t *len, void *const *dst,
+                          uint8_t *tags, void *hip_stream);
+int pgcm_decrypt_verify_batch_iv(pgcm_key_t *key, size_t n, const uint8_t *ivs, uint32_t iv_bytes,
+                                 const void *const *aad, const uint32_t *aad_len,
+                                 const void *const *src, const uint64_t *len, void *const *dst,
+                                 const uint8_t *tags, uint8_t *ok, void *hip_stream);
 
 /* Static text for a pgcm_status value. */
 const char *pgcm_strerror(int status);

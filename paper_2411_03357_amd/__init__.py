@@ -1,9 +1,9 @@
-"""Batched AES-256-GCM for one MI355X: a thin ctypes binding over libpgcm.so.
+"""Batched AES-GCM (AES-256 first of all) for one MI355X: a thin ctypes binding over libpgcm.so.
 
 The binding marshals arguments only; every step of the cipher runs in the library's HIP
 kernels.  Importing the package does not load the library; the first call does, and fails
 loudly when libpgcm.so has not been built (python -m paper_2411_03357_amd.build).
 """
-from .binding import (PgcmError, Key, expand_key, encrypt_batch, decrypt_verify_batch,  # noqa: F401
+from .binding import (PgcmError, Key, expand_key, expand_key_bytes, encrypt_batch, decrypt_verify_batch,  # noqa: F401
                       plan_units, unit_bytes, library_path, load_library, set_timing,
                       last_bulk_kernel_ms, EXPORTS, Sequencer, seq_iv_bytes, SEQ_EXPORTS)

@@ -8,7 +8,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpgcm.so")
 _lib = None
 
-EXPORTS = ("pgcm_expand_key", "pgcm_free_key", "pgcm_encrypt_batch", "pgcm_decrypt_verify_batch",
+EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_encrypt_batch",
+           "pgcm_decrypt_verify_batch", "pgcm_encrypt_batch_iv", "pgcm_decrypt_verify_batch_iv",
            "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_units", "pgcm_unit_bytes",
            "pgcm_set_timing", "pgcm_last_bulk_kernel_ms")
 
@@ -37,12 +38,19 @@ def load_library():
     vp, sz = C.c_void_p, C.c_size_t
     lib.pgcm_expand_key.argtypes = [vp, vp, C.POINTER(vp)]
     lib.pgcm_expand_key.restype = C.c_int
+    lib.pgcm_expand_key_bytes.argtypes = [vp, C.c_uint32, vp, C.POINTER(vp)]
+    lib.pgcm_expand_key_bytes.restype = C.c_int
     lib.pgcm_free_key.argtypes = [vp]
     lib.pgcm_free_key.restype = None
     lib.pgcm_encrypt_batch.argtypes = [vp, sz, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.pgcm_encrypt_batch.restype = C.c_int
     lib.pgcm_decrypt_verify_batch.argtypes = [vp, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.pgcm_decrypt_verify_batch.restype = C.c_int
+    lib.pgcm_encrypt_batch_iv.argtypes = [vp, sz, vp, C.c_uint32, vp, vp, vp, vp, vp, vp, vp]
+    lib.pgcm_encrypt_batch_iv.restype = C.c_int
+    lib.pgcm_decrypt_verify_batch_iv.argtypes = [vp, sz, vp, C.c_uint32, vp, vp, vp, vp, vp, vp,
+                                                 vp, vp]
+    lib.pgcm_decrypt_verify_batch_iv.restype = C.c_int
     lib.pgcm_strerror.argtypes = [C.c_int]
     lib.pgcm_strerror.restype = C.c_char_p
     lib.pgcm_last_hip_error.argtypes = []
@@ -124,10 +132,14 @@ class Key:
             pass
 
 
+def _key_bytes(key):
+    return np.frombuffer(bytes(key), dtype=np.uint8) if not isinstance(key, np.ndarray) else \
+        np.ascontiguousarray(key, dtype=np.uint8)
+
+
 def expand_key(key, stream=None) -> Key:
     """pgcm_expand_key: `key` is 32 bytes (bytes or uint8 array)."""
-    kb = np.frombuffer(bytes(key), dtype=np.uint8) if not isinstance(key, np.ndarray) else \
-        np.ascontiguousarray(key, dtype=np.uint8)
+    kb = _key_bytes(key)
     if kb.size != 32:
         raise ValueError("AES-256 keys are 32 bytes")
     out = C.c_void_p()
@@ -135,23 +147,40 @@ def expand_key(key, stream=None) -> Key:
     return Key(out.value)
 
 
-def encrypt_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, stream=None):
-    """pgcm_encrypt_batch.  ivs, tags: CUDA uint8 tensors (n*12, n*16 bytes) or device addresses;
-    src, dst, aad: sequences / uint64 arrays of n device addresses; length: n byte counts;
-    aad and aad_len are both None when no chunk has AAD."""
+def expand_key_bytes(key, stream=None) -> Key:
+    """pgcm_expand_key_bytes: `key` is 16, 24 or 32 bytes; the library checks the length."""
+    kb = _key_bytes(key)
+    out = C.c_void_p()
+    _check(load_library().pgcm_expand_key_bytes(kb.ctypes.data, kb.size, _stream_handle(stream),
+                                                C.byref(out)))
+    return Key(out.value)
+
+
+def encrypt_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, stream=None, iv_bytes=None):
+    """pgcm_encrypt_batch, or pgcm_encrypt_batch_iv when iv_bytes is given.  ivs, tags: CUDA uint8
+    tensors (n*12 or n*iv_bytes, n*16 bytes) or device addresses; src, dst, aad: sequences / uint64
+    arrays of n device addresses; length: n byte counts; aad and aad_len are both None when no
+    chunk has AAD."""
     n = len(length)
     src_a = _host_array(src, np.uint64, n, "src")
     dst_a = _host_array(dst, np.uint64, n, "dst")
     len_a = _host_array(length, np.uint64, n, "length")
     aad_a = _host_array(aad, np.uint64, n, "aad")
     alen_a = _host_array(aad_len, np.uint32, n, "aad_len")
+    if iv_bytes is not None:
+        _check(load_library().pgcm_encrypt_batch_iv(
+            key.handle, n, _dev_ptr(ivs), iv_bytes, _addr(aad_a), _addr(alen_a), _addr(src_a),
+            _addr(len_a), _addr(dst_a), _dev_ptr(tags), _stream_handle(stream)))
+        return
     _check(load_library().pgcm_encrypt_batch(
         key.handle, n, _dev_ptr(ivs), _addr(aad_a), _addr(alen_a), _addr(src_a), _addr(len_a),
         _addr(dst_a), _dev_ptr(tags), _stream_handle(stream)))
 
 
-def decrypt_verify_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, ok, stream=None):
-    """pgcm_decrypt_verify_batch.  As encrypt_batch; tags is read, ok (CUDA uint8 tensor of n
+def decrypt_verify_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, ok, stream=None,
+                         iv_bytes=None):
+    """pgcm_decrypt_verify_batch (pgcm_decrypt_verify_batch_iv when iv_bytes is given).  As
+    encrypt_batch; tags is read, ok (CUDA uint8 tensor of n
     bytes) receives 1 per authentic chunk and 0 per rejected one."""
     n = len(length)
     src_a = _host_array(src, np.uint64, n, "src")
@@ -159,6 +188,11 @@ def decrypt_verify_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, ok
     len_a = _host_array(length, np.uint64, n, "length")
     aad_a = _host_array(aad, np.uint64, n, "aad")
     alen_a = _host_array(aad_len, np.uint32, n, "aad_len")
+    if iv_bytes is not None:
+        _check(load_library().pgcm_decrypt_verify_batch_iv(
+            key.handle, n, _dev_ptr(ivs), iv_bytes, _addr(aad_a), _addr(alen_a), _addr(src_a),
+            _addr(len_a), _addr(dst_a), _dev_ptr(tags), _dev_ptr(ok), _stream_handle(stream)))
+        return
     _check(load_library().pgcm_decrypt_verify_batch(
         key.handle, n, _dev_ptr(ivs), _addr(aad_a), _addr(alen_a), _addr(src_a), _addr(len_a),
         _addr(dst_a), _dev_ptr(tags), _dev_ptr(ok), _stream_handle(stream)))

@@ -61,6 +61,7 @@ inline uint32_t fold_levels(uint32_t nunits, uint32_t out_counts[kMaxLevels]) {
 struct pgcm_key {
     int device = -1;
     int num_cu = 0;
+    int rounds = 0;  // 10, 12 or 14
     KeyTables* tables = nullptr;  // device
     // descriptor staging: pinned host buffers used in turn, each guarded by an event that marks
     // the end of its last upload
@@ -121,10 +122,34 @@ int ensure_work(pgcm_key* k, size_t bytes, hipStream_t stream) {
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const void* const* aad,
-              const uint32_t* aad_len, const void* const* src, const uint64_t* len,
-              void* const* dst, uint8_t* tags, uint8_t* ok, void* hip_stream) {
+// the kernels that run the cipher are compiled once per round count
+template <bool kDecrypt, class... Args>
+void launch_bulk(int rounds, dim3 grid, hipStream_t stream, Args... args) {
+    if (rounds == 10)
+        hipLaunchKernelGGL((bulk_kernel<kDecrypt, 10>), grid, dim3(kGroupThreads), 0, stream, args...);
+    else if (rounds == 12)
+        hipLaunchKernelGGL((bulk_kernel<kDecrypt, 12>), grid, dim3(kGroupThreads), 0, stream, args...);
+    else
+        hipLaunchKernelGGL((bulk_kernel<kDecrypt, 14>), grid, dim3(kGroupThreads), 0, stream, args...);
+}
+
+template <bool kDecrypt, class... Args>
+void launch_small(int rounds, dim3 grid, hipStream_t stream, Args... args) {
+    const dim3 block(kSmallChunksPerGroup * 64);
+    if (rounds == 10)
+        hipLaunchKernelGGL((small_kernel<kDecrypt, 10>), grid, block, 0, stream, args...);
+    else if (rounds == 12)
+        hipLaunchKernelGGL((small_kernel<kDecrypt, 12>), grid, block, 0, stream, args...);
+    else
+        hipLaunchKernelGGL((small_kernel<kDecrypt, 14>), grid, block, 0, stream, args...);
+}
+
+int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, uint32_t iv_len,
+              const void* const* aad, const uint32_t* aad_len, const void* const* src,
+              const uint64_t* len, void* const* dst, uint8_t* tags, uint8_t* ok,
+              void* hip_stream) {
     if (key == nullptr || key->tables == nullptr) return PGCM_ERR_ARG;
+    if (iv_len == 0) return PGCM_ERR_ARG;  // GCM takes no empty IV
     if (n == 0) return PGCM_OK;
     if (ivs == nullptr || src == nullptr || len == nullptr || dst == nullptr || tags == nullptr)
         return PGCM_ERR_ARG;
@@ -190,11 +215,12 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
         const uint32_t groups = (nchunks + kSmallChunksPerGroup - 1) / kSmallChunksPerGroup;
         if (key->timing) PGCM_HIP(hipEventRecord(key->bulk_start, stream));
         if (decrypt)
-            hipLaunchKernelGGL(small_kernel<true>, dim3(groups), dim3(kSmallChunksPerGroup * 64), 0,
-                               stream, key->tables, h_desc, nchunks, ivs, tags, ok);
+            launch_small<true>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
+                               (const ChunkDesc*)h_desc, nchunks, ivs, iv_len, tags, ok);
         else
-            hipLaunchKernelGGL(small_kernel<false>, dim3(groups), dim3(kSmallChunksPerGroup * 64), 0,
-                               stream, key->tables, h_desc, nchunks, ivs, tags, nullptr);
+            launch_small<false>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
+                                (const ChunkDesc*)h_desc, nchunks, ivs, iv_len, tags,
+                                (uint8_t*)nullptr);
         if (key->timing) {
             PGCM_HIP(hipEventRecord(key->bulk_stop, stream));
             key->timed = true;
@@ -214,7 +240,9 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     const size_t upload_bytes = round_up(off_fold + sizeof(FoldItem) * (size_t)nfold, 256);
     const size_t off_counter = upload_bytes;
     const size_t off_ekj0 = off_counter + 256;
-    const size_t off_sets = round_up(off_ekj0 + sizeof(Block) * n, 1024);
+    // pre-counter blocks, only for IVs that are not 96 bits long
+    const size_t off_j0 = off_ekj0 + sizeof(Block) * n;
+    const size_t off_sets = round_up(off_j0 + (iv_len == 12 ? 0 : sizeof(Block) * n), 1024);
     const size_t work_bytes = off_sets + sizeof(Block) * 64 * (size_t)nslots;
 
     const int s = key->next_stage;
@@ -292,6 +320,10 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     uint32_t* d_counter = reinterpret_cast<uint32_t*>(key->work + off_counter);
     Block* d_ekj0 = reinterpret_cast<Block*>(key->work + off_ekj0);
     Block* d_sets = reinterpret_cast<Block*>(key->work + off_sets);
+    Block* d_j0 = iv_len == 12 ? nullptr : reinterpret_cast<Block*>(key->work + off_j0);
+    if (d_j0 != nullptr)
+        hipLaunchKernelGGL(j0_kernel, dim3((nchunks + 63) / 64), dim3(64), 0, stream, key->tables,
+                           ivs, iv_len, nchunks, d_j0);
 
     // the unit counter is left at zero by the last kernel of every batch; it only needs clearing
     // when the workspace is new (or has moved) or an earlier batch was cut short
@@ -306,13 +338,13 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
         if (groups > (uint32_t)key->num_cu) groups = (uint32_t)key->num_cu;
         if (key->timing) PGCM_HIP(hipEventRecord(key->bulk_start, stream));
         if (decrypt)
-            hipLaunchKernelGGL(bulk_kernel<true>, dim3(groups), dim3(kGroupThreads), 0, stream,
-                               key->tables, d_desc, d_ubase, d_coarse, nunits, d_counter, ivs,
-                               d_ekj0, d_sets);
+            launch_bulk<true>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
+                              d_desc, d_ubase, d_coarse, nunits, d_counter, ivs,
+                              (const Block*)d_j0, d_ekj0, d_sets);
         else
-            hipLaunchKernelGGL(bulk_kernel<false>, dim3(groups), dim3(kGroupThreads), 0, stream,
-                               key->tables, d_desc, d_ubase, d_coarse, nunits, d_counter, ivs,
-                               d_ekj0, d_sets);
+            launch_bulk<false>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
+                               d_desc, d_ubase, d_coarse, nunits, d_counter, ivs,
+                               (const Block*)d_j0, d_ekj0, d_sets);
         if (key->timing) {
             PGCM_HIP(hipEventRecord(key->bulk_stop, stream));
             key->timed = true;
@@ -326,10 +358,11 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, const v
     const uint32_t final_groups = (nchunks + 15) / 16;
     if (decrypt) {
         hipLaunchKernelGGL(final_kernel<true>, dim3(final_groups), dim3(1024), 0, stream,
-                           key->tables, d_desc, nchunks, ivs, d_ekj0, d_sets, tags, ok, d_counter);
+                           key->tables, d_desc, nchunks, ivs, d_j0, d_ekj0, d_sets, tags, ok,
+                           d_counter);
     } else {
         hipLaunchKernelGGL(final_kernel<false>, dim3(final_groups), dim3(1024), 0, stream,
-                           key->tables, d_desc, nchunks, ivs, d_ekj0, d_sets, tags, nullptr,
+                           key->tables, d_desc, nchunks, ivs, d_j0, d_ekj0, d_sets, tags, nullptr,
                            d_counter);
     }
     PGCM_HIP(hipGetLastError());
@@ -343,8 +376,14 @@ extern "C" {
 #pragma GCC visibility push(default)
 
 int pgcm_expand_key(const uint8_t key[32], void* hip_stream, pgcm_key_t** out) {
+    return pgcm_expand_key_bytes(key, 32, hip_stream, out);
+}
+
+int pgcm_expand_key_bytes(const uint8_t* key, uint32_t key_bytes, void* hip_stream,
+                          pgcm_key_t** out) {
     if (key == nullptr || out == nullptr) return PGCM_ERR_ARG;
     *out = nullptr;
+    if (key_bytes != 16 && key_bytes != 24 && key_bytes != 32) return PGCM_ERR_ARG;
     pgcm_key* k = new (std::nothrow) pgcm_key();
     if (k == nullptr) return PGCM_ERR_NOMEM;
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -363,9 +402,11 @@ int pgcm_expand_key(const uint8_t key[32], void* hip_stream, pgcm_key_t** out) {
                 break;
             }
         if (rc != PGCM_OK) break;
-        // a 32-byte pageable copy: staged by the runtime, complete on return for this size
-        if (hip_failed(hipMemcpyAsync(d_key, key, 32, hipMemcpyHostToDevice, stream))) { rc = PGCM_ERR_HIP; break; }
-        hipLaunchKernelGGL(expand_key_kernel, dim3(1), dim3(1024), 0, stream, k->tables, d_key);
+        // a pageable copy of at most 32 bytes: staged by the runtime, complete on return for this size
+        if (hip_failed(hipMemcpyAsync(d_key, key, key_bytes, hipMemcpyHostToDevice, stream))) { rc = PGCM_ERR_HIP; break; }
+        k->rounds = (int)(key_bytes / 4 + 6);
+        hipLaunchKernelGGL(expand_key_kernel, dim3(1), dim3(1024), 0, stream, k->tables, d_key,
+                           key_bytes / 4);
         if (hip_failed(hipGetLastError())) { rc = PGCM_ERR_HIP; break; }
         if (hip_failed(hipMemsetAsync(d_key, 0, 32, stream))) { rc = PGCM_ERR_HIP; break; }
         if (hip_failed(hipStreamSynchronize(stream))) { rc = PGCM_ERR_HIP; break; }
@@ -405,15 +446,31 @@ void pgcm_free_key(pgcm_key_t* k) {
 int pgcm_encrypt_batch(pgcm_key_t* key, size_t n, const uint8_t* ivs, const void* const* aad,
                        const uint32_t* aad_len, const void* const* src, const uint64_t* len,
                        void* const* dst, uint8_t* tags, void* hip_stream) {
-    return run_batch(false, key, n, ivs, aad, aad_len, src, len, dst, tags, nullptr, hip_stream);
+    return run_batch(false, key, n, ivs, 12, aad, aad_len, src, len, dst, tags, nullptr,
+                     hip_stream);
+}
+
+int pgcm_encrypt_batch_iv(pgcm_key_t* key, size_t n, const uint8_t* ivs, uint32_t iv_bytes,
+                          const void* const* aad, const uint32_t* aad_len, const void* const* src,
+                          const uint64_t* len, void* const* dst, uint8_t* tags, void* hip_stream) {
+    return run_batch(false, key, n, ivs, iv_bytes, aad, aad_len, src, len, dst, tags, nullptr,
+                     hip_stream);
 }
 
 int pgcm_decrypt_verify_batch(pgcm_key_t* key, size_t n, const uint8_t* ivs,
                               const void* const* aad, const uint32_t* aad_len,
                               const void* const* src, const uint64_t* len, void* const* dst,
                               const uint8_t* tags, uint8_t* ok, void* hip_stream) {
-    return run_batch(true, key, n, ivs, aad, aad_len, src, len, dst, const_cast<uint8_t*>(tags), ok,
-                     hip_stream);
+    return run_batch(true, key, n, ivs, 12, aad, aad_len, src, len, dst,
+                     const_cast<uint8_t*>(tags), ok, hip_stream);
+}
+
+int pgcm_decrypt_verify_batch_iv(pgcm_key_t* key, size_t n, const uint8_t* ivs, uint32_t iv_bytes,
+                                 const void* const* aad, const uint32_t* aad_len,
+                                 const void* const* src, const uint64_t* len, void* const* dst,
+                                 const uint8_t* tags, uint8_t* ok, void* hip_stream) {
+    return run_batch(true, key, n, ivs, iv_bytes, aad, aad_len, src, len, dst,
+                     const_cast<uint8_t*>(tags), ok, hip_stream);
 }
 
 const char* pgcm_strerror(int status) {

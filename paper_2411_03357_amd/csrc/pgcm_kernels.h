@@ -6,27 +6,31 @@
 
 namespace pgcm {
 
-__global__ void expand_key_kernel(KeyTables* kt, const uint32_t* key_words);
+__global__ void expand_key_kernel(KeyTables* kt, const uint32_t* key_words, uint32_t nk);
 
-template <bool kDecrypt>
+__global__ void j0_kernel(const KeyTables* kt, const uint8_t* ivs, uint32_t iv_len,
+                          uint32_t nchunks, Block* j0);
+
+// kRounds: 10, 12 or 14
+template <bool kDecrypt, int kRounds>
 __global__ void bulk_kernel(const KeyTables* kt, const ChunkDesc* chunks,
                             const uint32_t* unit_base, const uint32_t* coarse_map,
                             uint32_t nunits_total, uint32_t* counter, const uint8_t* ivs,
-                            Block* ekj0, Block* sets);
+                            const Block* j0, Block* ekj0, Block* sets);
 
 __global__ void fold_kernel(const KeyTables* kt, const FoldItem* items, uint32_t power,
                             Block* sets);
 
 template <bool kDecrypt>
 __global__ void final_kernel(const KeyTables* kt, const ChunkDesc* chunks, uint32_t nchunks,
-                             const uint8_t* ivs, const Block* ekj0, const Block* sets,
-                             uint8_t* tags, uint8_t* ok, uint32_t* counter);
+                             const uint8_t* ivs, const Block* j0, const Block* ekj0,
+                             const Block* sets, uint8_t* tags, uint8_t* ok, uint32_t* counter);
 
 constexpr uint32_t kSmallChunksPerGroup = 4;
 
-template <bool kDecrypt>
+template <bool kDecrypt, int kRounds>
 __global__ void small_kernel(const KeyTables* kt, const ChunkDesc* chunks_host, uint32_t nchunks,
-                             const uint8_t* ivs, uint8_t* tags, uint8_t* ok);
+                             const uint8_t* ivs, uint32_t iv_len, uint8_t* tags, uint8_t* ok);
 
 __global__ void upload_kernel(uint4* dst, const uint4* src_host, uint32_t n16);
 

@@ -1,8 +1,9 @@
-// HIP kernels for batched AES-256-GCM on gfx950 (MI355X).
+// HIP kernels for batched AES-GCM on gfx950 (MI355X).
 //
 // What is computed is the AES-GCM transform the paper's transport applies to every transfer
 // (paper sections 2.2 and 4.1), i.e. FIPS-197 AES-256 in the GCM mode of NIST SP 800-38D with a
-// 96-bit IV.  How it is computed here:
+// 96-bit IV; the other two key lengths and other IV lengths are served by the same kernels
+// (round count as a template parameter, pre-counter blocks hashed beforehand).  How:
 //   * AES rounds read four 1 KiB round tables, each replicated 32 times in LDS so that lane l
 //     always reads bank l % 32: table lookups never collide, whatever the data.  AddRoundKey is
 //     folded into forming the next round's lookup addresses (one SDWA XOR per state byte).
@@ -134,13 +135,14 @@ __device__ Block gf_mul_table(const Block* __restrict__ tbl, const Block& x) {
 }
 
 // ------------------------------------------------------------------------------------------
-// AES-256 block encryption from tables in global memory (set-up, J0, not the bulk path)
+// AES block encryption from tables in global memory (set-up, J0, not the bulk path)
 __device__ __forceinline__ uint32_t byte_of(uint32_t w, int k) { return (w >> (8 * k)) & 0xFF; }
 
-__device__ void aes256_block_global(const KeyTables* __restrict__ kt, uint32_t s[4]) {
+__device__ void aes_block_global(const KeyTables* __restrict__ kt, uint32_t s[4]) {
     const uint32_t* rk = kt->rk;
+    const int nr = (int)kt->rounds;
     uint32_t a0 = s[0] ^ rk[0], a1 = s[1] ^ rk[1], a2 = s[2] ^ rk[2], a3 = s[3] ^ rk[3];
-    for (int r = 1; r < 14; ++r) {
+    for (int r = 1; r < nr; ++r) {
         uint32_t t0 = kt->te[0][byte_of(a0, 0)] ^ kt->te[1][byte_of(a1, 1)] ^
                       kt->te[2][byte_of(a2, 2)] ^ kt->te[3][byte_of(a3, 3)] ^ rk[4 * r + 0];
         uint32_t t1 = kt->te[0][byte_of(a1, 0)] ^ kt->te[1][byte_of(a2, 1)] ^
@@ -156,10 +158,10 @@ __device__ void aes256_block_global(const KeyTables* __restrict__ kt, uint32_t s
         return (uint32_t)S[byte_of(c0, 0)] | ((uint32_t)S[byte_of(c1, 1)] << 8) |
                ((uint32_t)S[byte_of(c2, 2)] << 16) | ((uint32_t)S[byte_of(c3, 3)] << 24);
     };
-    s[0] = last(a0, a1, a2, a3) ^ rk[56];
-    s[1] = last(a1, a2, a3, a0) ^ rk[57];
-    s[2] = last(a2, a3, a0, a1) ^ rk[58];
-    s[3] = last(a3, a0, a1, a2) ^ rk[59];
+    s[0] = last(a0, a1, a2, a3) ^ rk[4 * nr + 0];
+    s[1] = last(a1, a2, a3, a0) ^ rk[4 * nr + 1];
+    s[2] = last(a2, a3, a0, a1) ^ rk[4 * nr + 2];
+    s[3] = last(a3, a0, a1, a2) ^ rk[4 * nr + 3];
 }
 
 __device__ __forceinline__ uint32_t sub_word(uint32_t w) {
@@ -172,9 +174,10 @@ __device__ __forceinline__ uint32_t sub_word(uint32_t w) {
 
 // ------------------------------------------------------------------------------------------
 // Key set-up: key schedule (FIPS-197 5.2), round tables, H and the nibble tables of H^(2^k).
-// One workgroup; `key_words` are the 32 key bytes as 8 little-endian words.
+// One workgroup; `key_words` are the key bytes as nk = 4, 6 or 8 little-endian words.
 __global__ __launch_bounds__(1024) void expand_key_kernel(KeyTables* __restrict__ kt,
-                                                          const uint32_t* __restrict__ key_words) {
+                                                          const uint32_t* __restrict__ key_words,
+                                                          uint32_t nk) {
     __shared__ Gf powers[kNumPowers];
     const uint32_t tid = threadIdx.x;
 
@@ -189,27 +192,30 @@ __global__ __launch_bounds__(1024) void expand_key_kernel(KeyTables* __restrict_
         kt->te[3][x] = (t0 << 24) | (t0 >> 8);
     }
     if (tid == 0) {
+        const uint32_t nr = nk + 6, nwords = 4 * (nr + 1);
         uint32_t w[60];
-        for (int i = 0; i < 8; ++i) w[i] = key_words[i];
+        for (uint32_t i = 0; i < 60; ++i) w[i] = 0;
+        for (uint32_t i = 0; i < nk; ++i) w[i] = key_words[i];
         uint32_t rcon = 1;
-        for (int i = 8; i < 60; ++i) {
+        for (uint32_t i = nk; i < nwords; ++i) {
             uint32_t t = w[i - 1];
-            if (i % 8 == 0) {
+            if (i % nk == 0) {
                 t = sub_word((t >> 8) | (t << 24)) ^ rcon;  // RotWord on little-endian bytes
                 rcon = xtime((uint8_t)rcon);
-            } else if (i % 8 == 4) {
+            } else if (nk > 6 && i % nk == 4) {
                 t = sub_word(t);
             }
-            w[i] = w[i - 8] ^ t;
+            w[i] = w[i - nk] ^ t;
         }
-        for (int i = 0; i < 60; ++i) kt->rk[i] = w[i];
-        for (int i = 0; i < 4; ++i) kt->pad_[i] = 0;
+        for (uint32_t i = 0; i < 60; ++i) kt->rk[i] = w[i];
+        kt->rounds = nr;
+        for (int i = 0; i < 3; ++i) kt->pad_[i] = 0;
     }
     __threadfence();
     __syncthreads();
     if (tid == 0) {
         uint32_t z[4] = {0, 0, 0, 0};
-        aes256_block_global(kt, z);
+        aes_block_global(kt, z);
         Block h{{z[0], z[1], z[2], z[3]}};
         kt->h = h;
         Gf p = gf_from_block(h);
@@ -251,7 +257,43 @@ __device__ Block aad_hash(const KeyTables* __restrict__ kt, const uint8_t* __res
     }
     return y;
 }
+
+// Pre-counter block of a chunk (SP 800-38D 7.1 step 2): IV || 0^31 1 for a 96-bit IV, else
+// GHASH_H(IV || 0-pad || 0^64 || [8 |IV|]_64).  Same remark on lanes as above.
+__device__ Block j0_from_iv(const KeyTables* __restrict__ kt, const uint8_t* __restrict__ iv,
+                            uint32_t iv_len) {
+    if (iv_len == 12) {
+        Block j;
+        for (int w = 0; w < 3; ++w)
+            j.w[w] = (uint32_t)iv[4 * w] | ((uint32_t)iv[4 * w + 1] << 8) |
+                     ((uint32_t)iv[4 * w + 2] << 16) | ((uint32_t)iv[4 * w + 3] << 24);
+        j.w[3] = 0x01000000u;  // be32(1)
+        return j;
+    }
+    Block y = aad_hash(kt, iv, iv_len);
+    const uint64_t bits = (uint64_t)iv_len * 8;
+    y.w[2] ^= bswap32((uint32_t)(bits >> 32));
+    y.w[3] ^= bswap32((uint32_t)bits);
+    return gf_mul_table(kt->ghash[0], y);
+}
+
+// A chunk's J0: read from `j0` when the host had it hashed beforehand (IVs that are not 96 bits
+// long), otherwise formed from the IV bytes.
+__device__ __forceinline__ Block chunk_j0(const KeyTables* __restrict__ kt,
+                                          const uint8_t* __restrict__ ivs,
+                                          const Block* __restrict__ j0, uint32_t chunk) {
+    if (j0 != nullptr) return j0[chunk];
+    return j0_from_iv(kt, ivs + (uint64_t)chunk * 12, 12);
+}
 }  // namespace
+
+// One thread per chunk: J0 of IVs whose length is not 96 bits, for the kernels that follow.
+__global__ __launch_bounds__(64) void j0_kernel(const KeyTables* __restrict__ kt,
+                                                const uint8_t* __restrict__ ivs, uint32_t iv_len,
+                                                uint32_t nchunks, Block* __restrict__ j0) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nchunks) j0[i] = j0_from_iv(kt, ivs + (uint64_t)i * iv_len, iv_len);
+}
 
 // ------------------------------------------------------------------------------------------
 // The bulk kernel.  LDS map (byte addresses; the object below is the kernel's only LDS):
@@ -428,10 +470,13 @@ struct GhashRowMul {
     }
 };
 
-// E_K(IV || be32(ctr)) for this lane's counter, with the row's GHASH multiplication G riding
-// along; rk is wave-uniform (scalar registers).  Between rounds the state is carried without its
-// round key: the key bytes are added while the next round's addresses are formed.
-__device__ __forceinline__ void aes256_ctr_lds(const uint32_t* __restrict__ rk, AesAddr& A,
+// E_K(J0[0..95] || be32(ctr)) for this lane's counter, with the row's GHASH multiplication G
+// riding along; rk is wave-uniform (scalar registers).  Between rounds the state is carried
+// without its round key: the key bytes are added while the next round's addresses are formed.
+// The sixteen byte steps of G: three in round 1, the other thirteen spread evenly over rounds
+// 2 .. kRounds (one each for AES-256, one or two each for the shorter keys).
+template <int kRounds>
+__device__ __forceinline__ void aes_ctr_lds(const uint32_t* __restrict__ rk, AesAddr& A,
                                                const CtrConsts& C, uint32_t ctr, GhashRowMul& G,
                                                uint32_t& o0, uint32_t& o1, uint32_t& o2,
                                                uint32_t& o3) {
@@ -448,8 +493,11 @@ __device__ __forceinline__ void aes256_ctr_lds(const uint32_t* __restrict__ rk, 
     G.step<1>();
     G.step<2>();
     __builtin_amdgcn_sched_barrier(0);
-    static_for<2, 15>([&](auto round) __attribute__((always_inline)) {
+    static_for<2, kRounds + 1>([&](auto round) __attribute__((always_inline)) {
         constexpr int r = decltype(round)::value;
+        constexpr int step_begin = 3 + (13 * (r - 2)) / (kRounds - 1),
+                      step_end = 3 + (13 * (r - 1)) / (kRounds - 1);
+        static_assert(step_end - step_begin == 1 || step_end - step_begin == 2, "hash steps");
         const uint32_t* k = rk + 4 * (r - 1);
         key_xor_into_addr<0, 0>(A.a[0][0], k[0], u0);
         key_xor_into_addr<1, 1>(A.a[0][1], k[0], u0);
@@ -475,9 +523,8 @@ __device__ __forceinline__ void aes256_ctr_lds(const uint32_t* __restrict__ rk, 
                  t02 = te_read<2>(A.a[0][2]), t13 = te_read<3>(A.a[1][3]);
         uint32_t t30 = te_read<0>(A.a[3][0]), t01 = te_read<1>(A.a[0][1]),
                  t12 = te_read<2>(A.a[1][2]), t23 = te_read<3>(A.a[2][3]);
-        // one GHASH byte step per round: steps 3 .. 15 in rounds 2 .. 14
-        G.template issue<r + 1>();
-        if constexpr (r < 14) {
+        G.template issue<step_begin>();
+        if constexpr (r < kRounds) {
             u0 = xor3(t00, t11, t22) ^ t33;
             u1 = xor3(t10, t21, t32) ^ t03;
             u2 = xor3(t20, t31, t02) ^ t13;
@@ -490,12 +537,13 @@ __device__ __forceinline__ void aes256_ctr_lds(const uint32_t* __restrict__ rk, 
                 uint32_t hi = __builtin_amdgcn_perm(v2, v3, 0x00040c0cu);  // [0, 0, v2.b0, v3.b0]
                 return xor3(lo, hi, key);
             };
-            o0 = last(t00, t11, t22, t33, rk[56]);
-            o1 = last(t10, t21, t32, t03, rk[57]);
-            o2 = last(t20, t31, t02, t13, rk[58]);
-            o3 = last(t30, t01, t12, t23, rk[59]);
+            o0 = last(t00, t11, t22, t33, rk[4 * kRounds + 0]);
+            o1 = last(t10, t21, t32, t03, rk[4 * kRounds + 1]);
+            o2 = last(t20, t31, t02, t13, rk[4 * kRounds + 2]);
+            o3 = last(t30, t01, t12, t23, rk[4 * kRounds + 3]);
         }
         G.consume();
+        if constexpr (step_end - step_begin == 2) G.template step<step_begin + 1>();
         // keep every round's hash step with its round: without this the compiler sinks the
         // hash XORs to the end of the block and spills the table entries they wait for
         __builtin_amdgcn_sched_barrier(0);
@@ -535,11 +583,12 @@ __device__ __forceinline__ void ghash_mul_lds(uint32_t base, uint32_t y[4]) {
 // idle, the last lane may hold the chunk's ragged last block, and the lane of block 0 folds in
 // the AAD state.  One code path serves both kinds: idle lanes run the cipher on a dummy counter,
 // touch no payload and keep a zero hash state.
-template <bool kDecrypt>
+template <bool kDecrypt, int kRounds>
 __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAddr& A,
-                                         const CtrConsts& C, const uint8_t* src, uint8_t* dst,
-                                         uint64_t len, int64_t blk, bool edge, const Block& aad_y,
-                                         Block* __restrict__ ekj0_out, uint32_t y[4]) {
+                                         const CtrConsts& C, uint32_t ctr1, const uint8_t* src,
+                                         uint8_t* dst, uint64_t len, int64_t blk, bool edge,
+                                         const Block& aad_y, Block* __restrict__ ekj0_out,
+                                         uint32_t y[4]) {
     bool active = true;
     uint32_t tail = 0;  // bytes in a ragged block, 0 = whole block
     if (edge) {
@@ -568,12 +617,13 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
         }
     }
 
-    // counter block IV || be32(blk + 2) (SP 800-38D 7.1 step 3 with J0 = IV || 0^31 1) ...
-    // ... while the hash state moves one row along: Y <- Y * H^64
+    // counter block inc32^(blk + 1)(J0): the first 96 bits of J0, then its counter field plus
+    // blk + 1 modulo 2^32 (SP 800-38D 6.2, 7.1 step 3; ctr1 is that field plus 1, 2 for a 96-bit
+    // IV) ... while the hash state moves one row along: Y <- Y * H^64
     GhashRowMul G;
     G.w[0] = y[0], G.w[1] = y[1], G.w[2] = y[2], G.w[3] = y[3];
     uint32_t s0, s1, s2, s3;
-    aes256_ctr_lds(rk, A, C, (uint32_t)blk + 2u, G, s0, s1, s2, s3);
+    aes_ctr_lds<kRounds>(rk, A, C, (uint32_t)blk + ctr1, G, s0, s1, s2, s3);
     uint32_t o0 = x0 ^ s0, o1 = x1 ^ s1, o2 = x2 ^ s2, o3 = x3 ^ s3;
 
     if (whole) {
@@ -606,8 +656,8 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
             c0 ^= aad_y.w[0], c1 ^= aad_y.w[1], c2 ^= aad_y.w[2], c3 ^= aad_y.w[3];
         }
         if (blk == -1) {
-            // the counter of "block -1" is 1: this idle lane has just computed E_K(J0), the
-            // mask of the chunk's tag (SP 800-38D 7.1 steps 2 and 6)
+            // the counter block of "block -1" is J0 itself: this idle lane has just computed
+            // E_K(J0), the mask of the chunk's tag (SP 800-38D 7.1 steps 2 and 6)
             *ekj0_out = Block{{s0, s1, s2, s3}};
         }
         if (!active) c0 = c1 = c2 = c3 = 0;  // idle lanes only occur before a chunk's start: Y = 0
@@ -622,12 +672,13 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
 // chunks); coarse_map[i >> kCoarseShift] is a chunk at or before the right one.
 // sets[i * 64 + lane] receives lane's GHASH sum over the unit's rows:
 //   sum over rows r of C(r, lane) * (H^64)^(rows after r).
-template <bool kDecrypt>
+// ivs: the chunks' 96-bit IVs, read when j0 is null; otherwise j0[c] is chunk c's J0.
+template <bool kDecrypt, int kRounds>
 __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks,
     const uint32_t* __restrict__ unit_base, const uint32_t* __restrict__ coarse_map,
     uint32_t nunits_total, uint32_t* __restrict__ counter, const uint8_t* __restrict__ ivs,
-    Block* __restrict__ ekj0, Block* __restrict__ sets) {
+    const Block* __restrict__ j0, Block* __restrict__ ekj0, Block* __restrict__ sets) {
     __shared__ BulkLds lds;
     // lookup addresses are formed as raw LDS addresses that assume this object starts at 0
     if (lds_offset(&lds) != 0) return;
@@ -646,9 +697,9 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     AesAddr A;
     aes_addr_init(A, lane);
     // the round keys stay in scalar registers for the whole kernel
-    uint32_t rk[60];
+    uint32_t rk[4 * (kRounds + 1)];
 #pragma unroll
-    for (int i = 0; i < 60; ++i) rk[i] = kt->rk[i];
+    for (int i = 0; i < 4 * (kRounds + 1); ++i) rk[i] = kt->rk[i];
 
     for (;;) {
         uint32_t item = 0;
@@ -671,12 +722,9 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
         const int64_t b1 = unit == 0 ? (int64_t)first_blocks : b0 + kUnitBlocks;
         const uint32_t nrows = (uint32_t)((b1 - b0 + kRowBlocks - 1) / kRowBlocks);
 
-        const uint8_t* ivp = ivs + (uint64_t)chunk * 12;
-        uint32_t iv[3];
-        for (int i = 0; i < 3; ++i)
-            iv[i] = (uint32_t)ivp[4 * i] | ((uint32_t)ivp[4 * i + 1] << 8) |
-                    ((uint32_t)ivp[4 * i + 2] << 16) | ((uint32_t)ivp[4 * i + 3] << 24);
-        const CtrConsts C = ctr_consts(rk, lane, iv[0], iv[1], iv[2]);
+        const Block j = chunk_j0(kt, ivs, j0, chunk);
+        const CtrConsts C = ctr_consts(rk, lane, j.w[0], j.w[1], j.w[2]);
+        const uint32_t ctr1 = bswap32(j.w[3]) + 1u;
 
         Block aad_y{{0, 0, 0, 0}};
         if (unit == 0 && cd->aad_len != 0) aad_y = aad_hash(kt, cd->aad, cd->aad_len);
@@ -687,19 +735,24 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
         int64_t row_blk = b1 - (int64_t)nrows * kRowBlocks;
         for (uint32_t r = 0; r < nrows; ++r, row_blk += kRowBlocks) {
             const bool edge = row_blk <= 0 || (unit + 1 == nunits && r + 1 == nrows);
-            bulk_row<kDecrypt>(rk, A, C, src, dst, len, row_blk + lane, edge, aad_y, ekj0 + chunk,
-                               y);
+            bulk_row<kDecrypt, kRounds>(rk, A, C, ctr1, src, dst, len, row_blk + lane, edge, aad_y,
+                                        ekj0 + chunk, y);
         }
         sets[(uint64_t)item * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
     }
 }
 
-template __global__ void bulk_kernel<false>(const KeyTables*, const ChunkDesc*, const uint32_t*,
-                                            const uint32_t*, uint32_t, uint32_t*, const uint8_t*,
-                                            Block*, Block*);
-template __global__ void bulk_kernel<true>(const KeyTables*, const ChunkDesc*, const uint32_t*,
-                                           const uint32_t*, uint32_t, uint32_t*, const uint8_t*,
-                                           Block*, Block*);
+#define PGCM_INSTANTIATE_BULK(D, R)                                                              \
+    template __global__ void bulk_kernel<D, R>(const KeyTables*, const ChunkDesc*, const uint32_t*, \
+                                               const uint32_t*, uint32_t, uint32_t*,                \
+                                               const uint8_t*, const Block*, Block*, Block*)
+PGCM_INSTANTIATE_BULK(false, 10);
+PGCM_INSTANTIATE_BULK(false, 12);
+PGCM_INSTANTIATE_BULK(false, 14);
+PGCM_INSTANTIATE_BULK(true, 10);
+PGCM_INSTANTIATE_BULK(true, 12);
+PGCM_INSTANTIATE_BULK(true, 14);
+#undef PGCM_INSTANTIATE_BULK
 
 // ------------------------------------------------------------------------------------------
 // Folding partial sets.  Consecutive sets of a chunk lie 2^power blocks apart, so, lane by lane,
@@ -773,7 +826,7 @@ constexpr uint32_t kFinalTables = 8;
 template <bool kDecrypt>
 __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks, uint32_t nchunks,
-    const uint8_t* __restrict__ ivs, const Block* __restrict__ ekj0,
+    const uint8_t* __restrict__ ivs, const Block* __restrict__ j0, const Block* __restrict__ ekj0,
     const Block* __restrict__ sets, uint8_t* __restrict__ tags, uint8_t* __restrict__ ok,
     uint32_t* __restrict__ counter) {
     __shared__ Block tables[kFinalTables][kNibbleTableEntries];
@@ -796,14 +849,10 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
         // and E_K(J0) is still to be computed
         const Block a = aad_hash(kt, cd.aad, cd.aad_len);
         y[0] = a.w[0], y[1] = a.w[1], y[2] = a.w[2], y[3] = a.w[3];
-        const uint8_t* ivp = ivs + (uint64_t)i * 12;
-        uint32_t j0[4];
-        for (int w = 0; w < 3; ++w)
-            j0[w] = (uint32_t)ivp[4 * w] | ((uint32_t)ivp[4 * w + 1] << 8) |
-                    ((uint32_t)ivp[4 * w + 2] << 16) | ((uint32_t)ivp[4 * w + 3] << 24);
-        j0[3] = 0x01000000u;  // be32(1)
-        aes256_block_global(kt, j0);
-        mask = Block{{j0[0], j0[1], j0[2], j0[3]}};
+        const Block j = chunk_j0(kt, ivs, j0, i);
+        uint32_t e[4] = {j.w[0], j.w[1], j.w[2], j.w[3]};
+        aes_block_global(kt, e);
+        mask = Block{{e[0], e[1], e[2], e[3]}};
     } else {
         uint32_t fold_table = 0xFFFFFFFFu;
         if (cd.final_power == kUnitPower) fold_table = lds_offset(tables[6]);
@@ -864,11 +913,11 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
 }
 
 template __global__ void final_kernel<false>(const KeyTables*, const ChunkDesc*, uint32_t,
-                                             const uint8_t*, const Block*, const Block*, uint8_t*,
-                                             uint8_t*, uint32_t*);
+                                             const uint8_t*, const Block*, const Block*,
+                                             const Block*, uint8_t*, uint8_t*, uint32_t*);
 template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, uint32_t,
-                                            const uint8_t*, const Block*, const Block*, uint8_t*,
-                                            uint8_t*, uint32_t*);
+                                            const uint8_t*, const Block*, const Block*,
+                                            const Block*, uint8_t*, uint8_t*, uint32_t*);
 
 // ------------------------------------------------------------------------------------------
 // The small-transfer path: a batch whose chunks are all at most kSmallChunkBytes long (the
@@ -879,11 +928,12 @@ template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, 
 // nibble tables of H^1 .. H^64.
 namespace {
 
-__device__ __forceinline__ void aes256_block_lds_plain(const uint32_t* __restrict__ rk,
-                                                       const uint32_t (*te)[256], uint32_t s[4]) {
+template <int kRounds>
+__device__ __forceinline__ void aes_block_lds_plain(const uint32_t* __restrict__ rk,
+                                                    const uint32_t (*te)[256], uint32_t s[4]) {
     uint32_t a0 = s[0] ^ rk[0], a1 = s[1] ^ rk[1], a2 = s[2] ^ rk[2], a3 = s[3] ^ rk[3];
 #pragma unroll
-    for (int r = 1; r < 14; ++r) {
+    for (int r = 1; r < kRounds; ++r) {
         uint32_t t0 = xor3(te[0][byte_of(a0, 0)], te[1][byte_of(a1, 1)], te[2][byte_of(a2, 2)]) ^
                       te[3][byte_of(a3, 3)] ^ rk[4 * r + 0];
         uint32_t t1 = xor3(te[0][byte_of(a1, 0)], te[1][byte_of(a2, 1)], te[2][byte_of(a3, 2)]) ^
@@ -900,18 +950,20 @@ __device__ __forceinline__ void aes256_block_lds_plain(const uint32_t* __restric
         uint32_t hi = __builtin_amdgcn_perm(te[2][byte_of(c2, 2)], te[3][byte_of(c3, 3)], 0x00040c0cu);
         return lo | hi;
     };
-    s[0] = last(a0, a1, a2, a3) ^ rk[56];
-    s[1] = last(a1, a2, a3, a0) ^ rk[57];
-    s[2] = last(a2, a3, a0, a1) ^ rk[58];
-    s[3] = last(a3, a0, a1, a2) ^ rk[59];
+    s[0] = last(a0, a1, a2, a3) ^ rk[4 * kRounds + 0];
+    s[1] = last(a1, a2, a3, a0) ^ rk[4 * kRounds + 1];
+    s[2] = last(a2, a3, a0, a1) ^ rk[4 * kRounds + 2];
+    s[3] = last(a3, a0, a1, a2) ^ rk[4 * kRounds + 3];
 }
 
 }  // namespace
 
-template <bool kDecrypt>
+// ivs: nchunks IVs of iv_len bytes each; J0 of an IV that is not 96 bits long is hashed here.
+template <bool kDecrypt, int kRounds>
 __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks_host, uint32_t nchunks,
-    const uint8_t* __restrict__ ivs, uint8_t* __restrict__ tags, uint8_t* __restrict__ ok) {
+    const uint8_t* __restrict__ ivs, uint32_t iv_len, uint8_t* __restrict__ tags,
+    uint8_t* __restrict__ ok) {
     __shared__ uint32_t te[4][256];
     __shared__ Block tables[7][kNibbleTableEntries];  // H^(2^k), k = 0 .. 6
     const uint32_t tid = threadIdx.x, lane = tid & 63;
@@ -927,13 +979,10 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
     uint32_t y[4] = {0, 0, 0, 0};
     Block aad_y{{0, 0, 0, 0}};
     if (cd.aad_len != 0) aad_y = aad_hash(kt, cd.aad, cd.aad_len);
-    const uint8_t* ivp = ivs + (uint64_t)i * 12;
-    uint32_t iv[3];
-    for (int w = 0; w < 3; ++w)
-        iv[w] = (uint32_t)ivp[4 * w] | ((uint32_t)ivp[4 * w + 1] << 8) |
-                ((uint32_t)ivp[4 * w + 2] << 16) | ((uint32_t)ivp[4 * w + 3] << 24);
+    const Block j = j0_from_iv(kt, ivs + (uint64_t)i * iv_len, iv_len);
+    const uint32_t ctr1 = bswap32(j.w[3]) + 1u;
 
-    // rows of 64 blocks aligned to the chunk's end; "block -1" (counter 1, i.e. J0) rides along
+    // rows of 64 blocks aligned to the chunk's end; "block -1" (counter block J0) rides along
     const int64_t nblk = (int64_t)((cd.len + 15) / 16);
     const uint32_t nrows = (uint32_t)((nblk + 1 + kRowBlocks - 1) / kRowBlocks);
     int64_t blk = nblk - (int64_t)nrows * kRowBlocks + lane;
@@ -955,8 +1004,8 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
             for (uint32_t b = 0; b < 15; ++b)
                 if (b < tail) x[b / 4] |= (uint32_t)sp[b] << (8 * (b % 4));
         }
-        uint32_t s[4] = {iv[0], iv[1], iv[2], bswap32((uint32_t)blk + 2u)};
-        aes256_block_lds_plain(rk, te, s);
+        uint32_t s[4] = {j.w[0], j.w[1], j.w[2], bswap32((uint32_t)blk + ctr1)};
+        aes_block_lds_plain<kRounds>(rk, te, s);
         if (r > 0) ghash_mul_lds(lds_offset(tables[kRowPower]), y);
         uint32_t o[4] = {x[0] ^ s[0], x[1] ^ s[1], x[2] ^ s[2], x[3] ^ s[3]};
         if (whole) {
@@ -1035,10 +1084,16 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
     }
 }
 
-template __global__ void small_kernel<false>(const KeyTables*, const ChunkDesc*, uint32_t,
-                                             const uint8_t*, uint8_t*, uint8_t*);
-template __global__ void small_kernel<true>(const KeyTables*, const ChunkDesc*, uint32_t,
-                                            const uint8_t*, uint8_t*, uint8_t*);
+#define PGCM_INSTANTIATE_SMALL(D, R)                                                      \
+    template __global__ void small_kernel<D, R>(const KeyTables*, const ChunkDesc*, uint32_t, \
+                                                const uint8_t*, uint32_t, uint8_t*, uint8_t*)
+PGCM_INSTANTIATE_SMALL(false, 10);
+PGCM_INSTANTIATE_SMALL(false, 12);
+PGCM_INSTANTIATE_SMALL(false, 14);
+PGCM_INSTANTIATE_SMALL(true, 10);
+PGCM_INSTANTIATE_SMALL(true, 12);
+PGCM_INSTANTIATE_SMALL(true, 14);
+#undef PGCM_INSTANTIATE_SMALL
 
 // Brings a batch's descriptors from pinned host memory into the device workspace.  Done by a
 // kernel so that the batch stays on one hardware queue: a DMA copy between kernels costs two

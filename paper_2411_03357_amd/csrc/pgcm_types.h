@@ -35,8 +35,10 @@ struct alignas(16) Block {
 };
 
 struct alignas(16) KeyTables {
-    uint32_t rk[60];       // AES-256 round key words, little-endian loads of the FIPS-197 bytes
-    uint32_t pad_[4];
+    uint32_t rk[60];       // round key words 0 .. 4 (rounds + 1) - 1, little-endian loads of the
+                           // FIPS-197 bytes; the rest zero
+    uint32_t rounds;       // Nr: 10, 12 or 14 for 128-, 192-, 256-bit keys (the paper's: 14)
+    uint32_t pad_[3];
     uint32_t te[4][256];   // round tables: te[r][x] = MixColumns contribution of S(x) in row r
     Block h;               // GHASH key H = E_K(0^128)
     Block ghash[kNumPowers][kNibbleTableEntries];

@@ -5,14 +5,26 @@ import torch
 import paper_2411_03357_amd as pgcm
 
 
+def expand(w):
+    """the workload's key on the GPU: the AES-256 entry point for 32-byte keys, the general one
+    otherwise"""
+    return pgcm.expand_key(w.key) if w.key.size == 32 else pgcm.expand_key_bytes(w.key)
+
+
 class DeviceBatch:
     """Device-resident inputs and outputs of one workload: packed payload buffer `plain`, packed
     ciphertext buffer `cipher`, packed decrypt output `back`, ivs, aad, tags, ok, and the host
     descriptor arrays the ABI takes."""
 
-    def __init__(self, w, plain: torch.Tensor, device="cuda"):
+    def __init__(self, w, plain: torch.Tensor, device="cuda", iv_entry=None):
+        """iv_entry: call the batch entry points that take an IV length (default: exactly when
+        the workload's IVs are not 12 bytes long)"""
         assert plain.dtype == torch.uint8 and plain.numel() == w.total_bytes
         self.w = w
+        iv_len = int(w.ivs.shape[1])
+        use_iv_entry = iv_len != 12 if iv_entry is None else iv_entry
+        assert use_iv_entry or iv_len == 12
+        self.iv_bytes = iv_len if use_iv_entry else None
         self.device = device
         self.plain = plain
         # bytes between chunks (alignment padding) are zero in all three buffers, so that whole
@@ -41,14 +53,15 @@ class DeviceBatch:
         src = self.plain if src is None else src
         dst = self.cipher if dst is None else dst
         pgcm.encrypt_batch(key, self.ivs, self.aad_ptrs, self.aad_lens, self.ptrs(src), self.lens,
-                           self.ptrs(dst), self.tags, stream)
+                           self.ptrs(dst), self.tags, stream, iv_bytes=self.iv_bytes)
 
     def decrypt(self, key, src=None, dst=None, tags=None, stream=None):
         src = self.cipher if src is None else src
         dst = self.back if dst is None else dst
         tags = self.tags if tags is None else tags
         pgcm.decrypt_verify_batch(key, self.ivs, self.aad_ptrs, self.aad_lens, self.ptrs(src),
-                                  self.lens, self.ptrs(dst), tags, self.ok, stream)
+                                  self.lens, self.ptrs(dst), tags, self.ok, stream,
+                                  iv_bytes=self.iv_bytes)
 
     def chunk_host(self, buf: torch.Tensor, i: int) -> np.ndarray:
         off, ln = int(self.w.offsets[i]), int(self.w.lens[i])

@@ -9,7 +9,7 @@ import torch
 import openssl_ref
 import oracle
 import workloads
-from gpu_harness import DeviceBatch, apply_tampers
+from gpu_harness import DeviceBatch, apply_tampers, expand
 
 import paper_2411_03357_amd as pgcm
 
@@ -26,11 +26,11 @@ def _oracle_encrypt(w, host_buf, idx=None):
     return cts, tags
 
 
-def _full_parity(w, flip=None):
+def _full_parity(w, flip=None, iv_entry=None):
     """encrypt + decrypt-verify of the whole workload compared with the oracle on every byte"""
     host = w.payload_host()
-    key = pgcm.expand_key(w.key)
-    b = DeviceBatch(w, torch.from_numpy(host).cuda())
+    key = expand(w)
+    b = DeviceBatch(w, torch.from_numpy(host).cuda(), iv_entry=iv_entry)
     b.cipher.fill_(0xEE)            # gaps between chunks must stay untouched
     b.encrypt(key)
     torch.cuda.synchronize()

@@ -40,8 +40,8 @@ class Tamper:
 class Workload:
     name: str
     seed: int
-    key: np.ndarray                 # (32,) uint8
-    ivs: np.ndarray                 # (n, 12) uint8
+    key: np.ndarray                 # (32,) uint8; (16,) or (24,) after with_cipher
+    ivs: np.ndarray                 # (n, 12) uint8; (n, iv_bytes) after with_cipher
     lens: np.ndarray                # (n,) uint64
     offsets: np.ndarray             # (n,) uint64 into the packed payload buffer
     total_bytes: int                # size of the packed buffer
@@ -219,6 +219,22 @@ def ragged_small(seed_shift: int = 0) -> Workload:
     aad = rng.integers(0, 256, int(sum(alens)), dtype=np.uint8)
     return Workload("ragged_small", seed, key, iv_sequence(iv0, lens.size), lens, offsets, total,
                     "u8", aad, aad_off)
+
+
+def with_cipher(w: Workload, key_bytes: int, iv_bytes: int) -> Workload:
+    """the same batch under another key length (16, 24, 32 bytes) and IV length: a fresh random
+    key and n distinct random IVs of iv_bytes bytes each (the paper's transport uses 32 and 12;
+    other users of AES-GCM do not)"""
+    import dataclasses
+    rng = np.random.default_rng([w.seed, 11, key_bytes, iv_bytes])
+    key = rng.integers(0, 256, key_bytes, dtype=np.uint8)
+    ivs = rng.integers(0, 256, (w.n, iv_bytes), dtype=np.uint8)
+    # distinct even when iv_bytes is tiny: the chunk index is written into the leading bytes
+    for i in range(w.n):
+        tagged = i.to_bytes(4, "big")[-min(4, iv_bytes):]
+        ivs[i, :len(tagged)] = np.frombuffer(tagged, np.uint8)
+    return dataclasses.replace(w, name="%s_k%d_iv%d" % (w.name, key_bytes, iv_bytes), key=key,
+                               ivs=ivs)
 
 
 FULL = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
