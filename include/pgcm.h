@@ -11,7 +11,7 @@
  * The cipher is AES-256 (FIPS-197) in GCM (NIST SP 800-38D) with 96-bit IVs and full 16-byte tags;
  * the entry points ending in _bytes and _iv open the cipher's other key lengths (128, 192 bits)
  * and IV lengths (SP 800-38D 5.2.1.1, 7.1 step 2) to users of the same transport other than the
- * paper's.  A batch uses one key; transfers under several keys are one batch per key.
+ * paper's, those ending in _keys take a key per chunk.
  *
  * Conventions for every call
  *   - "DEVICE" pointers address memory the current HIP device can access: its own memory, or
@@ -122,6 +122,31 @@ int pgcm_decrypt_verify_batch_iv(pgcm_key_t *key, size_t n, const uint8_t *ivs, 
                                  const void *const *aad, const uint32_t *aad_len,
                                  const void *const *src, const uint64_t *len, void *const *dst,
                                  const uint8_t *tags, uint8_t *ok, void *hip_stream);
+
+/*
+ * The two batch calls for chunks that do not all share one key (tenants, sessions or directions
+ * with keys of their own; the paper's transport has a single session key, section 2.2).
+ *   keys       HOST array of nkeys key objects, all created on the current device, any mix of key
+ *              lengths; nkeys >= 1.
+ *   key_index  HOST array of n entries: chunk i is processed under keys[key_index[i]];
+ *              an entry >= nkeys is PGCM_ERR_ARG.
+ *   ivs, iv_bytes, tags, ok and the other arrays: as for the _iv calls, indexed by chunk.
+ * The chunks are grouped by key, keeping their order, and each group runs as one batch of its key
+ * (so each key object's one-stream rule applies), the groups one after the other on hip_stream.
+ * All arguments are checked before anything is enqueued; if an allocation or a HIP call fails in
+ * a later group, the groups before it stay enqueued.
+ */
+int pgcm_encrypt_batch_keys(pgcm_key_t *const *keys, size_t nkeys, const uint32_t *key_index,
+                            size_t n, const uint8_t *ivs, uint32_t iv_bytes,
+                            const void *const *aad, const uint32_t *aad_len,
+                            const void *const *src, const uint64_t *len, void *const *dst,
+                            uint8_t *tags, void *hip_stream);
+int pgcm_decrypt_verify_batch_keys(pgcm_key_t *const *keys, size_t nkeys,
+                                   const uint32_t *key_index, size_t n, const uint8_t *ivs,
+                                   uint32_t iv_bytes, const void *const *aad,
+                                   const uint32_t *aad_len, const void *const *src,
+                                   const uint64_t *len, void *const *dst, const uint8_t *tags,
+                                   uint8_t *ok, void *hip_stream);
 
 /* Static text for a pgcm_status value. */
 const char *pgcm_strerror(int status);

@@ -10,6 +10,7 @@ _lib = None
 
 EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_encrypt_batch",
            "pgcm_decrypt_verify_batch", "pgcm_encrypt_batch_iv", "pgcm_decrypt_verify_batch_iv",
+           "pgcm_encrypt_batch_keys", "pgcm_decrypt_verify_batch_keys",
            "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_units", "pgcm_unit_bytes",
            "pgcm_set_timing", "pgcm_last_bulk_kernel_ms")
 
@@ -51,6 +52,12 @@ def load_library():
     lib.pgcm_decrypt_verify_batch_iv.argtypes = [vp, sz, vp, C.c_uint32, vp, vp, vp, vp, vp, vp,
                                                  vp, vp]
     lib.pgcm_decrypt_verify_batch_iv.restype = C.c_int
+    lib.pgcm_encrypt_batch_keys.argtypes = [vp, sz, vp, sz, vp, C.c_uint32, vp, vp, vp, vp, vp, vp,
+                                            vp]
+    lib.pgcm_encrypt_batch_keys.restype = C.c_int
+    lib.pgcm_decrypt_verify_batch_keys.argtypes = [vp, sz, vp, sz, vp, C.c_uint32, vp, vp, vp, vp,
+                                                   vp, vp, vp, vp]
+    lib.pgcm_decrypt_verify_batch_keys.restype = C.c_int
     lib.pgcm_strerror.argtypes = [C.c_int]
     lib.pgcm_strerror.restype = C.c_char_p
     lib.pgcm_last_hip_error.argtypes = []
@@ -196,6 +203,44 @@ def decrypt_verify_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, ok
     _check(load_library().pgcm_decrypt_verify_batch(
         key.handle, n, _dev_ptr(ivs), _addr(aad_a), _addr(alen_a), _addr(src_a), _addr(len_a),
         _addr(dst_a), _dev_ptr(tags), _dev_ptr(ok), _stream_handle(stream)))
+
+
+def _key_handles(keys):
+    return np.array([k.handle for k in keys], np.uint64)
+
+
+def encrypt_batch_keys(keys, key_index, ivs, iv_bytes, aad, aad_len, src, length, dst, tags,
+                       stream=None):
+    """pgcm_encrypt_batch_keys: keys is a sequence of Key objects, key_index n indices into it."""
+    n = len(length)
+    handles = _key_handles(keys)
+    idx_a = _host_array(key_index, np.uint32, n, "key_index")
+    src_a = _host_array(src, np.uint64, n, "src")
+    dst_a = _host_array(dst, np.uint64, n, "dst")
+    len_a = _host_array(length, np.uint64, n, "length")
+    aad_a = _host_array(aad, np.uint64, n, "aad")
+    alen_a = _host_array(aad_len, np.uint32, n, "aad_len")
+    _check(load_library().pgcm_encrypt_batch_keys(
+        _addr(handles) if handles.size else None, handles.size, _addr(idx_a), n, _dev_ptr(ivs),
+        iv_bytes, _addr(aad_a), _addr(alen_a), _addr(src_a), _addr(len_a), _addr(dst_a),
+        _dev_ptr(tags), _stream_handle(stream)))
+
+
+def decrypt_verify_batch_keys(keys, key_index, ivs, iv_bytes, aad, aad_len, src, length, dst, tags,
+                              ok, stream=None):
+    """pgcm_decrypt_verify_batch_keys"""
+    n = len(length)
+    handles = _key_handles(keys)
+    idx_a = _host_array(key_index, np.uint32, n, "key_index")
+    src_a = _host_array(src, np.uint64, n, "src")
+    dst_a = _host_array(dst, np.uint64, n, "dst")
+    len_a = _host_array(length, np.uint64, n, "length")
+    aad_a = _host_array(aad, np.uint64, n, "aad")
+    alen_a = _host_array(aad_len, np.uint32, n, "aad_len")
+    _check(load_library().pgcm_decrypt_verify_batch_keys(
+        _addr(handles) if handles.size else None, handles.size, _addr(idx_a), n, _dev_ptr(ivs),
+        iv_bytes, _addr(aad_a), _addr(alen_a), _addr(src_a), _addr(len_a), _addr(dst_a),
+        _dev_ptr(tags), _dev_ptr(ok), _stream_handle(stream)))
 
 
 def plan_units(length):

@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <new>
+#include <vector>
 
 #include "../../include/pgcm.h"
 #include "pgcm_kernels.h"
@@ -144,11 +145,10 @@ void launch_small(int rounds, dim3 grid, hipStream_t stream, Args... args) {
         hipLaunchKernelGGL((small_kernel<kDecrypt, 14>), grid, block, 0, stream, args...);
 }
 
-int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, uint32_t iv_len,
-              const void* const* aad, const uint32_t* aad_len, const void* const* src,
-              const uint64_t* len, void* const* dst, uint8_t* tags, uint8_t* ok,
-              void* hip_stream) {
-    if (key == nullptr || key->tables == nullptr) return PGCM_ERR_ARG;
+// what must hold for the arrays of a batch as a whole
+int check_batch(size_t n, const uint8_t* ivs, uint32_t iv_len, const void* const* aad,
+                const uint32_t* aad_len, const void* const* src, const uint64_t* len,
+                void* const* dst, const uint8_t* tags, bool decrypt, const uint8_t* ok) {
     if (iv_len == 0) return PGCM_ERR_ARG;  // GCM takes no empty IV
     if (n == 0) return PGCM_OK;
     if (ivs == nullptr || src == nullptr || len == nullptr || dst == nullptr || tags == nullptr)
@@ -156,20 +156,42 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, uint32_
     if ((aad == nullptr) != (aad_len == nullptr)) return PGCM_ERR_ARG;
     if (decrypt && ok == nullptr) return PGCM_ERR_ARG;
     if (n > 0x7FFFFFFFull) return PGCM_ERR_ARG;
+    return PGCM_OK;
+}
+
+// ... and for one of its chunks
+inline int check_chunk(size_t i, const void* const* aad, const uint32_t* aad_len,
+                       const void* const* src, const uint64_t* len, void* const* dst) {
+    if (len[i] > PGCM_MAX_CHUNK_BYTES) return PGCM_ERR_LEN;
+    if (len[i] != 0) {
+        if (src[i] == nullptr || dst[i] == nullptr) return PGCM_ERR_ARG;
+        if (((uintptr_t)src[i] | (uintptr_t)dst[i]) & 15) return PGCM_ERR_ALIGN;
+    }
+    if (aad_len != nullptr && aad_len[i] != 0 && aad[i] == nullptr) return PGCM_ERR_ARG;
+    return PGCM_OK;
+}
+
+// One batch under one key.  `order` (may be null) picks the batch's chunks out of the caller's
+// arrays: chunk k of the batch is the caller's chunk order[k]; null means 0, 1, .., n - 1.
+int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, const uint8_t* ivs,
+              uint32_t iv_len, const void* const* aad, const uint32_t* aad_len,
+              const void* const* src, const uint64_t* len, void* const* dst, uint8_t* tags,
+              uint8_t* ok, void* hip_stream) {
+    if (key == nullptr || key->tables == nullptr) return PGCM_ERR_ARG;
+    int rc = check_batch(n, ivs, iv_len, aad, aad_len, src, len, dst, tags, decrypt, ok);
+    if (rc != PGCM_OK || n == 0) return rc;
+    auto at = [order](size_t k) -> size_t { return order ? order[k] : k; };
 
     // validate everything before touching any state
     const uint32_t nchunks = (uint32_t)n;
     uint64_t nunits64 = 0, nslots64 = 0;
     uint64_t fold_items64[kMaxLevels] = {0, 0, 0, 0};
     bool all_small = true;
-    for (size_t i = 0; i < n; ++i) {
-        if (len[i] > PGCM_MAX_CHUNK_BYTES) return PGCM_ERR_LEN;
+    for (size_t k = 0; k < n; ++k) {
+        const size_t i = at(k);
+        rc = check_chunk(i, aad, aad_len, src, len, dst);
+        if (rc != PGCM_OK) return rc;
         if (len[i] > kSmallChunkBytes) all_small = false;
-        if (len[i] != 0) {
-            if (src[i] == nullptr || dst[i] == nullptr) return PGCM_ERR_ARG;
-            if (((uintptr_t)src[i] | (uintptr_t)dst[i]) & 15) return PGCM_ERR_ALIGN;
-        }
-        if (aad_len != nullptr && aad_len[i] != 0 && aad[i] == nullptr) return PGCM_ERR_ARG;
         const uint32_t nu = plan_chunk(len[i]).nunits;
         uint32_t outs[kMaxLevels];
         const uint32_t levels = fold_levels(nu, outs);
@@ -200,12 +222,14 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, uint32_
         // small-transfer path: one kernel, descriptors read straight from the pinned staging
         // buffer, no device workspace
         const int s = key->next_stage;
-        int rc = ensure_stage(key, s, sizeof(ChunkDesc) * n);
+        rc = ensure_stage(key, s, sizeof(ChunkDesc) * n);
         if (rc != PGCM_OK) return rc;
         ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(key->stage[s]);
-        for (size_t i = 0; i < n; ++i) {
-            ChunkDesc& d = h_desc[i];
+        for (size_t k = 0; k < n; ++k) {
+            const size_t i = at(k);
+            ChunkDesc& d = h_desc[k];
             memset(&d, 0, sizeof(d));
+            d.index = (uint32_t)i;
             d.src = (const uint8_t*)src[i];
             d.dst = (uint8_t*)dst[i];
             d.len = len[i];
@@ -246,7 +270,7 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, uint32_
     const size_t work_bytes = off_sets + sizeof(Block) * 64 * (size_t)nslots;
 
     const int s = key->next_stage;
-    int rc = ensure_stage(key, s, upload_bytes);
+    rc = ensure_stage(key, s, upload_bytes);
     if (rc != PGCM_OK) return rc;
     rc = ensure_work(key, work_bytes, stream);
     if (rc != PGCM_OK) return rc;
@@ -257,9 +281,10 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, uint32_
     FoldItem* h_fold = reinterpret_cast<FoldItem*>(key->stage[s] + off_fold);
     uint32_t unit = 0, slot = nunits, coarse_next = 0;
     uint32_t fold_fill[kMaxLevels] = {0, 0, 0, 0};
-    for (size_t i = 0; i < n; ++i) {
+    for (size_t k = 0; k < n; ++k) {
+        const size_t i = at(k);
         const UnitPlan p = plan_chunk(len[i]);
-        ChunkDesc& d = h_desc[i];
+        ChunkDesc& d = h_desc[k];
         d.src = (const uint8_t*)src[i];
         d.dst = (uint8_t*)dst[i];
         d.len = len[i];
@@ -268,11 +293,11 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, uint32_
         d.unit_base = unit;
         d.nunits = p.nunits;
         d.first_blocks = p.first_blocks;
-        d.pad_ = 0;
-        h_ubase[i] = unit;
+        d.index = (uint32_t)i;
+        h_ubase[k] = unit;
         // coarse map: for every 2^kCoarseShift-th unit, the chunk that holds it
         while (coarse_next < ncoarse && ((uint64_t)coarse_next << kCoarseShift) < (uint64_t)unit + p.nunits) {
-            h_coarse[coarse_next++] = (uint32_t)i;
+            h_coarse[coarse_next++] = (uint32_t)k;
         }
         // fold levels: groups of kFan sets counted back from the end, the first one short
         uint32_t base = unit, count = p.nunits, power = kUnitPower, level = 0;
@@ -323,7 +348,7 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, uint32_
     Block* d_j0 = iv_len == 12 ? nullptr : reinterpret_cast<Block*>(key->work + off_j0);
     if (d_j0 != nullptr)
         hipLaunchKernelGGL(j0_kernel, dim3((nchunks + 63) / 64), dim3(64), 0, stream, key->tables,
-                           ivs, iv_len, nchunks, d_j0);
+                           d_desc, ivs, iv_len, nchunks, d_j0);
 
     // the unit counter is left at zero by the last kernel of every batch; it only needs clearing
     // when the workspace is new (or has moved) or an earlier batch was cut short
@@ -367,6 +392,49 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint8_t* ivs, uint32_
     }
     PGCM_HIP(hipGetLastError());
     key->counter_dirty = false;
+    return PGCM_OK;
+}
+
+// A batch whose chunks name their key: the chunks are grouped by key (keeping their order) and
+// every group runs as one batch of its key, one after the other on the stream.
+int run_batch_keys(bool decrypt, pgcm_key* const* keys, size_t nkeys, const uint32_t* key_index,
+                   size_t n, const uint8_t* ivs, uint32_t iv_len, const void* const* aad,
+                   const uint32_t* aad_len, const void* const* src, const uint64_t* len,
+                   void* const* dst, uint8_t* tags, uint8_t* ok, void* hip_stream) {
+    if (keys == nullptr || nkeys == 0 || nkeys > 0x7FFFFFFFull) return PGCM_ERR_ARG;
+    int cur_device = -1;
+    PGCM_HIP(hipGetDevice(&cur_device));
+    for (size_t k = 0; k < nkeys; ++k)
+        if (keys[k] == nullptr || keys[k]->tables == nullptr || keys[k]->device != cur_device)
+            return PGCM_ERR_ARG;
+    int rc = check_batch(n, ivs, iv_len, aad, aad_len, src, len, dst, tags, decrypt, ok);
+    if (rc != PGCM_OK || n == 0) return rc;
+    if (key_index == nullptr) return PGCM_ERR_ARG;
+    // every chunk is checked before the first group is enqueued
+    std::vector<uint32_t> first, fill, order;
+    try {
+        first.assign(nkeys + 1, 0);
+        fill.assign(nkeys, 0);
+        order.resize(n);
+    } catch (const std::bad_alloc&) {
+        return PGCM_ERR_NOMEM;
+    }
+    for (size_t i = 0; i < n; ++i) {
+        if (key_index[i] >= nkeys) return PGCM_ERR_ARG;
+        rc = check_chunk(i, aad, aad_len, src, len, dst);
+        if (rc != PGCM_OK) return rc;
+        ++first[key_index[i] + 1];
+    }
+    for (size_t k = 0; k < nkeys; ++k) first[k + 1] += first[k];
+    for (size_t k = 0; k < nkeys; ++k) fill[k] = first[k];
+    for (size_t i = 0; i < n; ++i) order[fill[key_index[i]]++] = (uint32_t)i;
+    for (size_t k = 0; k < nkeys; ++k) {
+        const size_t count = first[k + 1] - first[k];
+        if (count == 0) continue;
+        rc = run_batch(decrypt, keys[k], count, order.data() + first[k], ivs, iv_len, aad, aad_len,
+                       src, len, dst, tags, ok, hip_stream);
+        if (rc != PGCM_OK) return rc;
+    }
     return PGCM_OK;
 }
 
@@ -446,14 +514,14 @@ void pgcm_free_key(pgcm_key_t* k) {
 int pgcm_encrypt_batch(pgcm_key_t* key, size_t n, const uint8_t* ivs, const void* const* aad,
                        const uint32_t* aad_len, const void* const* src, const uint64_t* len,
                        void* const* dst, uint8_t* tags, void* hip_stream) {
-    return run_batch(false, key, n, ivs, 12, aad, aad_len, src, len, dst, tags, nullptr,
+    return run_batch(false, key, n, nullptr, ivs, 12, aad, aad_len, src, len, dst, tags, nullptr,
                      hip_stream);
 }
 
 int pgcm_encrypt_batch_iv(pgcm_key_t* key, size_t n, const uint8_t* ivs, uint32_t iv_bytes,
                           const void* const* aad, const uint32_t* aad_len, const void* const* src,
                           const uint64_t* len, void* const* dst, uint8_t* tags, void* hip_stream) {
-    return run_batch(false, key, n, ivs, iv_bytes, aad, aad_len, src, len, dst, tags, nullptr,
+    return run_batch(false, key, n, nullptr, ivs, iv_bytes, aad, aad_len, src, len, dst, tags, nullptr,
                      hip_stream);
 }
 
@@ -461,7 +529,7 @@ int pgcm_decrypt_verify_batch(pgcm_key_t* key, size_t n, const uint8_t* ivs,
                               const void* const* aad, const uint32_t* aad_len,
                               const void* const* src, const uint64_t* len, void* const* dst,
                               const uint8_t* tags, uint8_t* ok, void* hip_stream) {
-    return run_batch(true, key, n, ivs, 12, aad, aad_len, src, len, dst,
+    return run_batch(true, key, n, nullptr, ivs, 12, aad, aad_len, src, len, dst,
                      const_cast<uint8_t*>(tags), ok, hip_stream);
 }
 
@@ -469,8 +537,27 @@ int pgcm_decrypt_verify_batch_iv(pgcm_key_t* key, size_t n, const uint8_t* ivs, 
                                  const void* const* aad, const uint32_t* aad_len,
                                  const void* const* src, const uint64_t* len, void* const* dst,
                                  const uint8_t* tags, uint8_t* ok, void* hip_stream) {
-    return run_batch(true, key, n, ivs, iv_bytes, aad, aad_len, src, len, dst,
+    return run_batch(true, key, n, nullptr, ivs, iv_bytes, aad, aad_len, src, len, dst,
                      const_cast<uint8_t*>(tags), ok, hip_stream);
+}
+
+int pgcm_encrypt_batch_keys(pgcm_key_t* const* keys, size_t nkeys, const uint32_t* key_index,
+                            size_t n, const uint8_t* ivs, uint32_t iv_bytes,
+                            const void* const* aad, const uint32_t* aad_len,
+                            const void* const* src, const uint64_t* len, void* const* dst,
+                            uint8_t* tags, void* hip_stream) {
+    return run_batch_keys(false, keys, nkeys, key_index, n, ivs, iv_bytes, aad, aad_len, src, len,
+                          dst, tags, nullptr, hip_stream);
+}
+
+int pgcm_decrypt_verify_batch_keys(pgcm_key_t* const* keys, size_t nkeys,
+                                   const uint32_t* key_index, size_t n, const uint8_t* ivs,
+                                   uint32_t iv_bytes, const void* const* aad,
+                                   const uint32_t* aad_len, const void* const* src,
+                                   const uint64_t* len, void* const* dst, const uint8_t* tags,
+                                   uint8_t* ok, void* hip_stream) {
+    return run_batch_keys(true, keys, nkeys, key_index, n, ivs, iv_bytes, aad, aad_len, src, len,
+                          dst, const_cast<uint8_t*>(tags), ok, hip_stream);
 }
 
 const char* pgcm_strerror(int status) {

@@ -8,8 +8,8 @@ namespace pgcm {
 
 __global__ void expand_key_kernel(KeyTables* kt, const uint32_t* key_words, uint32_t nk);
 
-__global__ void j0_kernel(const KeyTables* kt, const uint8_t* ivs, uint32_t iv_len,
-                          uint32_t nchunks, Block* j0);
+__global__ void j0_kernel(const KeyTables* kt, const ChunkDesc* chunks, const uint8_t* ivs,
+                          uint32_t iv_len, uint32_t nchunks, Block* j0);
 
 // kRounds: 10, 12 or 14
 template <bool kDecrypt, int kRounds>

@@ -277,22 +277,25 @@ __device__ Block j0_from_iv(const KeyTables* __restrict__ kt, const uint8_t* __r
     return gf_mul_table(kt->ghash[0], y);
 }
 
-// A chunk's J0: read from `j0` when the host had it hashed beforehand (IVs that are not 96 bits
-// long), otherwise formed from the IV bytes.
+// J0 of the batch's chunk number `chunk`: read from `j0` when the host had it hashed beforehand
+// (IVs that are not 96 bits long), otherwise formed from the IV bytes, which sit at the chunk's
+// place `index` in the caller's array.
 __device__ __forceinline__ Block chunk_j0(const KeyTables* __restrict__ kt,
                                           const uint8_t* __restrict__ ivs,
-                                          const Block* __restrict__ j0, uint32_t chunk) {
+                                          const Block* __restrict__ j0, uint32_t chunk,
+                                          uint32_t index) {
     if (j0 != nullptr) return j0[chunk];
-    return j0_from_iv(kt, ivs + (uint64_t)chunk * 12, 12);
+    return j0_from_iv(kt, ivs + (uint64_t)index * 12, 12);
 }
 }  // namespace
 
 // One thread per chunk: J0 of IVs whose length is not 96 bits, for the kernels that follow.
 __global__ __launch_bounds__(64) void j0_kernel(const KeyTables* __restrict__ kt,
+                                                const ChunkDesc* __restrict__ chunks,
                                                 const uint8_t* __restrict__ ivs, uint32_t iv_len,
                                                 uint32_t nchunks, Block* __restrict__ j0) {
     const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < nchunks) j0[i] = j0_from_iv(kt, ivs + (uint64_t)i * iv_len, iv_len);
+    if (i < nchunks) j0[i] = j0_from_iv(kt, ivs + (uint64_t)chunks[i].index * iv_len, iv_len);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -672,7 +675,7 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
 // chunks); coarse_map[i >> kCoarseShift] is a chunk at or before the right one.
 // sets[i * 64 + lane] receives lane's GHASH sum over the unit's rows:
 //   sum over rows r of C(r, lane) * (H^64)^(rows after r).
-// ivs: the chunks' 96-bit IVs, read when j0 is null; otherwise j0[c] is chunk c's J0.
+// ivs: 96-bit IVs (a chunk's at its `index`), read when j0 is null; otherwise j0[c] is chunk c's J0.
 template <bool kDecrypt, int kRounds>
 __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks,
@@ -722,7 +725,7 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
         const int64_t b1 = unit == 0 ? (int64_t)first_blocks : b0 + kUnitBlocks;
         const uint32_t nrows = (uint32_t)((b1 - b0 + kRowBlocks - 1) / kRowBlocks);
 
-        const Block j = chunk_j0(kt, ivs, j0, chunk);
+        const Block j = chunk_j0(kt, ivs, j0, chunk, cd->index);
         const CtrConsts C = ctr_consts(rk, lane, j.w[0], j.w[1], j.w[2]);
         const uint32_t ctr1 = bswap32(j.w[3]) + 1u;
 
@@ -849,7 +852,7 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
         // and E_K(J0) is still to be computed
         const Block a = aad_hash(kt, cd.aad, cd.aad_len);
         y[0] = a.w[0], y[1] = a.w[1], y[2] = a.w[2], y[3] = a.w[3];
-        const Block j = chunk_j0(kt, ivs, j0, i);
+        const Block j = chunk_j0(kt, ivs, j0, i, cd.index);
         uint32_t e[4] = {j.w[0], j.w[1], j.w[2], j.w[3]};
         aes_block_global(kt, e);
         mask = Block{{e[0], e[1], e[2], e[3]}};
@@ -891,7 +894,7 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
     ghash_mul_lds(lds_offset(tables[0]), y);
     const uint32_t t[4] = {y[0] ^ mask.w[0], y[1] ^ mask.w[1], y[2] ^ mask.w[2], y[3] ^ mask.w[3]};
 
-    uint8_t* tp = tags + (uint64_t)i * 16;
+    uint8_t* tp = tags + (uint64_t)cd.index * 16;
     if (!kDecrypt) {
         if (lane == 0)
             for (int b = 0; b < 16; ++b) tp[b] = (uint8_t)(t[b / 4] >> (8 * (b % 4)));
@@ -900,7 +903,7 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
         uint32_t diff = 0;
         for (int b = 0; b < 16; ++b) diff |= (uint32_t)tp[b] ^ ((t[b / 4] >> (8 * (b % 4))) & 0xFF);
         diff = __builtin_amdgcn_readfirstlane(diff);
-        if (lane == 0) ok[i] = diff == 0 ? 1 : 0;
+        if (lane == 0) ok[cd.index] = diff == 0 ? 1 : 0;
         if (diff != 0) {
             // rejected: unauthenticated plaintext must not stay behind; the wavefront zero-fills
             // exactly len bytes
@@ -958,7 +961,8 @@ __device__ __forceinline__ void aes_block_lds_plain(const uint32_t* __restrict__
 
 }  // namespace
 
-// ivs: nchunks IVs of iv_len bytes each; J0 of an IV that is not 96 bits long is hashed here.
+// ivs: IVs of iv_len bytes each, a chunk's at its `index`; J0 of an IV that is not 96 bits long is
+// hashed here.
 template <bool kDecrypt, int kRounds>
 __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks_host, uint32_t nchunks,
@@ -979,7 +983,7 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
     uint32_t y[4] = {0, 0, 0, 0};
     Block aad_y{{0, 0, 0, 0}};
     if (cd.aad_len != 0) aad_y = aad_hash(kt, cd.aad, cd.aad_len);
-    const Block j = j0_from_iv(kt, ivs + (uint64_t)i * iv_len, iv_len);
+    const Block j = j0_from_iv(kt, ivs + (uint64_t)cd.index * iv_len, iv_len);
     const uint32_t ctr1 = bswap32(j.w[3]) + 1u;
 
     // rows of 64 blocks aligned to the chunk's end; "block -1" (counter block J0) rides along
@@ -1066,7 +1070,7 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
     ghash_mul_lds(lds_offset(tables[0]), y);
     const uint32_t t[4] = {y[0] ^ mask[0], y[1] ^ mask[1], y[2] ^ mask[2], y[3] ^ mask[3]};
 
-    uint8_t* tp = tags + (uint64_t)i * 16;
+    uint8_t* tp = tags + (uint64_t)cd.index * 16;
     if (!kDecrypt) {
         if (lane == 0)
             for (int b = 0; b < 16; ++b) tp[b] = (uint8_t)(t[b / 4] >> (8 * (b % 4)));
@@ -1074,7 +1078,7 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
         uint32_t diff = 0;
         for (int b = 0; b < 16; ++b) diff |= (uint32_t)tp[b] ^ ((t[b / 4] >> (8 * (b % 4))) & 0xFF);
         diff = __builtin_amdgcn_readfirstlane(diff);
-        if (lane == 0) ok[i] = diff == 0 ? 1 : 0;
+        if (lane == 0) ok[cd.index] = diff == 0 ? 1 : 0;
         if (diff != 0) {
             const uint64_t whole = cd.len / 16;
             uint4* d = reinterpret_cast<uint4*>(cd.dst);

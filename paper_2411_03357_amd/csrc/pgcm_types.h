@@ -56,7 +56,7 @@ struct alignas(16) ChunkDesc {
     uint32_t final_base;    // first set slot the final step folds
     uint32_t final_count;   // number of sets it folds: 1..32, or 0 for an empty chunk
     uint32_t final_power;   // log2 of the distance, in blocks, between consecutive such sets
-    uint32_t pad_;
+    uint32_t index;         // the chunk's place in the caller's ivs, tags and ok arrays
 };
 static_assert(sizeof(ChunkDesc) == 64, "descriptor layout");
 

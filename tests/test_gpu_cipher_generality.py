@@ -96,3 +96,76 @@ def test_lengths_the_cipher_does_not_have_are_errors():
         b.decrypt(key)
     assert e.value.status == -1
     key.free()
+
+
+@pytest.mark.parametrize("iv_bytes", [12, 16])
+def test_several_keys_in_one_batch(iv_bytes):
+    """every chunk names its key; groups of one key take the bulk or the small-transfer path on
+    their own (key 3 only gets chunks of at most 8 KiB), ivs / tags / ok stay indexed by chunk"""
+    w = workloads.with_cipher(workloads.ragged_small(), 32, iv_bytes)
+    rng = np.random.default_rng(workloads.BASE_SEED + 99 + iv_bytes)
+    raw_keys = [rng.integers(0, 256, kb, dtype=np.uint8) for kb in (32, 16, 24, 32, 16)]
+    key_index = rng.integers(0, 3, w.n).astype(np.uint32)
+    key_index[w.lens <= 8192] = rng.integers(0, 4, int((w.lens <= 8192).sum()))   # key 4: unused
+    assert set(key_index.tolist()) == {0, 1, 2, 3}
+    keys = [pgcm.expand_key_bytes(k) for k in raw_keys]
+    host = w.payload_host()
+    b = DeviceBatch(w, torch.from_numpy(host).cuda())
+    b.cipher.fill_(0xEE)
+    pgcm.encrypt_batch_keys(keys, key_index, b.ivs, iv_bytes, b.aad_ptrs, b.aad_lens,
+                            b.ptrs(b.plain), b.lens, b.ptrs(b.cipher), b.tags)
+    torch.cuda.synchronize()
+    cipher = b.cipher.cpu().numpy()
+    tags = b.tags.cpu().numpy().reshape(-1, 16)
+    expect = np.full(w.total_bytes, 0xEE, np.uint8)
+    for i in range(w.n):
+        ct, tag = oracle.encrypt(raw_keys[key_index[i]], w.ivs[i], w.aad_of(i), w.chunk(host, i))
+        off = int(w.offsets[i])
+        expect[off:off + len(ct)] = np.frombuffer(ct, np.uint8)
+        assert tags[i].tobytes() == tag, i
+    assert np.array_equal(cipher, expect)
+
+    # decrypt: one chunk tampered, one chunk given to the wrong key
+    bad_ct, wrong_key = 14, 20
+    cipher_t = b.cipher.clone()
+    cipher_t[int(w.offsets[bad_ct]) + 7] ^= 0x20
+    idx2 = key_index.copy()
+    idx2[wrong_key] = (idx2[wrong_key] + 1) % 3
+    b.back.fill_(0xDD)
+    pgcm.decrypt_verify_batch_keys(keys, idx2, b.ivs, iv_bytes, b.aad_ptrs, b.aad_lens,
+                                   b.ptrs(cipher_t), b.lens, b.ptrs(b.back), b.tags, b.ok)
+    torch.cuda.synchronize()
+    ok = b.ok.cpu().numpy()
+    back = b.back.cpu().numpy()
+    expect = np.full(w.total_bytes, 0xDD, np.uint8)
+    for i in range(w.n):
+        off, ln = int(w.offsets[i]), int(w.lens[i])
+        good = i not in (bad_ct, wrong_key)
+        assert ok[i] == (1 if good else 0), i
+        expect[off:off + ln] = host[off:off + ln] if good else 0
+    assert np.array_equal(back, expect)
+
+    # argument errors: nothing may be enqueued, outputs stay as they are
+    before = b.tags.clone()
+    idx3 = key_index.copy()
+    idx3[5] = len(keys)
+    with pytest.raises(pgcm.PgcmError) as e:
+        pgcm.encrypt_batch_keys(keys, idx3, b.ivs, iv_bytes, b.aad_ptrs, b.aad_lens,
+                                b.ptrs(b.plain), b.lens, b.ptrs(b.cipher), b.tags)
+    assert e.value.status == -1
+    with pytest.raises(pgcm.PgcmError) as e:
+        pgcm.encrypt_batch_keys([], key_index, b.ivs, iv_bytes, b.aad_ptrs, b.aad_lens,
+                                b.ptrs(b.plain), b.lens, b.ptrs(b.cipher), b.tags)
+    assert e.value.status == -1
+    misaligned = b.ptrs(b.plain).copy()
+    misaligned[w.n - 1] += 4     # the last chunk, in the last group: still nothing is enqueued
+    b.tags.zero_()
+    with pytest.raises(pgcm.PgcmError) as e:
+        pgcm.encrypt_batch_keys(keys, key_index, b.ivs, iv_bytes, b.aad_ptrs, b.aad_lens,
+                                misaligned, b.lens, b.ptrs(b.cipher), b.tags)
+    assert e.value.status == -2
+    torch.cuda.synchronize()
+    assert not bool(b.tags.any())
+    b.tags.copy_(before)
+    for k in keys:
+        k.free()
