@@ -74,6 +74,8 @@ def main():
                     help="AES key length; the headline (and the paper's transport) is 32")
     ap.add_argument("--iv-bytes", type=int, default=12,
                     help="IV length; the headline (and the paper's transport) is 12")
+    ap.add_argument("--unit-bytes", type=int, default=0,
+                    help="force the scheduler's unit size (1024 .. 16384); 0: its own choice")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-chunks", type=int, default=0)
     ap.add_argument("--host-bounce", action="store_true",
@@ -101,6 +103,7 @@ def main():
     if not headline_cipher:
         w = workloads.with_cipher(w, args.key_bytes, args.iv_bytes)
     key = pgcm.expand_key(w.key) if args.key_bytes == 32 else pgcm.expand_key_bytes(w.key)
+    pgcm.set_unit_bytes(key, args.unit_bytes)
     b = DeviceBatch(w, w.payload_device())
     if args.host_bounce:
         b.cipher = torch.zeros(w.total_bytes, dtype=torch.uint8, pin_memory=True)
@@ -191,7 +194,7 @@ def main():
         "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": w.name, "chunks": w.n, "payload_bytes": payload,
-                   "step": "encrypt batch + decrypt-verify batch", "unit_bytes": pgcm.unit_bytes(),
+                   "step": "encrypt batch + decrypt-verify batch", "unit_bytes": args.unit_bytes or pgcm.batch_unit_bytes(w.lens),
                    "key_bytes": args.key_bytes, "iv_bytes": args.iv_bytes,
                    "ciphertext": "pinned host memory" if args.host_bounce else "device memory"},
         "enc_GBps": round(payload / (enc_ms[len(enc_ms) // 2] * 1e-3) / 1e9, 2),

@@ -45,7 +45,8 @@ typedef enum {
     PGCM_ERR_ARG = -1,   /* a required pointer is NULL, n is too large, a key or IV length is
                             not allowed, or the key lives on another GPU */
     PGCM_ERR_ALIGN = -2, /* a src or dst pointer is not 16-byte aligned */
-    PGCM_ERR_LEN = -3,   /* a chunk is longer than 2^36 - 32 bytes (the GCM limit) */
+    PGCM_ERR_LEN = -3,   /* a chunk is longer than 2^36 - 32 bytes (the GCM limit), or than a
+                            forced unit size allows (pgcm_set_unit_bytes) */
     PGCM_ERR_NOMEM = -4, /* host or device allocation failed */
     PGCM_ERR_HIP = -5    /* a HIP call failed; see pgcm_last_hip_error */
 } pgcm_status;
@@ -156,9 +157,9 @@ int pgcm_last_hip_error(void);
 
 /*
  * Host-only view of the chunk-to-wavefront schedule (section 5.1: requests arrive as batches of
- * copies of differing sizes).  Every chunk is cut into units of pgcm_unit_bytes() bytes counted
- * back from its end, so only a chunk's first unit can be short; wavefronts take units one at a
- * time from a shared counter.  Every unit leaves 64 partial hash sums; a chunk's sums are folded
+ * copies of differing sizes).  Every chunk is cut into units of pgcm_batch_unit_bytes(n, len)
+ * bytes counted back from its end, so only a chunk's first unit can be short; wavefronts take
+ * units one at a time from a shared counter.  Every unit leaves 64 partial hash sums; a chunk's sums are folded
  * 32 units at a time, level by level, until at most 32 remain for the chunk's final step.
  * Fills, for chunk i: nunits[i] (0 for an empty chunk), first_blocks[i] (16-byte blocks in its
  * first unit), unit_base[i] (index of its first unit among all units of the batch),
@@ -171,6 +172,24 @@ int64_t pgcm_plan_units(size_t n, const uint64_t *len, uint32_t *nunits, uint32_
 
 /* Bytes per full unit (a multiple of the 1 KiB a wavefront handles per step). */
 uint32_t pgcm_unit_bytes(void);
+
+/*
+ * Bytes per unit for a batch with these chunk lengths (len: HOST array of n byte counts): the
+ * smallest power of two from 1 KiB to pgcm_unit_bytes() with which the batch has at most 4096
+ * units (the chip's wavefront slots: every unit then has a wavefront of its own at once, so a
+ * batch of a few swap-sized chunks spreads over the whole chip), and pgcm_unit_bytes() when none
+ * has (wavefronts then take units in turn).  0 when len is NULL and n is not 0.  Batches that take the small-transfer path
+ * (every chunk at most 8 KiB) are not cut into units at all.
+ */
+uint32_t pgcm_batch_unit_bytes(size_t n, const uint64_t *len);
+
+/*
+ * Tuning and test aid: fixes the unit size of every later batch under this key to unit_bytes
+ * (a power of two from 1024 to pgcm_unit_bytes()), or returns to the per-batch choice with 0.
+ * Anything else is PGCM_ERR_ARG.  With a forced small unit a chunk of more than 32^5 units is
+ * refused with PGCM_ERR_LEN by the batch calls.
+ */
+int pgcm_set_unit_bytes(pgcm_key_t *key, uint32_t unit_bytes);
 
 /*
  * Measurement aid.  With timing enabled, every batch call also records a pair of HIP events on

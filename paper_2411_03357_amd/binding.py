@@ -12,6 +12,7 @@ EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_en
            "pgcm_decrypt_verify_batch", "pgcm_encrypt_batch_iv", "pgcm_decrypt_verify_batch_iv",
            "pgcm_encrypt_batch_keys", "pgcm_decrypt_verify_batch_keys",
            "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_units", "pgcm_unit_bytes",
+           "pgcm_batch_unit_bytes", "pgcm_set_unit_bytes",
            "pgcm_set_timing", "pgcm_last_bulk_kernel_ms")
 
 
@@ -66,6 +67,10 @@ def load_library():
     lib.pgcm_plan_units.restype = C.c_int64
     lib.pgcm_unit_bytes.argtypes = []
     lib.pgcm_unit_bytes.restype = C.c_uint32
+    lib.pgcm_batch_unit_bytes.argtypes = [sz, vp]
+    lib.pgcm_batch_unit_bytes.restype = C.c_uint32
+    lib.pgcm_set_unit_bytes.argtypes = [vp, C.c_uint32]
+    lib.pgcm_set_unit_bytes.restype = C.c_int
     lib.pgcm_set_timing.argtypes = [vp, C.c_int]
     lib.pgcm_set_timing.restype = C.c_int
     lib.pgcm_last_bulk_kernel_ms.argtypes = [vp, C.POINTER(C.c_float)]
@@ -260,6 +265,11 @@ def plan_units(length):
     return out
 
 
+def set_unit_bytes(key: Key, unit_bytes: int):
+    """pgcm_set_unit_bytes (0: chosen per batch)"""
+    _check(load_library().pgcm_set_unit_bytes(key.handle, unit_bytes))
+
+
 def set_timing(key: Key, enable: bool):
     """pgcm_set_timing"""
     _check(load_library().pgcm_set_timing(key.handle, 1 if enable else 0))
@@ -274,6 +284,12 @@ def last_bulk_kernel_ms(key: Key) -> float:
 
 def unit_bytes() -> int:
     return int(load_library().pgcm_unit_bytes())
+
+
+def batch_unit_bytes(length) -> int:
+    """pgcm_batch_unit_bytes; host only."""
+    len_a = np.ascontiguousarray(length, dtype=np.uint64)
+    return int(load_library().pgcm_batch_unit_bytes(len_a.size, _addr(len_a) if len_a.size else None))
 
 
 # ---------------------------------------------------------------------------------------------

@@ -36,21 +36,45 @@ struct UnitPlan {
     uint32_t nunits, first_blocks;
 };
 
-inline UnitPlan plan_chunk(uint64_t len) {
+inline UnitPlan plan_chunk(uint64_t len, uint32_t unit_power) {
     uint64_t nblk = (len + 15) / 16;
     UnitPlan p{0, 0};
     if (nblk == 0) return p;
-    uint64_t nunits = (nblk + kUnitBlocks - 1) / kUnitBlocks;
+    uint64_t nunits = (nblk + ((uint64_t)1 << unit_power) - 1) >> unit_power;
     p.nunits = (uint32_t)nunits;
-    p.first_blocks = (uint32_t)(nblk - (nunits - 1) * kUnitBlocks);
+    p.first_blocks = (uint32_t)(nblk - ((nunits - 1) << unit_power));
     return p;
+}
+
+// Unit size of a batch: the smallest, from one row up, with which the batch has at most
+// kWaveSlots units, so that every unit gets a wavefront of its own at once; the full unit when
+// even that leaves more.  `order` as for run_batch.
+inline uint32_t choose_unit_power(size_t n, const uint32_t* order, const uint64_t* len) {
+    constexpr uint32_t kChoices = kUnitPower - kMinUnitPower + 1;
+    uint64_t units[kChoices] = {};
+    for (size_t k = 0; k < n; ++k) {
+        const uint64_t l = len[order ? order[k] : k];
+        if (l > PGCM_MAX_CHUNK_BYTES) return kUnitPower;  // rejected later
+        const uint64_t nblk = (l + 15) / 16;
+        for (uint32_t c = 0; c < kChoices; ++c) {
+            const uint32_t u = kMinUnitPower + c;
+            units[c] += (nblk + ((uint64_t)1 << u) - 1) >> u;
+        }
+        if (units[kChoices - 1] > kWaveSlots) return kUnitPower;
+    }
+    for (uint32_t c = 0; c < kChoices; ++c)
+        if (units[c] <= kWaveSlots) return kMinUnitPower + c;
+    return kUnitPower;
 }
 
 // Partial sets of a chunk are folded kFan at a time until at most kFan remain for the final
 // step.  Returns the number of fold levels and, per level, the number of sets it produces.
+// More than kMaxLevels levels (only possible when a small unit is forced on a huge chunk) is
+// reported as kMaxLevels + 1 with nothing written past the array.
 inline uint32_t fold_levels(uint32_t nunits, uint32_t out_counts[kMaxLevels]) {
     uint32_t levels = 0, c = nunits;
     while (c > kFan) {
+        if (levels == kMaxLevels) return kMaxLevels + 1;
         c = (c + kFan - 1) / kFan;
         out_counts[levels++] = c;
     }
@@ -63,6 +87,7 @@ struct pgcm_key {
     int device = -1;
     int num_cu = 0;
     int rounds = 0;  // 10, 12 or 14
+    uint32_t forced_unit_power = 0;  // 0: chosen per batch
     KeyTables* tables = nullptr;  // device
     // descriptor staging: pinned host buffers used in turn, each guarded by an event that marks
     // the end of its last upload
@@ -184,6 +209,8 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
 
     // validate everything before touching any state
     const uint32_t nchunks = (uint32_t)n;
+    const uint32_t unit_power =
+        key->forced_unit_power ? key->forced_unit_power : choose_unit_power(n, order, len);
     uint64_t nunits64 = 0, nslots64 = 0;
     uint64_t fold_items64[kMaxLevels] = {0, 0, 0, 0};
     bool all_small = true;
@@ -192,9 +219,10 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
         rc = check_chunk(i, aad, aad_len, src, len, dst);
         if (rc != PGCM_OK) return rc;
         if (len[i] > kSmallChunkBytes) all_small = false;
-        const uint32_t nu = plan_chunk(len[i]).nunits;
+        const uint32_t nu = plan_chunk(len[i], unit_power).nunits;
         uint32_t outs[kMaxLevels];
         const uint32_t levels = fold_levels(nu, outs);
+        if (levels > kMaxLevels) return PGCM_ERR_LEN;  // a forced small unit on a huge chunk
         nunits64 += nu;
         nslots64 += nu;
         for (uint32_t l = 0; l < levels; ++l) {
@@ -283,7 +311,7 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
     uint32_t fold_fill[kMaxLevels] = {0, 0, 0, 0};
     for (size_t k = 0; k < n; ++k) {
         const size_t i = at(k);
-        const UnitPlan p = plan_chunk(len[i]);
+        const UnitPlan p = plan_chunk(len[i], unit_power);
         ChunkDesc& d = h_desc[k];
         d.src = (const uint8_t*)src[i];
         d.dst = (uint8_t*)dst[i];
@@ -300,7 +328,7 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
             h_coarse[coarse_next++] = (uint32_t)k;
         }
         // fold levels: groups of kFan sets counted back from the end, the first one short
-        uint32_t base = unit, count = p.nunits, power = kUnitPower, level = 0;
+        uint32_t base = unit, count = p.nunits, power = unit_power, level = 0;
         while (count > kFan) {
             const uint32_t groups = (count + kFan - 1) / kFan;
             const uint32_t first = count - (groups - 1) * kFan;
@@ -364,11 +392,11 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
         if (key->timing) PGCM_HIP(hipEventRecord(key->bulk_start, stream));
         if (decrypt)
             launch_bulk<true>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
-                              d_desc, d_ubase, d_coarse, nunits, d_counter, ivs,
+                              d_desc, d_ubase, d_coarse, nunits, unit_power, d_counter, ivs,
                               (const Block*)d_j0, d_ekj0, d_sets);
         else
             launch_bulk<false>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
-                               d_desc, d_ubase, d_coarse, nunits, d_counter, ivs,
+                               d_desc, d_ubase, d_coarse, nunits, unit_power, d_counter, ivs,
                                (const Block*)d_j0, d_ekj0, d_sets);
         if (key->timing) {
             PGCM_HIP(hipEventRecord(key->bulk_stop, stream));
@@ -378,17 +406,17 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
     for (uint32_t l = 0; l < kMaxLevels; ++l) {
         if (fold_count[l] == 0) continue;
         hipLaunchKernelGGL(fold_kernel, dim3(fold_count[l]), dim3(64), 0, stream, key->tables,
-                           d_fold + fold_first[l], kUnitPower + kFanPower * l, d_sets);
+                           d_fold + fold_first[l], unit_power + kFanPower * l, d_sets);
     }
     const uint32_t final_groups = (nchunks + 15) / 16;
     if (decrypt) {
         hipLaunchKernelGGL(final_kernel<true>, dim3(final_groups), dim3(1024), 0, stream,
                            key->tables, d_desc, nchunks, ivs, d_j0, d_ekj0, d_sets, tags, ok,
-                           d_counter);
+                           unit_power, d_counter);
     } else {
         hipLaunchKernelGGL(final_kernel<false>, dim3(final_groups), dim3(1024), 0, stream,
                            key->tables, d_desc, nchunks, ivs, d_j0, d_ekj0, d_sets, tags, nullptr,
-                           d_counter);
+                           unit_power, d_counter);
     }
     PGCM_HIP(hipGetLastError());
     key->counter_dirty = false;
@@ -565,7 +593,7 @@ const char* pgcm_strerror(int status) {
         case PGCM_OK: return "success";
         case PGCM_ERR_ARG: return "invalid argument";
         case PGCM_ERR_ALIGN: return "src or dst pointer not 16-byte aligned";
-        case PGCM_ERR_LEN: return "chunk longer than the GCM limit of 2^36 - 32 bytes";
+        case PGCM_ERR_LEN: return "chunk longer than the GCM limit of 2^36 - 32 bytes, or too long for a forced unit size";
         case PGCM_ERR_NOMEM: return "out of host or device memory";
         case PGCM_ERR_HIP: return "a HIP runtime call failed";
         default: return "unknown status";
@@ -578,16 +606,18 @@ int64_t pgcm_plan_units(size_t n, const uint64_t* len, uint32_t* nunits, uint32_
                         uint32_t* unit_base, uint32_t* final_count, uint32_t* final_power) {
     if (n != 0 && len == nullptr) return PGCM_ERR_ARG;
     uint64_t total = 0;
+    const uint32_t unit_power = choose_unit_power(n, nullptr, len);
     for (size_t i = 0; i < n; ++i) {
         if (len[i] > PGCM_MAX_CHUNK_BYTES) return PGCM_ERR_LEN;
-        UnitPlan p = plan_chunk(len[i]);
+        UnitPlan p = plan_chunk(len[i], unit_power);
         uint32_t outs[kMaxLevels];
         const uint32_t levels = fold_levels(p.nunits, outs);
+        if (levels > kMaxLevels) return PGCM_ERR_LEN;  // cannot happen with the chosen unit
         if (nunits) nunits[i] = p.nunits;
         if (first_blocks) first_blocks[i] = p.first_blocks;
         if (unit_base) unit_base[i] = (uint32_t)total;
         if (final_count) final_count[i] = levels ? outs[levels - 1] : p.nunits;
-        if (final_power) final_power[i] = kUnitPower + kFanPower * levels;
+        if (final_power) final_power[i] = unit_power + kFanPower * levels;
         total += p.nunits;
         if (total > 0xFFFFFFF0ull / 64) return PGCM_ERR_ARG;
     }
@@ -595,6 +625,25 @@ int64_t pgcm_plan_units(size_t n, const uint64_t* len, uint32_t* nunits, uint32_
 }
 
 uint32_t pgcm_unit_bytes(void) { return kUnitBytes; }
+
+uint32_t pgcm_batch_unit_bytes(size_t n, const uint64_t* len) {
+    if (n != 0 && len == nullptr) return 0;
+    return 16u << choose_unit_power(n, nullptr, len);
+}
+
+int pgcm_set_unit_bytes(pgcm_key_t* key, uint32_t unit_bytes) {
+    if (key == nullptr) return PGCM_ERR_ARG;
+    if (unit_bytes == 0) {
+        key->forced_unit_power = 0;
+        return PGCM_OK;
+    }
+    for (uint32_t u = kMinUnitPower; u <= kUnitPower; ++u)
+        if (unit_bytes == (16u << u)) {
+            key->forced_unit_power = u;
+            return PGCM_OK;
+        }
+    return PGCM_ERR_ARG;
+}
 
 int pgcm_set_timing(pgcm_key_t* key, int enable) {
     if (key == nullptr) return PGCM_ERR_ARG;

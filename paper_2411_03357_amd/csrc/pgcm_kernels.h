@@ -15,8 +15,8 @@ __global__ void j0_kernel(const KeyTables* kt, const ChunkDesc* chunks, const ui
 template <bool kDecrypt, int kRounds>
 __global__ void bulk_kernel(const KeyTables* kt, const ChunkDesc* chunks,
                             const uint32_t* unit_base, const uint32_t* coarse_map,
-                            uint32_t nunits_total, uint32_t* counter, const uint8_t* ivs,
-                            const Block* j0, Block* ekj0, Block* sets);
+                            uint32_t nunits_total, uint32_t unit_power, uint32_t* counter,
+                            const uint8_t* ivs, const Block* j0, Block* ekj0, Block* sets);
 
 __global__ void fold_kernel(const KeyTables* kt, const FoldItem* items, uint32_t power,
                             Block* sets);
@@ -24,7 +24,8 @@ __global__ void fold_kernel(const KeyTables* kt, const FoldItem* items, uint32_t
 template <bool kDecrypt>
 __global__ void final_kernel(const KeyTables* kt, const ChunkDesc* chunks, uint32_t nchunks,
                              const uint8_t* ivs, const Block* j0, const Block* ekj0,
-                             const Block* sets, uint8_t* tags, uint8_t* ok, uint32_t* counter);
+                             const Block* sets, uint8_t* tags, uint8_t* ok, uint32_t unit_power,
+                             uint32_t* counter);
 
 constexpr uint32_t kSmallChunksPerGroup = 4;
 

@@ -670,7 +670,11 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
 
 }  // namespace
 
-// The schedule: wavefronts take units from `counter` until none is left.  Unit i belongs to the
+// The schedule: wavefront w of the launch starts with unit w; when the launch has a wavefront for
+// every unit that is all.  Otherwise the remaining units are handed out through `counter` until
+// none is left (the counter serves about one request per 11 ns: a launch whose wavefronts all
+// began by asking it would spend its first 50 us queueing, and a batch of many small units would
+// be bound by it).  Unit i belongs to the
 // chunk c with unit_base[c] <= i < unit_base[c + 1] (unit_base has one entry more than there are
 // chunks); coarse_map[i >> kCoarseShift] is a chunk at or before the right one.
 // sets[i * 64 + lane] receives lane's GHASH sum over the unit's rows:
@@ -680,8 +684,9 @@ template <bool kDecrypt, int kRounds>
 __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks,
     const uint32_t* __restrict__ unit_base, const uint32_t* __restrict__ coarse_map,
-    uint32_t nunits_total, uint32_t* __restrict__ counter, const uint8_t* __restrict__ ivs,
-    const Block* __restrict__ j0, Block* __restrict__ ekj0, Block* __restrict__ sets) {
+    uint32_t nunits_total, uint32_t unit_power, uint32_t* __restrict__ counter,
+    const uint8_t* __restrict__ ivs, const Block* __restrict__ j0, Block* __restrict__ ekj0,
+    Block* __restrict__ sets) {
     __shared__ BulkLds lds;
     // lookup addresses are formed as raw LDS addresses that assume this object starts at 0
     if (lds_offset(&lds) != 0) return;
@@ -704,11 +709,10 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
 #pragma unroll
     for (int i = 0; i < 4 * (kRounds + 1); ++i) rk[i] = kt->rk[i];
 
+    const uint32_t nwaves = gridDim.x * kWavesPerGroup;
+    const bool one_each = nunits_total <= nwaves;
+    uint32_t item = blockIdx.x * kWavesPerGroup + (tid >> 6);
     for (;;) {
-        uint32_t item = 0;
-        if (lane == 0)
-            item = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        item = __builtin_amdgcn_readfirstlane(item);
         if (item >= nunits_total) break;  // every wavefront gets here: the counter only grows
 
         uint32_t chunk = coarse_map[item >> kCoarseShift];
@@ -721,8 +725,9 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
         const uint32_t first_blocks = cd->first_blocks;
         // the unit's blocks [b0, b1) of the chunk
         // unit 0 also takes "block -1", whose counter block is J0
-        const int64_t b0 = unit == 0 ? -1 : (int64_t)first_blocks + (int64_t)(unit - 1) * kUnitBlocks;
-        const int64_t b1 = unit == 0 ? (int64_t)first_blocks : b0 + kUnitBlocks;
+        const int64_t b0 =
+            unit == 0 ? -1 : (int64_t)first_blocks + ((int64_t)(unit - 1) << unit_power);
+        const int64_t b1 = unit == 0 ? (int64_t)first_blocks : b0 + ((int64_t)1 << unit_power);
         const uint32_t nrows = (uint32_t)((b1 - b0 + kRowBlocks - 1) / kRowBlocks);
 
         const Block j = chunk_j0(kt, ivs, j0, chunk, cd->index);
@@ -742,12 +747,17 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
                                         ekj0 + chunk, y);
         }
         sets[(uint64_t)item * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
+        if (one_each) break;
+        if (lane == 0)
+            item = nwaves + __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+        item = __builtin_amdgcn_readfirstlane(item);
     }
 }
 
 #define PGCM_INSTANTIATE_BULK(D, R)                                                              \
     template __global__ void bulk_kernel<D, R>(const KeyTables*, const ChunkDesc*, const uint32_t*, \
-                                               const uint32_t*, uint32_t, uint32_t*,                \
+                                               const uint32_t*, uint32_t, uint32_t, uint32_t*,      \
                                                const uint8_t*, const Block*, Block*, Block*)
 PGCM_INSTANTIATE_BULK(false, 10);
 PGCM_INSTANTIATE_BULK(false, 12);
@@ -823,6 +833,7 @@ __global__ __launch_bounds__(64) void fold_kernel(const KeyTables* __restrict__ 
 // length block, mask with E_K(J0) (SP 800-38D 7.1 steps 5-6); then write the tag, or compare it
 // and write the verdict (7.2).  Workgroup 0 also clears `counter` for the next batch.
 // LDS: nibble tables of H^1 .. H^32 (tree), and of the two most common fold distances.
+// unit_power: log2 of the blocks per unit the batch was cut into.
 constexpr uint32_t kFinalChunksPerGroup = 16;
 constexpr uint32_t kFinalTables = 8;
 
@@ -831,14 +842,15 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks, uint32_t nchunks,
     const uint8_t* __restrict__ ivs, const Block* __restrict__ j0, const Block* __restrict__ ekj0,
     const Block* __restrict__ sets, uint8_t* __restrict__ tags, uint8_t* __restrict__ ok,
-    uint32_t* __restrict__ counter) {
+    uint32_t unit_power, uint32_t* __restrict__ counter) {
     __shared__ Block tables[kFinalTables][kNibbleTableEntries];
     const uint32_t tid = threadIdx.x, lane = tid & 63;
     if (blockIdx.x == 0 && tid == 0) *counter = 0;
-    // tables 0..5: H^(2^k) for the lane tree; 6, 7: H^(2^10), H^(2^15) for folding
+    // tables 0..5: H^(2^k) for the lane tree; 6, 7: the fold distances of chunks with no and
+    // with one fold level behind them
     for (uint32_t k = 0; k < 6; ++k) copy_power_table(tables[k], kt, k, tid, blockDim.x);
-    copy_power_table(tables[6], kt, kUnitPower, tid, blockDim.x);
-    copy_power_table(tables[7], kt, kUnitPower + kFanPower, tid, blockDim.x);
+    copy_power_table(tables[6], kt, unit_power, tid, blockDim.x);
+    copy_power_table(tables[7], kt, unit_power + kFanPower, tid, blockDim.x);
     __syncthreads();
 
     const uint32_t i = blockIdx.x * kFinalChunksPerGroup + (tid >> 6);
@@ -858,8 +870,8 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
         mask = Block{{e[0], e[1], e[2], e[3]}};
     } else {
         uint32_t fold_table = 0xFFFFFFFFu;
-        if (cd.final_power == kUnitPower) fold_table = lds_offset(tables[6]);
-        if (cd.final_power == kUnitPower + kFanPower) fold_table = lds_offset(tables[7]);
+        if (cd.final_power == unit_power) fold_table = lds_offset(tables[6]);
+        if (cd.final_power == unit_power + kFanPower) fold_table = lds_offset(tables[7]);
         fold_sets(kt, sets, cd.final_base, cd.final_count, cd.final_power, lane, fold_table, y);
         // lanes -> one value: lane j's sum still lacks H^(64 - j).  Tree: with s = 32, 16, .., 1
         // lane j takes Y_j * H^s + Y_(j+s); lane 0 ends with sum_j Y_j * H^(63 - j); then one more H.
@@ -917,10 +929,12 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
 
 template __global__ void final_kernel<false>(const KeyTables*, const ChunkDesc*, uint32_t,
                                              const uint8_t*, const Block*, const Block*,
-                                             const Block*, uint8_t*, uint8_t*, uint32_t*);
+                                             const Block*, uint8_t*, uint8_t*, uint32_t,
+                                             uint32_t*);
 template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, uint32_t,
                                             const uint8_t*, const Block*, const Block*,
-                                            const Block*, uint8_t*, uint8_t*, uint32_t*);
+                                            const Block*, uint8_t*, uint8_t*, uint32_t,
+                                            uint32_t*);
 
 // ------------------------------------------------------------------------------------------
 // The small-transfer path: a batch whose chunks are all at most kSmallChunkBytes long (the

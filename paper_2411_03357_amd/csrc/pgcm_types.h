@@ -7,12 +7,18 @@ namespace pgcm {
 // A wavefront handles 64 consecutive 16-byte blocks (one 1 KiB "row") per step, one block per
 // lane.  A unit is the piece of a chunk one wavefront walks in one go, and the granule of the
 // dynamic schedule; units are counted back from the chunk's end, so only a chunk's first unit
-// can be short.
+// can be short.  A unit is 2^unit_power blocks, one to sixteen rows: sixteen for batches that fill
+// the chip; for smaller batches the smallest size that still gives every unit a wavefront of
+// its own, so that the batch spreads over as many wavefronts as there are and no unit waits.
 constexpr uint32_t kRowBlocks = 64;
 constexpr uint32_t kRowPower = 6;      // H^64: one row further along a lane's stripe
-constexpr uint32_t kUnitPower = 10;    // 1024 blocks = 16 KiB per unit
+constexpr uint32_t kUnitPower = 10;    // the full unit: 1024 blocks = 16 KiB
+constexpr uint32_t kMinUnitPower = kRowPower;
 constexpr uint32_t kUnitBlocks = 1u << kUnitPower;
 constexpr uint32_t kUnitBytes = kUnitBlocks * 16;
+// wavefront slots of a 256-CU chip at sixteen per compute unit: a batch gets the smallest unit
+// with which it has at most this many units (the full unit if none has)
+constexpr uint32_t kWaveSlots = 4096;
 constexpr uint32_t kWavesPerGroup = 16;
 constexpr uint32_t kGroupThreads = kWavesPerGroup * 64;
 static_assert((1u << kRowPower) == kRowBlocks, "row power");
@@ -52,7 +58,7 @@ struct alignas(16) ChunkDesc {
     uint32_t aad_len;
     uint32_t unit_base;     // index of this chunk's first unit among all units = its set slot
     uint32_t nunits;        // 0 for an empty chunk
-    uint32_t first_blocks;  // blocks in unit 0; every later unit has kUnitBlocks
+    uint32_t first_blocks;  // blocks in unit 0; every later unit has 2^unit_power
     uint32_t final_base;    // first set slot the final step folds
     uint32_t final_count;   // number of sets it folds: 1..32, or 0 for an empty chunk
     uint32_t final_power;   // log2 of the distance, in blocks, between consecutive such sets

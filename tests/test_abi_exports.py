@@ -44,13 +44,8 @@ def test_strerror_and_null_arguments_without_gpu():
     assert lib.pgcm_last_hip_error() == 0
 
 
-def test_unit_plan():
-    unit = pgcm.unit_bytes()
-    assert unit % 1024 == 0 and unit >= 1024
+def _check_plan(lens, unit):
     ub = unit // 16
-    lens = [0, 1, 15, 16, 17, unit - 1, unit, unit + 1, 3 * unit, 3 * unit + 16 * 7 + 3,
-            32 * unit, 32 * unit + 1, 33 * unit, 1024 * unit, 1024 * unit + 5, 1025 * unit,
-            (1 << 36) - 32]
     p = pgcm.plan_units(lens)
     run = 0
     for i, ln in enumerate(lens):
@@ -71,10 +66,48 @@ def test_unit_plan():
         assert int(p["final_count"][i]) == c and levels <= 4
         assert int(p["final_power"][i]) == (ub.bit_length() - 1) + 5 * levels
     assert p["total"] == run
+
+
+def test_unit_plan():
+    unit = pgcm.unit_bytes()
+    assert unit == 16384
+    lens = [0, 1, 15, 16, 17, unit - 1, unit, unit + 1, 3 * unit, 3 * unit + 16 * 7 + 3,
+            32 * unit, 32 * unit + 1, 33 * unit, 1024 * unit, 1024 * unit + 5, 1025 * unit,
+            (1 << 36) - 32]
+    assert pgcm.batch_unit_bytes(lens) == unit
+    _check_plan(lens, unit)
     with pytest.raises(pgcm.PgcmError) as e:
         pgcm.plan_units([1 << 36])
     assert e.value.status == -3
     assert pgcm.plan_units([])["total"] == 0
+
+
+def test_unit_shrinks_for_batches_that_cannot_fill_the_chip():
+    """the smallest unit, from one 1 KiB row up, that leaves at most 4096 units; the full unit
+    when none does"""
+    KIB, MIB = 1024, 1 << 20
+    cases = [([], 1024), ([0, 0], 1024), ([1], 1024), ([320 * KIB], 1024), ([4 * MIB], 1024),
+             ([4 * MIB + 1], 2048), ([8 * MIB], 2048), ([16 * MIB], 4096), ([32 * MIB], 8192),
+             ([64 * MIB], 16384), ([64 * MIB + 1], 16384), ([1 << 30], 16384),
+             ([320 * KIB] * 12, 1024), ([320 * KIB] * 13, 2048), ([320 * KIB] * 16, 2048),
+             ([320 * KIB] * 64, 8192), ([320 * KIB] * 204, 16384), ([320 * KIB] * 4096, 16384),
+             ([2 * MIB] * 2, 1024), ([2 * MIB] * 4, 2048), ([2 * MIB] * 32, 16384),
+             # units are counted per chunk: 4096 chunks of 1 KiB + 1 B need two 1 KiB units each
+             ([KIB] * 4096, 1024), ([KIB + 1] * 4096, 2048), ([1] * 4097, 16384),
+             ([(1 << 36) - 32, 5], 16384)]
+    for lens, unit in cases:
+        assert pgcm.batch_unit_bytes(lens) == unit, (lens[:2], len(lens))
+        ub = unit // 16
+        units = sum(((ln + 15) // 16 + ub - 1) // ub for ln in lens)
+        if unit < 16384:
+            assert units <= 4096
+        if unit > 1024:
+            smaller = unit // 32
+            assert sum(((ln + 15) // 16 + smaller - 1) // smaller for ln in lens) > 4096
+        if lens:
+            _check_plan(lens, unit)
+    extra = [0, 1, 1023, 1025, 33 * 1024 + 7]
+    _check_plan([320 * KIB] * 3 + extra, pgcm.batch_unit_bytes([320 * KIB] * 3 + extra))
 
 
 def test_workload_generators_are_seeded_and_shaped():

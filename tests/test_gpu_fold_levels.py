@@ -28,14 +28,34 @@ def _workload(lens, seed_shift, aad_len):
                               lens, offsets, total, "u8", aad, aad_off)
 
 
-def test_two_fold_levels_against_the_oracle():
+def _levels(nunits):
+    levels = 0
+    while nunits > 32:
+        nunits, levels = (nunits + 31) // 32, levels + 1
+    return levels
+
+
+@pytest.mark.parametrize("forced_unit", [None, 16384, 1024])
+def test_fold_levels_against_the_oracle(forced_unit):
+    """a 16 MiB chunk: two fold levels with 16 KiB units (1025 sets -> 33, the first group short,
+    -> 2), with the 8 KiB units a batch of this size gets by itself (2049 -> 65 -> 3) and with
+    1 KiB units (16385 -> 513 -> 17)"""
     unit = pgcm.unit_bytes()
-    # 1024 units + 3 blocks + 5 bytes: level 1 has 33 groups (first one short), level 2 folds 33 -> 2
     big = 1024 * unit + 3 * 16 + 5
     w = _workload([big, 33 * unit + 1, 40], 0, 20)
+    auto = pgcm.batch_unit_bytes(w.lens)
+    assert auto == 8192
     plan = pgcm.plan_units(w.lens)
-    assert int(plan["final_power"][0]) == 20 and int(plan["final_power"][1]) == 15
+    up = auto.bit_length() - 5                  # log2(blocks per unit)
+    for i in range(2):
+        nunits = -(-int(w.lens[i]) // auto)
+        assert int(plan["nunits"][i]) == nunits
+        assert int(plan["final_power"][i]) == up + 5 * _levels(nunits)
+    use = forced_unit or auto
+    assert _levels(-(-big // use)) == 2
     key = pgcm.expand_key(w.key)
+    if forced_unit:
+        pgcm.set_unit_bytes(key, forced_unit)
     b = DeviceBatch(w, w.payload_device())
     b.encrypt(key)
     b.decrypt(key)
@@ -63,6 +83,7 @@ def test_three_fold_levels_against_libcrypto():
     unit = pgcm.unit_bytes()
     big = (32 * 32 * 32 + 40) * unit + 16 * 9 + 11      # 512 MiB + 640 KiB + ...
     w = _workload([big], 1, 13)
+    assert pgcm.batch_unit_bytes(w.lens) == unit      # 512 MiB fills the chip with full units
     plan = pgcm.plan_units(w.lens)
     assert int(plan["final_power"][0]) == 25
     key = pgcm.expand_key(w.key)

@@ -26,10 +26,12 @@ def _oracle_encrypt(w, host_buf, idx=None):
     return cts, tags
 
 
-def _full_parity(w, flip=None, iv_entry=None):
-    """encrypt + decrypt-verify of the whole workload compared with the oracle on every byte"""
+def _full_parity(w, flip=None, iv_entry=None, unit_bytes=0):
+    """encrypt + decrypt-verify of the whole workload compared with the oracle on every byte;
+    unit_bytes forces the scheduler's unit size (0: its own choice for the batch)"""
     host = w.payload_host()
     key = expand(w)
+    pgcm.set_unit_bytes(key, unit_bytes)
     b = DeviceBatch(w, torch.from_numpy(host).cuda(), iv_entry=iv_entry)
     b.cipher.fill_(0xEE)            # gaps between chunks must stay untouched
     b.encrypt(key)
@@ -91,6 +93,24 @@ def test_ragged_edge_cases_full_parity():
     last = int(w.lens[13]) - 1
     _full_parity(w, flip=[(13, last, 7, "ct"), (25, 0, 0, "ct"), (2, 15, 3, "tag"),
                           (0, 0, 0, "tag")])
+
+
+@pytest.mark.parametrize("unit_bytes", [1024, 2048, 4096, 8192, 16384])
+def test_every_unit_size_full_parity(unit_bytes):
+    """small batches get small units by themselves; here every unit size is forced on the
+    edge-case batch and on a ragged mixed-size batch, so that unit boundaries, short first units
+    and fold levels of each size are compared byte for byte"""
+    w = workloads.ragged_small()
+    last = int(w.lens[13]) - 1
+    _full_parity(w, flip=[(13, last, 7, "ct"), (25, 0, 0, "ct"), (2, 15, 3, "tag")],
+                 unit_bytes=unit_bytes)
+    _full_parity(workloads.mini(4), unit_bytes=unit_bytes)
+    key = pgcm.expand_key(w.key)
+    for bad in (1, 512, 1000, 3000, 32768, 1 << 20):
+        with pytest.raises(pgcm.PgcmError) as e:
+            pgcm.set_unit_bytes(key, bad)
+        assert e.value.status == -1
+    key.free()
 
 
 def test_small_transfer_path_full_parity():
