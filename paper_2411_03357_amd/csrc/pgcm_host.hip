@@ -29,6 +29,9 @@ inline bool hip_failed(hipError_t e) {
     } while (0)
 
 constexpr int kStages = 2;
+// a fold level with at most this many items (one workgroup each fits the chip at once) is folded
+// by the tree kernel
+constexpr uint32_t kFoldTreeMaxItems = 256;
 
 // Per-chunk schedule: units are counted back from the chunk's end, so that every unit but the
 // first is full and all row boundaries line up with the end of the chunk.
@@ -405,8 +408,14 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
     }
     for (uint32_t l = 0; l < kMaxLevels; ++l) {
         if (fold_count[l] == 0) continue;
-        hipLaunchKernelGGL(fold_kernel, dim3(fold_count[l]), dim3(64), 0, stream, key->tables,
-                           d_fold + fold_first[l], unit_power + kFanPower * l, d_sets);
+        // few items: a workgroup each, folding as a tree; many: a wavefront each, as a chain
+        if (fold_count[l] <= kFoldTreeMaxItems)
+            hipLaunchKernelGGL(fold_tree_kernel, dim3(fold_count[l]), dim3(kFoldTreeWaves * 64), 0,
+                               stream, key->tables, d_fold + fold_first[l],
+                               unit_power + kFanPower * l, d_sets);
+        else
+            hipLaunchKernelGGL(fold_kernel, dim3(fold_count[l]), dim3(64), 0, stream, key->tables,
+                               d_fold + fold_first[l], unit_power + kFanPower * l, d_sets);
     }
     const uint32_t final_groups = (nchunks + 15) / 16;
     if (decrypt) {

@@ -21,6 +21,10 @@ __global__ void bulk_kernel(const KeyTables* kt, const ChunkDesc* chunks,
 __global__ void fold_kernel(const KeyTables* kt, const FoldItem* items, uint32_t power,
                             Block* sets);
 
+constexpr uint32_t kFoldTreeWaves = 16;
+__global__ void fold_tree_kernel(const KeyTables* kt, const FoldItem* items, uint32_t power,
+                                 Block* sets);
+
 template <bool kDecrypt>
 __global__ void final_kernel(const KeyTables* kt, const ChunkDesc* chunks, uint32_t nchunks,
                              const uint8_t* ivs, const Block* j0, const Block* ekj0,

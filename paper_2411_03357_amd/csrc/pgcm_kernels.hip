@@ -828,6 +828,51 @@ __global__ __launch_bounds__(64) void fold_kernel(const KeyTables* __restrict__ 
     sets[(uint64_t)it.out_slot * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
 }
 
+// The same fold as a tree, for batches with few fold items, where the time of one item counts and
+// not the number of items the chip gets through: one workgroup of sixteen wavefronts per item.
+// The item's sets, counted back from its last, are the leaves; wavefront w first folds leaves
+// 2w and 2w + 1 (missing leaves at the front count as zero, which changes nothing), then four
+// rounds through LDS halve the number of partial results, round j with H^(2^(power + j)): five
+// multiplications deep instead of thirty-one.
+__global__ __launch_bounds__(kFoldTreeWaves * 64) void fold_tree_kernel(
+    const KeyTables* __restrict__ kt, const FoldItem* __restrict__ items, uint32_t power,
+    Block* __restrict__ sets) {
+    constexpr uint32_t kLevels = kFanPower;  // 2^5 leaves
+    static_assert(kFoldTreeWaves * 2 == kFan, "two leaves per wavefront");
+    __shared__ Block tables[kLevels][kNibbleTableEntries];
+    __shared__ Block partial[kFoldTreeWaves][64];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const FoldItem it = items[blockIdx.x];
+    for (uint32_t j = 0; j < kLevels; ++j) copy_power_table(tables[j], kt, power + j, tid, blockDim.x);
+
+    // leaves 2w and 2w + 1 of 32, the item's sets being leaves 32 - in_count .. 31
+    const uint32_t pad = kFan - it.in_count;
+    const Block* __restrict__ in = sets + (uint64_t)it.in_base * 64 + lane;
+    uint32_t y[4] = {0, 0, 0, 0};
+    Block second{{0, 0, 0, 0}};
+    if (2 * wave >= pad) {
+        const Block first = in[(uint64_t)(2 * wave - pad) * 64];
+        y[0] = first.w[0], y[1] = first.w[1], y[2] = first.w[2], y[3] = first.w[3];
+    }
+    if (2 * wave + 1 >= pad) second = in[(uint64_t)(2 * wave + 1 - pad) * 64];
+    __syncthreads();  // tables are in place
+    ghash_mul_lds(lds_offset(tables[0]), y);
+    y[0] ^= second.w[0], y[1] ^= second.w[1], y[2] ^= second.w[2], y[3] ^= second.w[3];
+    // every wavefront passes every barrier; only the shrinking front half has work to do
+    for (uint32_t j = 1; j < kLevels; ++j) {
+        partial[wave][lane] = Block{{y[0], y[1], y[2], y[3]}};
+        __syncthreads();
+        if (wave < (kFoldTreeWaves >> j)) {
+            const Block a = partial[2 * wave][lane], b = partial[2 * wave + 1][lane];
+            y[0] = a.w[0], y[1] = a.w[1], y[2] = a.w[2], y[3] = a.w[3];
+            ghash_mul_lds(lds_offset(tables[j]), y);
+            y[0] ^= b.w[0], y[1] ^= b.w[1], y[2] ^= b.w[2], y[3] ^= b.w[3];
+        }
+        __syncthreads();
+    }
+    if (wave == 0) sets[(uint64_t)it.out_slot * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
+}
+
 // Per chunk (one wavefront each, sixteen chunks a workgroup): fold the remaining sets, fold the 64
 // lanes with a reduction tree (DPP inside rows of 16 lanes, LDS permutes across them), add the
 // length block, mask with E_K(J0) (SP 800-38D 7.1 steps 5-6); then write the tag, or compare it
