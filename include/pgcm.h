@@ -194,11 +194,18 @@ int pgcm_set_unit_bytes(pgcm_key_t *key, uint32_t unit_bytes);
 /*
  * Measurement aid.  With timing enabled, every batch call also records a pair of HIP events on
  * its stream around the bulk kernel (the one launch that touches the payload: keystream, XOR
- * and GHASH of every unit).  pgcm_last_bulk_kernel_ms waits for the most recent batch's
- * bulk kernel and returns its duration in milliseconds; PGCM_ERR_ARG when nothing was timed.
+ * and GHASH of every unit; for the small-transfer path, its one kernel).  The library keeps the
+ * pairs of the 256 most recent timed launches, so a run of batches can be enqueued back to back
+ * and read afterwards.  Switching timing on (again) forgets earlier launches.
+ * pgcm_last_bulk_kernel_ms waits for the most recent timed launch and returns its duration in
+ * milliseconds; PGCM_ERR_ARG when nothing was timed.
+ * pgcm_bulk_kernel_ms_history waits for and returns the durations of the most recent
+ * min(max, 256, launches timed) launches, oldest first, in ms[] (HOST), and returns how many it
+ * wrote, or a negative pgcm_status.
  */
 int pgcm_set_timing(pgcm_key_t *key, int enable);
 int pgcm_last_bulk_kernel_ms(pgcm_key_t *key, float *ms);
+int64_t pgcm_bulk_kernel_ms_history(pgcm_key_t *key, float *ms, size_t max);
 
 #ifdef __cplusplus
 }

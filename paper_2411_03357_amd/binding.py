@@ -13,7 +13,7 @@ EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_en
            "pgcm_encrypt_batch_keys", "pgcm_decrypt_verify_batch_keys",
            "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_units", "pgcm_unit_bytes",
            "pgcm_batch_unit_bytes", "pgcm_set_unit_bytes",
-           "pgcm_set_timing", "pgcm_last_bulk_kernel_ms")
+           "pgcm_set_timing", "pgcm_last_bulk_kernel_ms", "pgcm_bulk_kernel_ms_history")
 
 
 class PgcmError(RuntimeError):
@@ -75,6 +75,8 @@ def load_library():
     lib.pgcm_set_timing.restype = C.c_int
     lib.pgcm_last_bulk_kernel_ms.argtypes = [vp, C.POINTER(C.c_float)]
     lib.pgcm_last_bulk_kernel_ms.restype = C.c_int
+    lib.pgcm_bulk_kernel_ms_history.argtypes = [vp, vp, sz]
+    lib.pgcm_bulk_kernel_ms_history.restype = C.c_int64
     _lib = lib
     return lib
 
@@ -280,6 +282,15 @@ def last_bulk_kernel_ms(key: Key) -> float:
     ms = C.c_float(0.0)
     _check(load_library().pgcm_last_bulk_kernel_ms(key.handle, C.byref(ms)))
     return float(ms.value)
+
+
+def bulk_kernel_ms_history(key: Key, max_launches: int = 256):
+    """pgcm_bulk_kernel_ms_history -> list of durations in ms, oldest first"""
+    out = np.zeros(max(1, max_launches), np.float32)
+    n = load_library().pgcm_bulk_kernel_ms_history(key.handle, out.ctypes.data, max_launches)
+    if n < 0:
+        raise PgcmError(int(n), load_library().pgcm_last_hip_error() if n == -5 else 0)
+    return [float(v) for v in out[:n]]
 
 
 def unit_bytes() -> int:

@@ -29,6 +29,7 @@ inline bool hip_failed(hipError_t e) {
     } while (0)
 
 constexpr int kStages = 2;
+constexpr uint32_t kTimingRing = 256;
 // a fold level with at most this many items (one workgroup each fits the chip at once) is folded
 // by the tree kernel
 constexpr uint32_t kFoldTreeMaxItems = 256;
@@ -106,9 +107,11 @@ struct pgcm_key {
     uint32_t* counter_at = nullptr;  // where the unit counter was last known to be zero
     bool counter_dirty = true;
     // optional timing of the bulk kernel alone (pgcm_set_timing)
+    // a ring of event pairs, one pair per timed launch, so that a run of batches can be timed
+    // without a host wait in between
     bool timing = false;
-    bool timed = false;
-    hipEvent_t bulk_start = nullptr, bulk_stop = nullptr;
+    uint64_t timed = 0;  // launches timed since timing was switched on
+    hipEvent_t bulk_start[kTimingRing] = {}, bulk_stop[kTimingRing] = {};
 };
 
 namespace {
@@ -268,7 +271,8 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
             d.aad = d.aad_len ? (const uint8_t*)aad[i] : nullptr;
         }
         const uint32_t groups = (nchunks + kSmallChunksPerGroup - 1) / kSmallChunksPerGroup;
-        if (key->timing) PGCM_HIP(hipEventRecord(key->bulk_start, stream));
+        if (key->timing)
+            PGCM_HIP(hipEventRecord(key->bulk_start[key->timed % kTimingRing], stream));
         if (decrypt)
             launch_small<true>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
                                (const ChunkDesc*)h_desc, nchunks, ivs, iv_len, tags, ok);
@@ -277,8 +281,8 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
                                 (const ChunkDesc*)h_desc, nchunks, ivs, iv_len, tags,
                                 (uint8_t*)nullptr);
         if (key->timing) {
-            PGCM_HIP(hipEventRecord(key->bulk_stop, stream));
-            key->timed = true;
+            PGCM_HIP(hipEventRecord(key->bulk_stop[key->timed % kTimingRing], stream));
+            ++key->timed;
         }
         PGCM_HIP(hipGetLastError());
         PGCM_HIP(hipEventRecord(key->stage_done[s], stream));
@@ -392,7 +396,8 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
     if (nunits > 0) {
         uint32_t groups = (nunits + kWavesPerGroup - 1) / kWavesPerGroup;
         if (groups > (uint32_t)key->num_cu) groups = (uint32_t)key->num_cu;
-        if (key->timing) PGCM_HIP(hipEventRecord(key->bulk_start, stream));
+        if (key->timing)
+            PGCM_HIP(hipEventRecord(key->bulk_start[key->timed % kTimingRing], stream));
         if (decrypt)
             launch_bulk<true>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
                               d_desc, d_ubase, d_coarse, nunits, unit_power, d_counter, ivs,
@@ -402,8 +407,8 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
                                d_desc, d_ubase, d_coarse, nunits, unit_power, d_counter, ivs,
                                (const Block*)d_j0, d_ekj0, d_sets);
         if (key->timing) {
-            PGCM_HIP(hipEventRecord(key->bulk_stop, stream));
-            key->timed = true;
+            PGCM_HIP(hipEventRecord(key->bulk_stop[key->timed % kTimingRing], stream));
+            ++key->timed;
         }
     }
     for (uint32_t l = 0; l < kMaxLevels; ++l) {
@@ -543,8 +548,10 @@ void pgcm_free_key(pgcm_key_t* k) {
         }
         if (k->stage_done[s]) (void)hipEventDestroy(k->stage_done[s]);
     }
-    if (k->bulk_start) (void)hipEventDestroy(k->bulk_start);
-    if (k->bulk_stop) (void)hipEventDestroy(k->bulk_stop);
+    for (uint32_t i = 0; i < kTimingRing; ++i) {
+        if (k->bulk_start[i]) (void)hipEventDestroy(k->bulk_start[i]);
+        if (k->bulk_stop[i]) (void)hipEventDestroy(k->bulk_stop[i]);
+    }
     delete k;
 }
 
@@ -656,20 +663,35 @@ int pgcm_set_unit_bytes(pgcm_key_t* key, uint32_t unit_bytes) {
 
 int pgcm_set_timing(pgcm_key_t* key, int enable) {
     if (key == nullptr) return PGCM_ERR_ARG;
-    if (enable && key->bulk_start == nullptr) {
-        PGCM_HIP(hipEventCreate(&key->bulk_start));
-        PGCM_HIP(hipEventCreate(&key->bulk_stop));
+    if (enable && key->bulk_start[0] == nullptr) {
+        for (uint32_t i = 0; i < kTimingRing; ++i) {
+            PGCM_HIP(hipEventCreate(&key->bulk_start[i]));
+            PGCM_HIP(hipEventCreate(&key->bulk_stop[i]));
+        }
     }
     key->timing = enable != 0;
-    key->timed = false;
+    key->timed = 0;
     return PGCM_OK;
 }
 
 int pgcm_last_bulk_kernel_ms(pgcm_key_t* key, float* ms) {
-    if (key == nullptr || ms == nullptr || !key->timed) return PGCM_ERR_ARG;
-    PGCM_HIP(hipEventSynchronize(key->bulk_stop));
-    PGCM_HIP(hipEventElapsedTime(ms, key->bulk_start, key->bulk_stop));
+    if (key == nullptr || ms == nullptr || key->timed == 0) return PGCM_ERR_ARG;
+    const uint32_t slot = (uint32_t)((key->timed - 1) % kTimingRing);
+    PGCM_HIP(hipEventSynchronize(key->bulk_stop[slot]));
+    PGCM_HIP(hipEventElapsedTime(ms, key->bulk_start[slot], key->bulk_stop[slot]));
     return PGCM_OK;
+}
+
+int64_t pgcm_bulk_kernel_ms_history(pgcm_key_t* key, float* ms, size_t max) {
+    if (key == nullptr || (ms == nullptr && max != 0)) return PGCM_ERR_ARG;
+    uint64_t count = key->timed < kTimingRing ? key->timed : kTimingRing;
+    if (count > max) count = max;
+    for (uint64_t i = 0; i < count; ++i) {
+        const uint32_t slot = (uint32_t)((key->timed - count + i) % kTimingRing);
+        PGCM_HIP(hipEventSynchronize(key->bulk_stop[slot]));
+        PGCM_HIP(hipEventElapsedTime(&ms[i], key->bulk_start[slot], key->bulk_stop[slot]));
+    }
+    return (int64_t)count;
 }
 
 #pragma GCC visibility pop

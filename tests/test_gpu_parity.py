@@ -232,3 +232,32 @@ def test_error_codes_and_empty_batch():
     torch.cuda.synchronize()
     assert torch.equal(b.cipher, before)        # failed calls enqueue nothing
     key.free()
+
+
+def test_bulk_kernel_timing_history():
+    w = workloads.mini(2)
+    key = pgcm.expand_key(w.key)
+    b = DeviceBatch(w, torch.from_numpy(w.payload_host()).cuda())
+    with pytest.raises(pgcm.PgcmError):
+        pgcm.last_bulk_kernel_ms(key)          # nothing timed yet
+    assert pgcm.bulk_kernel_ms_history(key) == []
+    pgcm.set_timing(key, True)
+    for _ in range(5):
+        b.encrypt(key)
+        b.decrypt(key)
+    hist = pgcm.bulk_kernel_ms_history(key)
+    assert len(hist) == 10 and all(0.0 < t < 50.0 for t in hist)
+    assert pgcm.bulk_kernel_ms_history(key, 3) == hist[-3:]
+    assert pgcm.last_bulk_kernel_ms(key) == hist[-1]
+    for _ in range(130):                       # more launches than the ring holds
+        b.encrypt(key)
+        b.decrypt(key)
+    assert len(pgcm.bulk_kernel_ms_history(key, 1000)) == 256
+    pgcm.set_timing(key, True)                 # switching on again forgets
+    assert pgcm.bulk_kernel_ms_history(key) == []
+    pgcm.set_timing(key, False)
+    b.encrypt(key)
+    assert pgcm.bulk_kernel_ms_history(key) == []
+    torch.cuda.synchronize()
+    assert bool((b.ok == 1).all()) and torch.equal(b.back, b.plain)
+    key.free()
