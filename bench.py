@@ -23,13 +23,13 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 3
 # `rocprofv3 --pmc` (summaries and commands: profiles/).  They describe the kernel sources whose
 # hash is given; once the sources change they no longer apply and bench.py reports null.
 COUNTERS = {
-    "sources_sha256": "56434797cbccc7747d7fe00ad316aaeb1a8631fdc6876b7aa210205b5d36abc1",
+    "sources_sha256": "8212582dd1f5a068dc82c6fef0b0c6767056b5d7b56cc2bff7f66c4b87b12c4e",
     "workload": "c2_opt13b_kv_4096x320KiB",
-    "fetch_size_kib": 658131.3,     # FETCH_SIZE per launch
-    "fetch_scale": 1310720.0 / 655382.1,   # a 1 310 720 KiB device copy reads 655 382.1
-    "write_size_kib": 1395451.3,    # WRITE_SIZE per launch
+    "fetch_size_kib": 657230.4,     # FETCH_SIZE per launch
+    "fetch_scale": 1310720.0 / 655381.9,   # a 1 310 720 KiB device copy reads 655 381.9
+    "write_size_kib": 1395322.3,    # WRITE_SIZE per launch
     "write_scale": 1310720.0 / 1310720.0,  # the same copy writes 1 310 720.0
-    "valu_wave_instructions": 597526528.0,  # SQ_INSTS_VALU per launch
+    "valu_wave_instructions": 609253376.0,  # SQ_INSTS_VALU per launch
     "lds_wave_instructions": 321931264.0,   # SQ_INSTS_LDS per launch
 }
 
