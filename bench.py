@@ -166,7 +166,7 @@ def main():
     traffic = None
     alu = None
     if (COUNTERS["workload"] == w.name and COUNTERS["sources_sha256"] == sources_sha256()
-            and not args.host_bounce):
+            and not args.host_bounce and args.unit_bytes == 0):
         traffic = int(1024 * (COUNTERS["fetch_size_kib"] * COUNTERS["fetch_scale"] +
                               COUNTERS["write_size_kib"] * COUNTERS["write_scale"]))
         lane_ops = COUNTERS["valu_wave_instructions"] * 64
