@@ -176,170 +176,153 @@ void launch_small(int rounds, dim3 grid, hipStream_t stream, Args... args) {
         hipLaunchKernelGGL((small_kernel<kDecrypt, 14>), grid, block, 0, stream, args...);
 }
 
+// The caller's arrays of one batch call.  `order` (may be null) picks the batch's chunks out of
+// them: chunk k of the batch is the caller's chunk order[k]; null means 0, 1, .., n - 1.
+struct BatchArgs {
+    bool decrypt;
+    size_t n;
+    const uint32_t* order;
+    const uint8_t* ivs;
+    uint32_t iv_len;
+    const void* const* aad;
+    const uint32_t* aad_len;
+    const void* const* src;
+    const uint64_t* len;
+    void* const* dst;
+    uint8_t* tags;
+    uint8_t* ok;
+    hipStream_t stream;
+
+    size_t at(size_t k) const { return order ? order[k] : k; }
+};
+
 // what must hold for the arrays of a batch as a whole
-int check_batch(size_t n, const uint8_t* ivs, uint32_t iv_len, const void* const* aad,
-                const uint32_t* aad_len, const void* const* src, const uint64_t* len,
-                void* const* dst, const uint8_t* tags, bool decrypt, const uint8_t* ok) {
-    if (iv_len == 0) return PGCM_ERR_ARG;  // GCM takes no empty IV
-    if (n == 0) return PGCM_OK;
-    if (ivs == nullptr || src == nullptr || len == nullptr || dst == nullptr || tags == nullptr)
+int check_batch(const BatchArgs& a) {
+    if (a.iv_len == 0) return PGCM_ERR_ARG;  // GCM takes no empty IV
+    if (a.n == 0) return PGCM_OK;
+    if (a.ivs == nullptr || a.src == nullptr || a.len == nullptr || a.dst == nullptr ||
+        a.tags == nullptr)
         return PGCM_ERR_ARG;
-    if ((aad == nullptr) != (aad_len == nullptr)) return PGCM_ERR_ARG;
-    if (decrypt && ok == nullptr) return PGCM_ERR_ARG;
-    if (n > 0x7FFFFFFFull) return PGCM_ERR_ARG;
+    if ((a.aad == nullptr) != (a.aad_len == nullptr)) return PGCM_ERR_ARG;
+    if (a.decrypt && a.ok == nullptr) return PGCM_ERR_ARG;
+    if (a.n > 0x7FFFFFFFull) return PGCM_ERR_ARG;
     return PGCM_OK;
 }
 
-// ... and for one of its chunks
-inline int check_chunk(size_t i, const void* const* aad, const uint32_t* aad_len,
-                       const void* const* src, const uint64_t* len, void* const* dst) {
-    if (len[i] > PGCM_MAX_CHUNK_BYTES) return PGCM_ERR_LEN;
-    if (len[i] != 0) {
-        if (src[i] == nullptr || dst[i] == nullptr) return PGCM_ERR_ARG;
-        if (((uintptr_t)src[i] | (uintptr_t)dst[i]) & 15) return PGCM_ERR_ALIGN;
+// ... and for the caller's chunk i
+inline int check_chunk(const BatchArgs& a, size_t i) {
+    if (a.len[i] > PGCM_MAX_CHUNK_BYTES) return PGCM_ERR_LEN;
+    if (a.len[i] != 0) {
+        if (a.src[i] == nullptr || a.dst[i] == nullptr) return PGCM_ERR_ARG;
+        if (((uintptr_t)a.src[i] | (uintptr_t)a.dst[i]) & 15) return PGCM_ERR_ALIGN;
     }
-    if (aad_len != nullptr && aad_len[i] != 0 && aad[i] == nullptr) return PGCM_ERR_ARG;
+    if (a.aad_len != nullptr && a.aad_len[i] != 0 && a.aad[i] == nullptr) return PGCM_ERR_ARG;
     return PGCM_OK;
 }
 
-// One batch under one key.  `order` (may be null) picks the batch's chunks out of the caller's
-// arrays: chunk k of the batch is the caller's chunk order[k]; null means 0, 1, .., n - 1.
-int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, const uint8_t* ivs,
-              uint32_t iv_len, const void* const* aad, const uint32_t* aad_len,
-              const void* const* src, const uint64_t* len, void* const* dst, uint8_t* tags,
-              uint8_t* ok, void* hip_stream) {
-    if (key == nullptr || key->tables == nullptr) return PGCM_ERR_ARG;
-    int rc = check_batch(n, ivs, iv_len, aad, aad_len, src, len, dst, tags, decrypt, ok);
-    if (rc != PGCM_OK || n == 0) return rc;
-    auto at = [order](size_t k) -> size_t { return order ? order[k] : k; };
+inline void describe_chunk(const BatchArgs& a, size_t i, ChunkDesc& d) {
+    memset(&d, 0, sizeof(d));
+    d.src = (const uint8_t*)a.src[i];
+    d.dst = (uint8_t*)a.dst[i];
+    d.len = a.len[i];
+    d.aad_len = a.aad_len ? a.aad_len[i] : 0;
+    d.aad = d.aad_len ? (const uint8_t*)a.aad[i] : nullptr;
+    d.index = (uint32_t)i;
+}
 
-    // validate everything before touching any state
-    const uint32_t nchunks = (uint32_t)n;
-    const uint32_t unit_power =
-        key->forced_unit_power ? key->forced_unit_power : choose_unit_power(n, order, len);
-    uint64_t nunits64 = 0, nslots64 = 0;
-    uint64_t fold_items64[kMaxLevels] = {0, 0, 0, 0};
-    bool all_small = true;
-    for (size_t k = 0; k < n; ++k) {
-        const size_t i = at(k);
-        rc = check_chunk(i, aad, aad_len, src, len, dst);
+// Sizes of a batch's schedule; filled by plan_batch, which also validates every chunk.
+struct BatchPlan {
+    bool all_small;       // every chunk fits the small-transfer path
+    uint32_t unit_power;  // log2 of the blocks per unit
+    uint32_t nunits;
+    uint32_t nslots;      // partial sets: one per unit and one per fold output
+    uint32_t fold_count[kMaxLevels], fold_first[kMaxLevels], nfold;
+    uint32_t ncoarse;
+};
+
+int plan_batch(const pgcm_key* key, const BatchArgs& a, BatchPlan* plan) {
+    plan->unit_power =
+        key->forced_unit_power ? key->forced_unit_power : choose_unit_power(a.n, a.order, a.len);
+    plan->all_small = true;
+    uint64_t nunits = 0, nslots = 0;
+    uint64_t fold_items[kMaxLevels] = {0, 0, 0, 0};
+    for (size_t k = 0; k < a.n; ++k) {
+        const size_t i = a.at(k);
+        const int rc = check_chunk(a, i);
         if (rc != PGCM_OK) return rc;
-        if (len[i] > kSmallChunkBytes) all_small = false;
-        const uint32_t nu = plan_chunk(len[i], unit_power).nunits;
+        if (a.len[i] > kSmallChunkBytes) plan->all_small = false;
+        const uint32_t nu = plan_chunk(a.len[i], plan->unit_power).nunits;
         uint32_t outs[kMaxLevels];
         const uint32_t levels = fold_levels(nu, outs);
         if (levels > kMaxLevels) return PGCM_ERR_LEN;  // a forced small unit on a huge chunk
-        nunits64 += nu;
-        nslots64 += nu;
+        nunits += nu;
+        nslots += nu;
         for (uint32_t l = 0; l < levels; ++l) {
-            fold_items64[l] += outs[l];
-            nslots64 += outs[l];
+            fold_items[l] += outs[l];
+            nslots += outs[l];
         }
     }
-    if (nslots64 > 0xFFFFFFF0ull / 64) return PGCM_ERR_ARG;  // set indices are 32-bit
-    const uint32_t nunits = (uint32_t)nunits64;
-    const uint32_t nslots = (uint32_t)nslots64;
-    uint32_t fold_count[kMaxLevels], fold_first[kMaxLevels], nfold = 0;
+    if (nslots > 0xFFFFFFF0ull / 64) return PGCM_ERR_ARG;  // set indices are 32-bit
+    plan->nunits = (uint32_t)nunits;
+    plan->nslots = (uint32_t)nslots;
+    plan->nfold = 0;
     for (uint32_t l = 0; l < kMaxLevels; ++l) {
-        fold_count[l] = (uint32_t)fold_items64[l];
-        fold_first[l] = nfold;
-        nfold += fold_count[l];
+        plan->fold_count[l] = (uint32_t)fold_items[l];
+        plan->fold_first[l] = plan->nfold;
+        plan->nfold += plan->fold_count[l];
     }
-    const uint32_t ncoarse = (nunits >> kCoarseShift) + 1;
+    plan->ncoarse = (plan->nunits >> kCoarseShift) + 1;
+    return PGCM_OK;
+}
 
-    hipStream_t stream = (hipStream_t)hip_stream;
-    int cur_device = -1;
-    PGCM_HIP(hipGetDevice(&cur_device));
-    if (cur_device != key->device) return PGCM_ERR_ARG;  // the key lives on another GPU
+// Byte offsets of the regions of the device workspace.  The regions up to upload_bytes are
+// written by the host into a staging buffer of the same layout and uploaded.
+struct WorkLayout {
+    size_t desc, ubase, coarse, fold, upload_bytes, counter, ekj0, j0, sets, bytes;
+};
 
-    if (all_small) {
-        // small-transfer path: one kernel, descriptors read straight from the pinned staging
-        // buffer, no device workspace
-        const int s = key->next_stage;
-        rc = ensure_stage(key, s, sizeof(ChunkDesc) * n);
-        if (rc != PGCM_OK) return rc;
-        ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(key->stage[s]);
-        for (size_t k = 0; k < n; ++k) {
-            const size_t i = at(k);
-            ChunkDesc& d = h_desc[k];
-            memset(&d, 0, sizeof(d));
-            d.index = (uint32_t)i;
-            d.src = (const uint8_t*)src[i];
-            d.dst = (uint8_t*)dst[i];
-            d.len = len[i];
-            d.aad_len = aad_len ? aad_len[i] : 0;
-            d.aad = d.aad_len ? (const uint8_t*)aad[i] : nullptr;
-        }
-        const uint32_t groups = (nchunks + kSmallChunksPerGroup - 1) / kSmallChunksPerGroup;
-        if (key->timing)
-            PGCM_HIP(hipEventRecord(key->bulk_start[key->timed % kTimingRing], stream));
-        if (decrypt)
-            launch_small<true>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
-                               (const ChunkDesc*)h_desc, nchunks, ivs, iv_len, tags, ok);
-        else
-            launch_small<false>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
-                                (const ChunkDesc*)h_desc, nchunks, ivs, iv_len, tags,
-                                (uint8_t*)nullptr);
-        if (key->timing) {
-            PGCM_HIP(hipEventRecord(key->bulk_stop[key->timed % kTimingRing], stream));
-            ++key->timed;
-        }
-        PGCM_HIP(hipGetLastError());
-        PGCM_HIP(hipEventRecord(key->stage_done[s], stream));
-        key->stage_used[s] = true;
-        key->next_stage = (s + 1) % kStages;
-        return PGCM_OK;
-    }
+WorkLayout lay_out(const BatchArgs& a, const BatchPlan& p) {
+    WorkLayout w;
+    w.desc = 0;
+    w.ubase = round_up(w.desc + sizeof(ChunkDesc) * a.n, 256);
+    w.coarse = round_up(w.ubase + sizeof(uint32_t) * (a.n + 1), 256);
+    w.fold = round_up(w.coarse + sizeof(uint32_t) * (size_t)p.ncoarse, 256);
+    w.upload_bytes = round_up(w.fold + sizeof(FoldItem) * (size_t)p.nfold, 256);
+    w.counter = w.upload_bytes;
+    w.ekj0 = w.counter + 256;
+    w.j0 = w.ekj0 + sizeof(Block) * a.n;  // pre-counter blocks: only for IVs not 96 bits long
+    w.sets = round_up(w.j0 + (a.iv_len == 12 ? 0 : sizeof(Block) * a.n), 1024);
+    w.bytes = w.sets + sizeof(Block) * 64 * (size_t)p.nslots;
+    return w;
+}
 
-    // workspace layout; the regions up to upload_bytes are written by the host and uploaded
-    const size_t off_desc = 0;
-    const size_t off_ubase = round_up(off_desc + sizeof(ChunkDesc) * n, 256);
-    const size_t off_coarse = round_up(off_ubase + sizeof(uint32_t) * (n + 1), 256);
-    const size_t off_fold = round_up(off_coarse + sizeof(uint32_t) * (size_t)ncoarse, 256);
-    const size_t upload_bytes = round_up(off_fold + sizeof(FoldItem) * (size_t)nfold, 256);
-    const size_t off_counter = upload_bytes;
-    const size_t off_ekj0 = off_counter + 256;
-    // pre-counter blocks, only for IVs that are not 96 bits long
-    const size_t off_j0 = off_ekj0 + sizeof(Block) * n;
-    const size_t off_sets = round_up(off_j0 + (iv_len == 12 ? 0 : sizeof(Block) * n), 1024);
-    const size_t work_bytes = off_sets + sizeof(Block) * 64 * (size_t)nslots;
-
-    const int s = key->next_stage;
-    rc = ensure_stage(key, s, upload_bytes);
-    if (rc != PGCM_OK) return rc;
-    rc = ensure_work(key, work_bytes, stream);
-    if (rc != PGCM_OK) return rc;
-
-    ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(key->stage[s] + off_desc);
-    uint32_t* h_ubase = reinterpret_cast<uint32_t*>(key->stage[s] + off_ubase);
-    uint32_t* h_coarse = reinterpret_cast<uint32_t*>(key->stage[s] + off_coarse);
-    FoldItem* h_fold = reinterpret_cast<FoldItem*>(key->stage[s] + off_fold);
-    uint32_t unit = 0, slot = nunits, coarse_next = 0;
+// Descriptors, unit maps and fold lists of the batch, written into the staging buffer.
+void fill_schedule(const BatchArgs& a, const BatchPlan& p, const WorkLayout& w, uint8_t* stage) {
+    ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(stage + w.desc);
+    uint32_t* h_ubase = reinterpret_cast<uint32_t*>(stage + w.ubase);
+    uint32_t* h_coarse = reinterpret_cast<uint32_t*>(stage + w.coarse);
+    FoldItem* h_fold = reinterpret_cast<FoldItem*>(stage + w.fold);
+    uint32_t unit = 0, slot = p.nunits, coarse_next = 0;
     uint32_t fold_fill[kMaxLevels] = {0, 0, 0, 0};
-    for (size_t k = 0; k < n; ++k) {
-        const size_t i = at(k);
-        const UnitPlan p = plan_chunk(len[i], unit_power);
+    for (size_t k = 0; k < a.n; ++k) {
+        const size_t i = a.at(k);
+        const UnitPlan up = plan_chunk(a.len[i], p.unit_power);
         ChunkDesc& d = h_desc[k];
-        d.src = (const uint8_t*)src[i];
-        d.dst = (uint8_t*)dst[i];
-        d.len = len[i];
-        d.aad_len = aad_len ? aad_len[i] : 0;
-        d.aad = d.aad_len ? (const uint8_t*)aad[i] : nullptr;
+        describe_chunk(a, i, d);
         d.unit_base = unit;
-        d.nunits = p.nunits;
-        d.first_blocks = p.first_blocks;
-        d.index = (uint32_t)i;
+        d.nunits = up.nunits;
+        d.first_blocks = up.first_blocks;
         h_ubase[k] = unit;
         // coarse map: for every 2^kCoarseShift-th unit, the chunk that holds it
-        while (coarse_next < ncoarse && ((uint64_t)coarse_next << kCoarseShift) < (uint64_t)unit + p.nunits) {
+        while (coarse_next < p.ncoarse &&
+               ((uint64_t)coarse_next << kCoarseShift) < (uint64_t)unit + up.nunits)
             h_coarse[coarse_next++] = (uint32_t)k;
-        }
         // fold levels: groups of kFan sets counted back from the end, the first one short
-        uint32_t base = unit, count = p.nunits, power = unit_power, level = 0;
+        uint32_t base = unit, count = up.nunits, power = p.unit_power, level = 0;
         while (count > kFan) {
             const uint32_t groups = (count + kFan - 1) / kFan;
             const uint32_t first = count - (groups - 1) * kFan;
-            FoldItem* items = h_fold + fold_first[level] + fold_fill[level];
+            FoldItem* items = h_fold + p.fold_first[level] + fold_fill[level];
             for (uint32_t g = 0; g < groups; ++g) {
                 items[g].in_base = base + (g == 0 ? 0 : first + (g - 1) * kFan);
                 items[g].in_count = g == 0 ? first : kFan;
@@ -356,82 +339,144 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
         d.final_base = base;
         d.final_count = count;
         d.final_power = power;
-        unit += p.nunits;
+        unit += up.nunits;
     }
-    h_ubase[n] = unit;
-    while (coarse_next < ncoarse) h_coarse[coarse_next++] = nchunks ? nchunks - 1 : 0;
+    h_ubase[a.n] = unit;
+    while (coarse_next < p.ncoarse) h_coarse[coarse_next++] = (uint32_t)a.n - 1;
+}
 
+int record_timing_start(pgcm_key* key, hipStream_t stream) {
+    if (key->timing) PGCM_HIP(hipEventRecord(key->bulk_start[key->timed % kTimingRing], stream));
+    return PGCM_OK;
+}
+
+int record_timing_stop(pgcm_key* key, hipStream_t stream) {
+    if (key->timing) {
+        PGCM_HIP(hipEventRecord(key->bulk_stop[key->timed % kTimingRing], stream));
+        ++key->timed;
+    }
+    return PGCM_OK;
+}
+
+// Small-transfer path: one kernel, descriptors read straight from the pinned staging buffer, no
+// device workspace.
+int run_small_batch(pgcm_key* key, const BatchArgs& a) {
+    const uint32_t nchunks = (uint32_t)a.n;
+    const int s = key->next_stage;
+    int rc = ensure_stage(key, s, sizeof(ChunkDesc) * a.n);
+    if (rc != PGCM_OK) return rc;
+    ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(key->stage[s]);
+    for (size_t k = 0; k < a.n; ++k) describe_chunk(a, a.at(k), h_desc[k]);
+    const dim3 grid((nchunks + kSmallChunksPerGroup - 1) / kSmallChunksPerGroup);
+    const KeyTables* kt = key->tables;
+    rc = record_timing_start(key, a.stream);
+    if (rc != PGCM_OK) return rc;
+    if (a.decrypt)
+        launch_small<true>(key->rounds, grid, a.stream, kt, (const ChunkDesc*)h_desc, nchunks,
+                           a.ivs, a.iv_len, a.tags, a.ok);
+    else
+        launch_small<false>(key->rounds, grid, a.stream, kt, (const ChunkDesc*)h_desc, nchunks,
+                            a.ivs, a.iv_len, a.tags, (uint8_t*)nullptr);
+    rc = record_timing_stop(key, a.stream);
+    if (rc != PGCM_OK) return rc;
+    PGCM_HIP(hipGetLastError());
+    PGCM_HIP(hipEventRecord(key->stage_done[s], a.stream));
+    key->stage_used[s] = true;
+    key->next_stage = (s + 1) % kStages;
+    return PGCM_OK;
+}
+
+// One batch under one key: validate everything, then enqueue upload, J0 (if needed), bulk, fold
+// levels and final kernels on the stream.
+int run_batch(pgcm_key* key, const BatchArgs& a) {
+    if (key == nullptr || key->tables == nullptr) return PGCM_ERR_ARG;
+    int rc = check_batch(a);
+    if (rc != PGCM_OK || a.n == 0) return rc;
+    BatchPlan p;
+    rc = plan_batch(key, a, &p);  // nothing has been touched so far
+    if (rc != PGCM_OK) return rc;
+    int cur_device = -1;
+    PGCM_HIP(hipGetDevice(&cur_device));
+    if (cur_device != key->device) return PGCM_ERR_ARG;  // the key lives on another GPU
+    if (p.all_small) return run_small_batch(key, a);
+
+    const uint32_t nchunks = (uint32_t)a.n;
+    const WorkLayout w = lay_out(a, p);
+    const int s = key->next_stage;
+    rc = ensure_stage(key, s, w.upload_bytes);
+    if (rc != PGCM_OK) return rc;
+    rc = ensure_work(key, w.bytes, a.stream);
+    if (rc != PGCM_OK) return rc;
+    fill_schedule(a, p, w, key->stage[s]);
     {
-        const uint32_t n16 = (uint32_t)(upload_bytes / 16);
+        const uint32_t n16 = (uint32_t)(w.upload_bytes / 16);
         uint32_t groups = (n16 + 255) / 256;
         if (groups > 1024) groups = 1024;
-        hipLaunchKernelGGL(upload_kernel, dim3(groups), dim3(256), 0, stream,
+        hipLaunchKernelGGL(upload_kernel, dim3(groups), dim3(256), 0, a.stream,
                            reinterpret_cast<uint4*>(key->work),
                            reinterpret_cast<const uint4*>(key->stage[s]), n16);
     }
-    PGCM_HIP(hipEventRecord(key->stage_done[s], stream));
+    PGCM_HIP(hipEventRecord(key->stage_done[s], a.stream));
     key->stage_used[s] = true;
     key->next_stage = (s + 1) % kStages;
 
-    const ChunkDesc* d_desc = reinterpret_cast<const ChunkDesc*>(key->work + off_desc);
-    const uint32_t* d_ubase = reinterpret_cast<const uint32_t*>(key->work + off_ubase);
-    const uint32_t* d_coarse = reinterpret_cast<const uint32_t*>(key->work + off_coarse);
-    const FoldItem* d_fold = reinterpret_cast<const FoldItem*>(key->work + off_fold);
-    uint32_t* d_counter = reinterpret_cast<uint32_t*>(key->work + off_counter);
-    Block* d_ekj0 = reinterpret_cast<Block*>(key->work + off_ekj0);
-    Block* d_sets = reinterpret_cast<Block*>(key->work + off_sets);
-    Block* d_j0 = iv_len == 12 ? nullptr : reinterpret_cast<Block*>(key->work + off_j0);
+    const KeyTables* kt = key->tables;
+    const ChunkDesc* d_desc = reinterpret_cast<const ChunkDesc*>(key->work + w.desc);
+    const uint32_t* d_ubase = reinterpret_cast<const uint32_t*>(key->work + w.ubase);
+    const uint32_t* d_coarse = reinterpret_cast<const uint32_t*>(key->work + w.coarse);
+    const FoldItem* d_fold = reinterpret_cast<const FoldItem*>(key->work + w.fold);
+    uint32_t* d_counter = reinterpret_cast<uint32_t*>(key->work + w.counter);
+    Block* d_ekj0 = reinterpret_cast<Block*>(key->work + w.ekj0);
+    Block* d_sets = reinterpret_cast<Block*>(key->work + w.sets);
+    Block* d_j0 = a.iv_len == 12 ? nullptr : reinterpret_cast<Block*>(key->work + w.j0);
     if (d_j0 != nullptr)
-        hipLaunchKernelGGL(j0_kernel, dim3((nchunks + 63) / 64), dim3(64), 0, stream, key->tables,
-                           d_desc, ivs, iv_len, nchunks, d_j0);
+        hipLaunchKernelGGL(j0_kernel, dim3((nchunks + 63) / 64), dim3(64), 0, a.stream, kt, d_desc,
+                           a.ivs, a.iv_len, nchunks, d_j0);
 
     // the unit counter is left at zero by the last kernel of every batch; it only needs clearing
     // when the workspace is new (or has moved) or an earlier batch was cut short
     if (key->counter_at != d_counter || key->counter_dirty) {
-        PGCM_HIP(hipMemsetAsync(d_counter, 0, sizeof(uint32_t), stream));
+        PGCM_HIP(hipMemsetAsync(d_counter, 0, sizeof(uint32_t), a.stream));
         key->counter_at = d_counter;
     }
     key->counter_dirty = true;
 
-    if (nunits > 0) {
-        uint32_t groups = (nunits + kWavesPerGroup - 1) / kWavesPerGroup;
+    if (p.nunits > 0) {
+        uint32_t groups = (p.nunits + kWavesPerGroup - 1) / kWavesPerGroup;
         if (groups > (uint32_t)key->num_cu) groups = (uint32_t)key->num_cu;
-        if (key->timing)
-            PGCM_HIP(hipEventRecord(key->bulk_start[key->timed % kTimingRing], stream));
-        if (decrypt)
-            launch_bulk<true>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
-                              d_desc, d_ubase, d_coarse, nunits, unit_power, d_counter, ivs,
-                              (const Block*)d_j0, d_ekj0, d_sets);
+        rc = record_timing_start(key, a.stream);
+        if (rc != PGCM_OK) return rc;
+        if (a.decrypt)
+            launch_bulk<true>(key->rounds, dim3(groups), a.stream, kt, d_desc, d_ubase, d_coarse,
+                              p.nunits, p.unit_power, d_counter, a.ivs, (const Block*)d_j0, d_ekj0,
+                              d_sets);
         else
-            launch_bulk<false>(key->rounds, dim3(groups), stream, (const KeyTables*)key->tables,
-                               d_desc, d_ubase, d_coarse, nunits, unit_power, d_counter, ivs,
-                               (const Block*)d_j0, d_ekj0, d_sets);
-        if (key->timing) {
-            PGCM_HIP(hipEventRecord(key->bulk_stop[key->timed % kTimingRing], stream));
-            ++key->timed;
-        }
+            launch_bulk<false>(key->rounds, dim3(groups), a.stream, kt, d_desc, d_ubase, d_coarse,
+                               p.nunits, p.unit_power, d_counter, a.ivs, (const Block*)d_j0,
+                               d_ekj0, d_sets);
+        rc = record_timing_stop(key, a.stream);
+        if (rc != PGCM_OK) return rc;
     }
     for (uint32_t l = 0; l < kMaxLevels; ++l) {
-        if (fold_count[l] == 0) continue;
+        if (p.fold_count[l] == 0) continue;
+        const uint32_t power = p.unit_power + kFanPower * l;
         // few items: a workgroup each, folding as a tree; many: a wavefront each, as a chain
-        if (fold_count[l] <= kFoldTreeMaxItems)
-            hipLaunchKernelGGL(fold_tree_kernel, dim3(fold_count[l]), dim3(kFoldTreeWaves * 64), 0,
-                               stream, key->tables, d_fold + fold_first[l],
-                               unit_power + kFanPower * l, d_sets);
+        if (p.fold_count[l] <= kFoldTreeMaxItems)
+            hipLaunchKernelGGL(fold_tree_kernel, dim3(p.fold_count[l]), dim3(kFoldTreeWaves * 64),
+                               0, a.stream, kt, d_fold + p.fold_first[l], power, d_sets);
         else
-            hipLaunchKernelGGL(fold_kernel, dim3(fold_count[l]), dim3(64), 0, stream, key->tables,
-                               d_fold + fold_first[l], unit_power + kFanPower * l, d_sets);
+            hipLaunchKernelGGL(fold_kernel, dim3(p.fold_count[l]), dim3(64), 0, a.stream, kt,
+                               d_fold + p.fold_first[l], power, d_sets);
     }
-    const uint32_t final_groups = (nchunks + 15) / 16;
-    if (decrypt) {
-        hipLaunchKernelGGL(final_kernel<true>, dim3(final_groups), dim3(1024), 0, stream,
-                           key->tables, d_desc, nchunks, ivs, d_j0, d_ekj0, d_sets, tags, ok,
-                           unit_power, d_counter);
-    } else {
-        hipLaunchKernelGGL(final_kernel<false>, dim3(final_groups), dim3(1024), 0, stream,
-                           key->tables, d_desc, nchunks, ivs, d_j0, d_ekj0, d_sets, tags, nullptr,
-                           unit_power, d_counter);
-    }
+    const dim3 final_grid((nchunks + 15) / 16);
+    if (a.decrypt)
+        hipLaunchKernelGGL(final_kernel<true>, final_grid, dim3(1024), 0, a.stream, kt, d_desc,
+                           nchunks, a.ivs, d_j0, d_ekj0, d_sets, a.tags, a.ok, p.unit_power,
+                           d_counter);
+    else
+        hipLaunchKernelGGL(final_kernel<false>, final_grid, dim3(1024), 0, a.stream, kt, d_desc,
+                           nchunks, a.ivs, d_j0, d_ekj0, d_sets, a.tags, (uint8_t*)nullptr,
+                           p.unit_power, d_counter);
     PGCM_HIP(hipGetLastError());
     key->counter_dirty = false;
     return PGCM_OK;
@@ -439,42 +484,41 @@ int run_batch(bool decrypt, pgcm_key* key, size_t n, const uint32_t* order, cons
 
 // A batch whose chunks name their key: the chunks are grouped by key (keeping their order) and
 // every group runs as one batch of its key, one after the other on the stream.
-int run_batch_keys(bool decrypt, pgcm_key* const* keys, size_t nkeys, const uint32_t* key_index,
-                   size_t n, const uint8_t* ivs, uint32_t iv_len, const void* const* aad,
-                   const uint32_t* aad_len, const void* const* src, const uint64_t* len,
-                   void* const* dst, uint8_t* tags, uint8_t* ok, void* hip_stream) {
+int run_batch_keys(pgcm_key* const* keys, size_t nkeys, const uint32_t* key_index,
+                   const BatchArgs& all) {
     if (keys == nullptr || nkeys == 0 || nkeys > 0x7FFFFFFFull) return PGCM_ERR_ARG;
     int cur_device = -1;
     PGCM_HIP(hipGetDevice(&cur_device));
     for (size_t k = 0; k < nkeys; ++k)
         if (keys[k] == nullptr || keys[k]->tables == nullptr || keys[k]->device != cur_device)
             return PGCM_ERR_ARG;
-    int rc = check_batch(n, ivs, iv_len, aad, aad_len, src, len, dst, tags, decrypt, ok);
-    if (rc != PGCM_OK || n == 0) return rc;
+    int rc = check_batch(all);
+    if (rc != PGCM_OK || all.n == 0) return rc;
     if (key_index == nullptr) return PGCM_ERR_ARG;
     // every chunk is checked before the first group is enqueued
     std::vector<uint32_t> first, fill, order;
     try {
         first.assign(nkeys + 1, 0);
         fill.assign(nkeys, 0);
-        order.resize(n);
+        order.resize(all.n);
     } catch (const std::bad_alloc&) {
         return PGCM_ERR_NOMEM;
     }
-    for (size_t i = 0; i < n; ++i) {
+    for (size_t i = 0; i < all.n; ++i) {
         if (key_index[i] >= nkeys) return PGCM_ERR_ARG;
-        rc = check_chunk(i, aad, aad_len, src, len, dst);
+        rc = check_chunk(all, i);
         if (rc != PGCM_OK) return rc;
         ++first[key_index[i] + 1];
     }
     for (size_t k = 0; k < nkeys; ++k) first[k + 1] += first[k];
     for (size_t k = 0; k < nkeys; ++k) fill[k] = first[k];
-    for (size_t i = 0; i < n; ++i) order[fill[key_index[i]]++] = (uint32_t)i;
+    for (size_t i = 0; i < all.n; ++i) order[fill[key_index[i]]++] = (uint32_t)i;
     for (size_t k = 0; k < nkeys; ++k) {
-        const size_t count = first[k + 1] - first[k];
-        if (count == 0) continue;
-        rc = run_batch(decrypt, keys[k], count, order.data() + first[k], ivs, iv_len, aad, aad_len,
-                       src, len, dst, tags, ok, hip_stream);
+        BatchArgs group = all;
+        group.n = first[k + 1] - first[k];
+        group.order = order.data() + first[k];
+        if (group.n == 0) continue;
+        rc = run_batch(keys[k], group);
         if (rc != PGCM_OK) return rc;
     }
     return PGCM_OK;
@@ -558,31 +602,31 @@ void pgcm_free_key(pgcm_key_t* k) {
 int pgcm_encrypt_batch(pgcm_key_t* key, size_t n, const uint8_t* ivs, const void* const* aad,
                        const uint32_t* aad_len, const void* const* src, const uint64_t* len,
                        void* const* dst, uint8_t* tags, void* hip_stream) {
-    return run_batch(false, key, n, nullptr, ivs, 12, aad, aad_len, src, len, dst, tags, nullptr,
-                     hip_stream);
+    return run_batch(key, BatchArgs{false, n, nullptr, ivs, 12, aad, aad_len, src, len, dst, tags,
+                                    nullptr, (hipStream_t)hip_stream});
 }
 
 int pgcm_encrypt_batch_iv(pgcm_key_t* key, size_t n, const uint8_t* ivs, uint32_t iv_bytes,
                           const void* const* aad, const uint32_t* aad_len, const void* const* src,
                           const uint64_t* len, void* const* dst, uint8_t* tags, void* hip_stream) {
-    return run_batch(false, key, n, nullptr, ivs, iv_bytes, aad, aad_len, src, len, dst, tags, nullptr,
-                     hip_stream);
+    return run_batch(key, BatchArgs{false, n, nullptr, ivs, iv_bytes, aad, aad_len, src, len, dst,
+                                    tags, nullptr, (hipStream_t)hip_stream});
 }
 
 int pgcm_decrypt_verify_batch(pgcm_key_t* key, size_t n, const uint8_t* ivs,
                               const void* const* aad, const uint32_t* aad_len,
                               const void* const* src, const uint64_t* len, void* const* dst,
                               const uint8_t* tags, uint8_t* ok, void* hip_stream) {
-    return run_batch(true, key, n, nullptr, ivs, 12, aad, aad_len, src, len, dst,
-                     const_cast<uint8_t*>(tags), ok, hip_stream);
+    return run_batch(key, BatchArgs{true, n, nullptr, ivs, 12, aad, aad_len, src, len, dst,
+                                    const_cast<uint8_t*>(tags), ok, (hipStream_t)hip_stream});
 }
 
 int pgcm_decrypt_verify_batch_iv(pgcm_key_t* key, size_t n, const uint8_t* ivs, uint32_t iv_bytes,
                                  const void* const* aad, const uint32_t* aad_len,
                                  const void* const* src, const uint64_t* len, void* const* dst,
                                  const uint8_t* tags, uint8_t* ok, void* hip_stream) {
-    return run_batch(true, key, n, nullptr, ivs, iv_bytes, aad, aad_len, src, len, dst,
-                     const_cast<uint8_t*>(tags), ok, hip_stream);
+    return run_batch(key, BatchArgs{true, n, nullptr, ivs, iv_bytes, aad, aad_len, src, len, dst,
+                                    const_cast<uint8_t*>(tags), ok, (hipStream_t)hip_stream});
 }
 
 int pgcm_encrypt_batch_keys(pgcm_key_t* const* keys, size_t nkeys, const uint32_t* key_index,
@@ -590,8 +634,9 @@ int pgcm_encrypt_batch_keys(pgcm_key_t* const* keys, size_t nkeys, const uint32_
                             const void* const* aad, const uint32_t* aad_len,
                             const void* const* src, const uint64_t* len, void* const* dst,
                             uint8_t* tags, void* hip_stream) {
-    return run_batch_keys(false, keys, nkeys, key_index, n, ivs, iv_bytes, aad, aad_len, src, len,
-                          dst, tags, nullptr, hip_stream);
+    return run_batch_keys(keys, nkeys, key_index,
+                          BatchArgs{false, n, nullptr, ivs, iv_bytes, aad, aad_len, src, len, dst,
+                                    tags, nullptr, (hipStream_t)hip_stream});
 }
 
 int pgcm_decrypt_verify_batch_keys(pgcm_key_t* const* keys, size_t nkeys,
@@ -600,8 +645,9 @@ int pgcm_decrypt_verify_batch_keys(pgcm_key_t* const* keys, size_t nkeys,
                                    const uint32_t* aad_len, const void* const* src,
                                    const uint64_t* len, void* const* dst, const uint8_t* tags,
                                    uint8_t* ok, void* hip_stream) {
-    return run_batch_keys(true, keys, nkeys, key_index, n, ivs, iv_bytes, aad, aad_len, src, len,
-                          dst, const_cast<uint8_t*>(tags), ok, hip_stream);
+    return run_batch_keys(keys, nkeys, key_index,
+                          BatchArgs{true, n, nullptr, ivs, iv_bytes, aad, aad_len, src, len, dst,
+                                    const_cast<uint8_t*>(tags), ok, (hipStream_t)hip_stream});
 }
 
 const char* pgcm_strerror(int status) {

@@ -203,6 +203,35 @@ def test_two_keys_and_back_to_back_batches_on_one_stream():
     k1.free()
 
 
+def test_two_keys_on_two_streams_at_once():
+    """a key object belongs to one stream at a time, but two keys may run on two streams
+    concurrently; the streams are ordinary torch streams of default priority"""
+    wa, wb = workloads.mini(3), workloads.mini(4)
+    wb.key = np.random.default_rng(3).integers(0, 256, 32, dtype=np.uint8)
+    ha, hb = wa.payload_host(), wb.payload_host()
+    ka, kb = pgcm.expand_key(wa.key), pgcm.expand_key(wb.key)
+    ba = DeviceBatch(wa, torch.from_numpy(ha).cuda())
+    bb = DeviceBatch(wb, torch.from_numpy(hb).cuda())
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(4):
+        ba.encrypt(ka, stream=sa)
+        bb.encrypt(kb, stream=sb)
+        ba.decrypt(ka, stream=sa)
+        bb.decrypt(kb, stream=sb)
+    sa.synchronize()
+    sb.synchronize()
+    for w, h, b in ((wa, ha, ba), (wb, hb, bb)):
+        cts, tags = _oracle_encrypt(w, h)
+        ch = b.cipher.cpu().numpy()
+        for i in range(w.n):
+            assert np.array_equal(w.chunk(ch, i), cts[i])
+        assert np.array_equal(b.tags.cpu().numpy().reshape(-1, 16), tags)
+        assert bool((b.ok == 1).all()) and torch.equal(b.back, b.plain)
+    ka.free()
+    kb.free()
+
+
 def test_error_codes_and_empty_batch():
     w = workloads.config1(n=4, size=64)
     key = pgcm.expand_key(w.key)
