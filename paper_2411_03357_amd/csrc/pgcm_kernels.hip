@@ -812,6 +812,71 @@ __device__ __forceinline__ uint32_t row_shift_down(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x100 + S, 0xF, 0xF, true);
 }
 
+// The 64 lane sums of a chunk -> its GHASH state, in every lane.  Lane j's sum still lacks
+// H^(64 - j).  Tree: with s = 32, 16, .., 1 lane j takes Y_j * H^s + Y_(j+s) (DPP inside rows of
+// 16 lanes, LDS permutes across them); lane 0 ends with sum_j Y_j * H^(63 - j); then one more H.
+// tree_tables: LDS address of the nibble tables of H^(2^k), k = 0 .. 5, 8 KiB apart.
+__device__ __forceinline__ void fold_lanes(uint32_t tree_tables, uint32_t y[4]) {
+    auto tree_step = [&](uint32_t k, uint32_t n0, uint32_t n1, uint32_t n2, uint32_t n3) {
+        ghash_mul_lds(tree_tables + k * kLdsGhBytes, y);
+        y[0] ^= n0, y[1] ^= n1, y[2] ^= n2, y[3] ^= n3;
+    };
+    tree_step(5, __shfl_down(y[0], 32, 64), __shfl_down(y[1], 32, 64), __shfl_down(y[2], 32, 64),
+              __shfl_down(y[3], 32, 64));
+    tree_step(4, __shfl_down(y[0], 16, 64), __shfl_down(y[1], 16, 64), __shfl_down(y[2], 16, 64),
+              __shfl_down(y[3], 16, 64));
+    tree_step(3, row_shift_down<8>(y[0]), row_shift_down<8>(y[1]), row_shift_down<8>(y[2]),
+              row_shift_down<8>(y[3]));
+    tree_step(2, row_shift_down<4>(y[0]), row_shift_down<4>(y[1]), row_shift_down<4>(y[2]),
+              row_shift_down<4>(y[3]));
+    tree_step(1, row_shift_down<2>(y[0]), row_shift_down<2>(y[1]), row_shift_down<2>(y[2]),
+              row_shift_down<2>(y[3]));
+    tree_step(0, row_shift_down<1>(y[0]), row_shift_down<1>(y[1]), row_shift_down<1>(y[2]),
+              row_shift_down<1>(y[3]));
+    ghash_mul_lds(tree_tables, y);
+    // only lane 0 holds the chunk's sum: hand it to every lane
+    for (int k = 0; k < 4; ++k) y[k] = __builtin_amdgcn_readfirstlane(y[k]);
+}
+
+// From the GHASH state over A and C (the same in every lane) to the end of the invocation:
+// length block, one more H, mask with E_K(J0) (SP 800-38D 7.1 steps 5-6); then write the tag, or
+// compare it and write the verdict (7.2), wiping the output of a rejected chunk.
+// h_table: LDS address of the nibble table of H.
+template <bool kDecrypt>
+__device__ __forceinline__ void finish_chunk(uint32_t h_table, uint32_t y[4],
+                                             const uint32_t mask[4], const ChunkDesc& cd,
+                                             uint8_t* __restrict__ tags, uint8_t* __restrict__ ok,
+                                             uint32_t lane) {
+    // [8 |A|]_64 || [8 |C|]_64, big endian
+    const uint64_t abits = (uint64_t)cd.aad_len * 8, cbits = cd.len * 8;
+    y[0] ^= bswap32((uint32_t)(abits >> 32));
+    y[1] ^= bswap32((uint32_t)abits);
+    y[2] ^= bswap32((uint32_t)(cbits >> 32));
+    y[3] ^= bswap32((uint32_t)cbits);
+    ghash_mul_lds(h_table, y);
+    const uint32_t t[4] = {y[0] ^ mask[0], y[1] ^ mask[1], y[2] ^ mask[2], y[3] ^ mask[3]};
+
+    uint8_t* tp = tags + (uint64_t)cd.index * 16;
+    if (!kDecrypt) {
+        if (lane == 0)
+            for (int b = 0; b < 16; ++b) tp[b] = (uint8_t)(t[b / 4] >> (8 * (b % 4)));
+    } else {
+        // all 16 bytes, no data-dependent exit (every lane holds the same values)
+        uint32_t diff = 0;
+        for (int b = 0; b < 16; ++b) diff |= (uint32_t)tp[b] ^ ((t[b / 4] >> (8 * (b % 4))) & 0xFF);
+        diff = __builtin_amdgcn_readfirstlane(diff);
+        if (lane == 0) ok[cd.index] = diff == 0 ? 1 : 0;
+        if (diff != 0) {
+            // rejected: unauthenticated plaintext must not stay behind; the wavefront zero-fills
+            // exactly len bytes
+            const uint64_t whole = cd.len / 16;
+            uint4* d = reinterpret_cast<uint4*>(cd.dst);
+            for (uint64_t b = lane; b < whole; b += 64) d[b] = make_uint4(0, 0, 0, 0);
+            for (uint64_t b = whole * 16 + lane; b < cd.len; b += 64) cd.dst[b] = 0;
+        }
+    }
+}
+
 }  // namespace
 
 // One wavefront (= one workgroup) per fold item of one level.
@@ -874,9 +939,7 @@ __global__ __launch_bounds__(kFoldTreeWaves * 64) void fold_tree_kernel(
 }
 
 // Per chunk (one wavefront each, sixteen chunks a workgroup): fold the remaining sets, fold the 64
-// lanes with a reduction tree (DPP inside rows of 16 lanes, LDS permutes across them), add the
-// length block, mask with E_K(J0) (SP 800-38D 7.1 steps 5-6); then write the tag, or compare it
-// and write the verdict (7.2).  Workgroup 0 also clears `counter` for the next batch.
+// lanes, finish the tag.  Workgroup 0 also clears `counter` for the next batch.
 // LDS: nibble tables of H^1 .. H^32 (tree), and of the two most common fold distances.
 // unit_power: log2 of the blocks per unit the batch was cut into.
 constexpr uint32_t kFinalChunksPerGroup = 16;
@@ -918,58 +981,10 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
         if (cd.final_power == unit_power) fold_table = lds_offset(tables[6]);
         if (cd.final_power == unit_power + kFanPower) fold_table = lds_offset(tables[7]);
         fold_sets(kt, sets, cd.final_base, cd.final_count, cd.final_power, lane, fold_table, y);
-        // lanes -> one value: lane j's sum still lacks H^(64 - j).  Tree: with s = 32, 16, .., 1
-        // lane j takes Y_j * H^s + Y_(j+s); lane 0 ends with sum_j Y_j * H^(63 - j); then one more H.
-        auto tree_step = [&](uint32_t k, uint32_t n0, uint32_t n1, uint32_t n2, uint32_t n3) {
-            ghash_mul_lds(lds_offset(tables[k]), y);
-            y[0] ^= n0, y[1] ^= n1, y[2] ^= n2, y[3] ^= n3;
-        };
-        tree_step(5, __shfl_down(y[0], 32, 64), __shfl_down(y[1], 32, 64),
-                  __shfl_down(y[2], 32, 64), __shfl_down(y[3], 32, 64));
-        tree_step(4, __shfl_down(y[0], 16, 64), __shfl_down(y[1], 16, 64),
-                  __shfl_down(y[2], 16, 64), __shfl_down(y[3], 16, 64));
-        tree_step(3, row_shift_down<8>(y[0]), row_shift_down<8>(y[1]), row_shift_down<8>(y[2]),
-                  row_shift_down<8>(y[3]));
-        tree_step(2, row_shift_down<4>(y[0]), row_shift_down<4>(y[1]), row_shift_down<4>(y[2]),
-                  row_shift_down<4>(y[3]));
-        tree_step(1, row_shift_down<2>(y[0]), row_shift_down<2>(y[1]), row_shift_down<2>(y[2]),
-                  row_shift_down<2>(y[3]));
-        tree_step(0, row_shift_down<1>(y[0]), row_shift_down<1>(y[1]), row_shift_down<1>(y[2]),
-                  row_shift_down<1>(y[3]));
-        ghash_mul_lds(lds_offset(tables[0]), y);
-        // only lane 0 holds the chunk's sum: hand it to every lane
-        for (int k = 0; k < 4; ++k) y[k] = __builtin_amdgcn_readfirstlane(y[k]);
+        fold_lanes(lds_offset(tables[0]), y);
         mask = ekj0[i];
     }
-
-    // [8 |A|]_64 || [8 |C|]_64, big endian
-    const uint64_t abits = (uint64_t)cd.aad_len * 8, cbits = cd.len * 8;
-    y[0] ^= bswap32((uint32_t)(abits >> 32));
-    y[1] ^= bswap32((uint32_t)abits);
-    y[2] ^= bswap32((uint32_t)(cbits >> 32));
-    y[3] ^= bswap32((uint32_t)cbits);
-    ghash_mul_lds(lds_offset(tables[0]), y);
-    const uint32_t t[4] = {y[0] ^ mask.w[0], y[1] ^ mask.w[1], y[2] ^ mask.w[2], y[3] ^ mask.w[3]};
-
-    uint8_t* tp = tags + (uint64_t)cd.index * 16;
-    if (!kDecrypt) {
-        if (lane == 0)
-            for (int b = 0; b < 16; ++b) tp[b] = (uint8_t)(t[b / 4] >> (8 * (b % 4)));
-    } else {
-        // all 16 bytes, no data-dependent exit (every lane holds the same values)
-        uint32_t diff = 0;
-        for (int b = 0; b < 16; ++b) diff |= (uint32_t)tp[b] ^ ((t[b / 4] >> (8 * (b % 4))) & 0xFF);
-        diff = __builtin_amdgcn_readfirstlane(diff);
-        if (lane == 0) ok[cd.index] = diff == 0 ? 1 : 0;
-        if (diff != 0) {
-            // rejected: unauthenticated plaintext must not stay behind; the wavefront zero-fills
-            // exactly len bytes
-            const uint64_t whole = cd.len / 16;
-            uint4* d = reinterpret_cast<uint4*>(cd.dst);
-            for (uint64_t b = lane; b < whole; b += 64) d[b] = make_uint4(0, 0, 0, 0);
-            for (uint64_t b = whole * 16 + lane; b < cd.len; b += 64) cd.dst[b] = 0;
-        }
-    }
+    finish_chunk<kDecrypt>(lds_offset(tables[0]), y, mask.w, cd, tags, ok, lane);
 }
 
 template __global__ void final_kernel<false>(const KeyTables*, const ChunkDesc*, uint32_t,
@@ -1102,49 +1117,9 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
         // nothing was hashed yet: the state is what the AAD left
         for (int w = 0; w < 4; ++w) y[w] = aad_y.w[w];
     } else {
-        auto tree_step = [&](uint32_t k, uint32_t n0, uint32_t n1, uint32_t n2, uint32_t n3) {
-            ghash_mul_lds(lds_offset(tables[k]), y);
-            y[0] ^= n0, y[1] ^= n1, y[2] ^= n2, y[3] ^= n3;
-        };
-        tree_step(5, __shfl_down(y[0], 32, 64), __shfl_down(y[1], 32, 64),
-                  __shfl_down(y[2], 32, 64), __shfl_down(y[3], 32, 64));
-        tree_step(4, __shfl_down(y[0], 16, 64), __shfl_down(y[1], 16, 64),
-                  __shfl_down(y[2], 16, 64), __shfl_down(y[3], 16, 64));
-        tree_step(3, row_shift_down<8>(y[0]), row_shift_down<8>(y[1]), row_shift_down<8>(y[2]),
-                  row_shift_down<8>(y[3]));
-        tree_step(2, row_shift_down<4>(y[0]), row_shift_down<4>(y[1]), row_shift_down<4>(y[2]),
-                  row_shift_down<4>(y[3]));
-        tree_step(1, row_shift_down<2>(y[0]), row_shift_down<2>(y[1]), row_shift_down<2>(y[2]),
-                  row_shift_down<2>(y[3]));
-        tree_step(0, row_shift_down<1>(y[0]), row_shift_down<1>(y[1]), row_shift_down<1>(y[2]),
-                  row_shift_down<1>(y[3]));
-        ghash_mul_lds(lds_offset(tables[0]), y);
-        for (int k = 0; k < 4; ++k) y[k] = __builtin_amdgcn_readfirstlane(y[k]);
+        fold_lanes(lds_offset(tables[0]), y);
     }
-    const uint64_t abits = (uint64_t)cd.aad_len * 8, cbits = cd.len * 8;
-    y[0] ^= bswap32((uint32_t)(abits >> 32));
-    y[1] ^= bswap32((uint32_t)abits);
-    y[2] ^= bswap32((uint32_t)(cbits >> 32));
-    y[3] ^= bswap32((uint32_t)cbits);
-    ghash_mul_lds(lds_offset(tables[0]), y);
-    const uint32_t t[4] = {y[0] ^ mask[0], y[1] ^ mask[1], y[2] ^ mask[2], y[3] ^ mask[3]};
-
-    uint8_t* tp = tags + (uint64_t)cd.index * 16;
-    if (!kDecrypt) {
-        if (lane == 0)
-            for (int b = 0; b < 16; ++b) tp[b] = (uint8_t)(t[b / 4] >> (8 * (b % 4)));
-    } else {
-        uint32_t diff = 0;
-        for (int b = 0; b < 16; ++b) diff |= (uint32_t)tp[b] ^ ((t[b / 4] >> (8 * (b % 4))) & 0xFF);
-        diff = __builtin_amdgcn_readfirstlane(diff);
-        if (lane == 0) ok[cd.index] = diff == 0 ? 1 : 0;
-        if (diff != 0) {
-            const uint64_t whole = cd.len / 16;
-            uint4* d = reinterpret_cast<uint4*>(cd.dst);
-            for (uint64_t b = lane; b < whole; b += 64) d[b] = make_uint4(0, 0, 0, 0);
-            for (uint64_t b = whole * 16 + lane; b < cd.len; b += 64) cd.dst[b] = 0;
-        }
-    }
+    finish_chunk<kDecrypt>(lds_offset(tables[0]), y, mask, cd, tags, ok, lane);
 }
 
 #define PGCM_INSTANTIATE_SMALL(D, R)                                                      \
