@@ -48,7 +48,8 @@ typedef enum {
     PGCM_ERR_LEN = -3,   /* a chunk is longer than 2^36 - 32 bytes (the GCM limit), or than a
                             forced unit size allows (pgcm_set_unit_bytes) */
     PGCM_ERR_NOMEM = -4, /* host or device allocation failed */
-    PGCM_ERR_HIP = -5    /* a HIP call failed; see pgcm_last_hip_error */
+    PGCM_ERR_HIP = -5,   /* a HIP call failed; see pgcm_last_hip_error */
+    PGCM_ERR_BUSY = -6   /* pgcm_bounce.h: every buffer of a pool is held */
 } pgcm_status;
 
 #define PGCM_MAX_CHUNK_BYTES ((((uint64_t)1) << 36) - 32)

@@ -398,3 +398,70 @@ def seq_iv_bytes(iv0, n) -> bytes:
     out = np.zeros(12, np.uint8)
     _seq_lib().pgcm_seq_iv_bytes(a.ctypes.data, n, out.ctypes.data)
     return out.tobytes()
+
+
+# ---------------------------------------------------------------------------------------------
+# include/pgcm_bounce.h: the pool of pinned bounce buffers
+BOUNCE_EXPORTS = ("pgcm_bounce_create", "pgcm_bounce_destroy", "pgcm_bounce_acquire",
+                  "pgcm_bounce_release", "pgcm_bounce_buffer_bytes", "pgcm_bounce_count")
+
+
+def _bounce_lib():
+    lib = load_library()
+    if not getattr(lib, "_bounce_bound", False):
+        vp = C.c_void_p
+        lib.pgcm_bounce_create.argtypes = [C.c_size_t, C.c_uint32, C.POINTER(vp)]
+        lib.pgcm_bounce_create.restype = C.c_int
+        lib.pgcm_bounce_destroy.argtypes = [vp]
+        lib.pgcm_bounce_destroy.restype = None
+        lib.pgcm_bounce_acquire.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_uint32)]
+        lib.pgcm_bounce_acquire.restype = C.c_int
+        lib.pgcm_bounce_release.argtypes = [vp, C.c_uint32, vp]
+        lib.pgcm_bounce_release.restype = C.c_int
+        lib.pgcm_bounce_buffer_bytes.argtypes = [vp]
+        lib.pgcm_bounce_buffer_bytes.restype = C.c_size_t
+        lib.pgcm_bounce_count.argtypes = [vp]
+        lib.pgcm_bounce_count.restype = C.c_uint32
+        lib._bounce_bound = True
+    return lib
+
+
+class BouncePool:
+    """Owns a pgcm_bounce_t.  acquire() -> (address, slot); release(slot, stream)."""
+
+    def __init__(self, buffer_bytes: int, count: int):
+        self._h = None
+        out = C.c_void_p()
+        _check(_bounce_lib().pgcm_bounce_create(buffer_bytes, count, C.byref(out)))
+        self._h = out.value
+
+    @property
+    def buffer_bytes(self) -> int:
+        return int(_bounce_lib().pgcm_bounce_buffer_bytes(self._h))
+
+    @property
+    def count(self) -> int:
+        return int(_bounce_lib().pgcm_bounce_count(self._h))
+
+    def acquire(self):
+        buf, slot = C.c_void_p(), C.c_uint32()
+        _check(_bounce_lib().pgcm_bounce_acquire(self._h, C.byref(buf), C.byref(slot)))
+        return int(buf.value), int(slot.value)
+
+    def release(self, slot: int, stream=None):
+        _check(_bounce_lib().pgcm_bounce_release(self._h, slot, _stream_handle(stream)))
+
+    def view(self, address: int, nbytes: int) -> np.ndarray:
+        """host view of nbytes at an address inside the pool (no copy)"""
+        return np.ctypeslib.as_array((C.c_uint8 * nbytes).from_address(address))
+
+    def destroy(self):
+        if self._h is not None:
+            _bounce_lib().pgcm_bounce_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -658,6 +658,7 @@ const char* pgcm_strerror(int status) {
         case PGCM_ERR_LEN: return "chunk longer than the GCM limit of 2^36 - 32 bytes, or too long for a forced unit size";
         case PGCM_ERR_NOMEM: return "out of host or device memory";
         case PGCM_ERR_HIP: return "a HIP runtime call failed";
+        case PGCM_ERR_BUSY: return "every buffer of the pool is held";
         default: return "unknown status";
     }
 }

@@ -29,12 +29,16 @@ def test_every_declared_symbol_is_exported():
     assert len(seq_names) == 9 and sorted(pgcm.SEQ_EXPORTS) == seq_names
     for n in seq_names:
         assert hasattr(lib, n), n
+    bounce_names = _declared("pgcm_bounce.h")
+    assert len(bounce_names) == 6 and sorted(pgcm.BOUNCE_EXPORTS) == bounce_names
+    for n in bounce_names:
+        assert hasattr(lib, n), n
 
 
 def test_strerror_and_null_arguments_without_gpu():
     lib = pgcm.load_library()
     assert lib.pgcm_strerror(0) == b"success"
-    for code in (-1, -2, -3, -4, -5, 17):
+    for code in (-1, -2, -3, -4, -5, -6, 17):
         assert len(lib.pgcm_strerror(code)) > 0
     assert lib.pgcm_expand_key(None, None, None) == -1
     assert lib.pgcm_encrypt_batch(None, 1, None, None, None, None, None, None, None, None) == -1
@@ -42,6 +46,18 @@ def test_strerror_and_null_arguments_without_gpu():
                                          None) == -1
     lib.pgcm_free_key(None)
     assert lib.pgcm_last_hip_error() == 0
+    # the bounce pool's argument checks come before any GPU call
+    from paper_2411_03357_amd.binding import _bounce_lib
+    bl = _bounce_lib()
+    out = ctypes.c_void_p()
+    assert bl.pgcm_bounce_create(0, 4, ctypes.byref(out)) == -1
+    assert bl.pgcm_bounce_create(4096, 0, ctypes.byref(out)) == -1
+    assert bl.pgcm_bounce_create(4096, 70000, ctypes.byref(out)) == -1
+    assert bl.pgcm_bounce_create(4096, 4, None) == -1
+    assert bl.pgcm_bounce_acquire(None, None, None) == -1
+    assert bl.pgcm_bounce_release(None, 0, None) == -1
+    assert bl.pgcm_bounce_buffer_bytes(None) == 0 and bl.pgcm_bounce_count(None) == 0
+    bl.pgcm_bounce_destroy(None)
 
 
 def _check_plan(lens, unit):
