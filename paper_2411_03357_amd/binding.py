@@ -465,3 +465,100 @@ class BouncePool:
             self.destroy()
         except Exception:
             pass
+
+
+# ---------------------------------------------------------------------------------------------
+# include/pgcm_pipe.h: the pipeline driver
+PIPE_EXPORTS = ("pgcm_pipe_create", "pgcm_pipe_destroy", "pgcm_pipe_swap_out",
+                "pgcm_pipe_notify_write", "pgcm_pipe_request", "pgcm_pipe_sync",
+                "pgcm_pipe_get_stats")
+
+
+class _PipeConfig(C.Structure):
+    _fields_ = [("iv0", C.c_uint8 * 12), ("depth", C.c_uint32), ("iv_start", C.c_uint64),
+                ("leeway", C.c_uint32), ("history_limit", C.c_uint32),
+                ("swap_threshold", C.c_uint64), ("max_chunk_bytes", C.c_uint64)]
+
+
+class _PipeStats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("transfers", "nops", "ahead_bytes", "critical_bytes",
+                                          "pre_bytes", "dropped_bytes")]
+
+
+_DELIVER_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_uint32, C.c_uint64, C.c_uint64, C.c_uint64,
+                          C.c_void_p, C.c_void_p, C.c_void_p)
+
+
+def _pipe_lib():
+    lib = load_library()
+    if not getattr(lib, "_pipe_bound", False):
+        vp = C.c_void_p
+        lib.pgcm_pipe_create.argtypes = [vp, C.POINTER(_PipeConfig), _DELIVER_FN, vp, C.POINTER(vp)]
+        lib.pgcm_pipe_create.restype = C.c_int
+        lib.pgcm_pipe_destroy.argtypes = [vp]
+        lib.pgcm_pipe_destroy.restype = None
+        for name in ("pgcm_pipe_swap_out", "pgcm_pipe_notify_write", "pgcm_pipe_request"):
+            getattr(lib, name).argtypes = [vp, vp, C.c_uint64, vp]
+            getattr(lib, name).restype = C.c_int
+        lib.pgcm_pipe_sync.argtypes = [vp, vp]
+        lib.pgcm_pipe_sync.restype = C.c_int
+        lib.pgcm_pipe_get_stats.argtypes = [vp, C.POINTER(_PipeStats)]
+        lib.pgcm_pipe_get_stats.restype = C.c_int
+        lib._pipe_bound = True
+    return lib
+
+
+class Pipe:
+    """Owns a pgcm_pipe_t.  deliver(kind, addr, length, iv, ciphertext_address, tag_address,
+    stream_handle) is called once per transfer, in wire order; kind is "send", "now" or "nop"."""
+
+    def __init__(self, key: Key, iv0: bytes, deliver, depth=4, iv_start=0, leeway=0,
+                 history_limit=512, swap_threshold=128 * 1024, max_chunk_bytes=8 << 20):
+        self._h = None
+        self._key = key                      # keeps the key alive as long as the pipe
+
+        def _trampoline(_user, kind, addr, length, iv, ct, tag, stream):
+            deliver(SEQ_KINDS[kind], addr, length, iv, ct, tag, stream or 0)
+
+        self._cb = _DELIVER_FN(_trampoline)  # must outlive the pipe
+        cfg = _PipeConfig()
+        iv0 = bytes(iv0)
+        if len(iv0) != 12:
+            raise ValueError("iv0 is 12 bytes")
+        for i in range(12):
+            cfg.iv0[i] = iv0[i]
+        cfg.depth, cfg.iv_start, cfg.leeway = depth, iv_start, leeway
+        cfg.history_limit, cfg.swap_threshold = history_limit, swap_threshold
+        cfg.max_chunk_bytes = max_chunk_bytes
+        out = C.c_void_p()
+        _check(_pipe_lib().pgcm_pipe_create(key.handle, C.byref(cfg), self._cb, None,
+                                            C.byref(out)))
+        self._h = out.value
+
+    def swap_out(self, addr: int, length: int, stream=None):
+        _check(_pipe_lib().pgcm_pipe_swap_out(self._h, addr, length, _stream_handle(stream)))
+
+    def notify_write(self, addr: int, length: int, stream=None):
+        _check(_pipe_lib().pgcm_pipe_notify_write(self._h, addr, length, _stream_handle(stream)))
+
+    def request(self, addr: int, length: int, stream=None):
+        _check(_pipe_lib().pgcm_pipe_request(self._h, addr, length, _stream_handle(stream)))
+
+    def sync(self, stream=None):
+        _check(_pipe_lib().pgcm_pipe_sync(self._h, _stream_handle(stream)))
+
+    def stats(self) -> dict:
+        st = _PipeStats()
+        _check(_pipe_lib().pgcm_pipe_get_stats(self._h, C.byref(st)))
+        return {n: int(getattr(st, n)) for n, _ in _PipeStats._fields_}
+
+    def destroy(self):
+        if self._h is not None:
+            _pipe_lib().pgcm_pipe_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

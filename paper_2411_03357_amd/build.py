@@ -6,10 +6,11 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpgcm.so")
-SOURCES = ["pgcm_kernels.hip", "pgcm_host.hip", "pgcm_bounce.hip", "pgcm_seq.cpp"]
+SOURCES = ["pgcm_kernels.hip", "pgcm_host.hip", "pgcm_bounce.hip", "pgcm_pipe.hip", "pgcm_seq.cpp"]
 HEADERS = ["pgcm_kernels.h", "pgcm_types.h", os.path.join("..", "..", "include", "pgcm.h"),
            os.path.join("..", "..", "include", "pgcm_seq.h"),
-           os.path.join("..", "..", "include", "pgcm_bounce.h")]
+           os.path.join("..", "..", "include", "pgcm_bounce.h"),
+           os.path.join("..", "..", "include", "pgcm_pipe.h")]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",

@@ -29,6 +29,10 @@ def test_every_declared_symbol_is_exported():
     assert len(seq_names) == 9 and sorted(pgcm.SEQ_EXPORTS) == seq_names
     for n in seq_names:
         assert hasattr(lib, n), n
+    pipe_names = _declared("pgcm_pipe.h")
+    assert len(pipe_names) == 7 and sorted(pgcm.PIPE_EXPORTS) == pipe_names
+    for n in pipe_names:
+        assert hasattr(lib, n), n
     bounce_names = _declared("pgcm_bounce.h")
     assert len(bounce_names) == 6 and sorted(pgcm.BOUNCE_EXPORTS) == bounce_names
     for n in bounce_names:
@@ -58,6 +62,20 @@ def test_strerror_and_null_arguments_without_gpu():
     assert bl.pgcm_bounce_release(None, 0, None) == -1
     assert bl.pgcm_bounce_buffer_bytes(None) == 0 and bl.pgcm_bounce_count(None) == 0
     bl.pgcm_bounce_destroy(None)
+    # ... and so do the pipe's
+    from paper_2411_03357_amd.binding import _pipe_lib, _PipeConfig, _DELIVER_FN
+    pl = _pipe_lib()
+    cfg = _PipeConfig()
+    cfg.depth, cfg.history_limit, cfg.max_chunk_bytes = 4, 16, 1 << 20
+    cb = _DELIVER_FN(lambda *a: None)
+    assert pl.pgcm_pipe_create(None, ctypes.byref(cfg), cb, None, ctypes.byref(out)) == -1
+    assert pl.pgcm_pipe_create(None, None, cb, None, ctypes.byref(out)) == -1
+    assert pl.pgcm_pipe_request(None, None, 0, None) == -1
+    assert pl.pgcm_pipe_swap_out(None, None, 0, None) == -1
+    assert pl.pgcm_pipe_notify_write(None, None, 0, None) == -1
+    assert pl.pgcm_pipe_sync(None, None) == -1
+    assert pl.pgcm_pipe_get_stats(None, None) == -1
+    pl.pgcm_pipe_destroy(None)
 
 
 def _check_plan(lens, unit):

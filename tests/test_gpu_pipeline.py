@@ -147,3 +147,86 @@ def test_a_replayed_or_reordered_delivery_is_rejected():
     assert ok.tolist()[:5] == [1, 0, 0, 1, 0]
     assert all(v == 1 for v in ok.tolist()[5:])
     key.free()
+
+
+# ------------------------------------------------------------------------------------------
+# the same, driven by the library's own pipe object (include/pgcm_pipe.h) instead of Python
+
+class CountingReceiver:
+    """the peer: decrypts delivery k straight out of the sender's buffer under IV_0 + start + k,
+    on the stream the delivery was made on"""
+
+    def __init__(self, keyb, iv0, iv_start):
+        self.key = pgcm.expand_key(keyb)
+        self.iv0, self.next_iv = iv0, iv_start
+        self.got = []       # (kind, addr, length, iv, plaintext tensor, ok tensor)
+
+    def deliver(self, kind, addr, length, iv, ct, tag, stream):
+        ivb = torch.from_numpy(np.frombuffer(pgcm.seq_iv_bytes(self.iv0, self.next_iv),
+                                             np.uint8).copy()).cuda()
+        self.next_iv += 1
+        out = torch.empty(max(16, (length + 15) // 16 * 16), dtype=torch.uint8, device="cuda")
+        ok = torch.zeros(1, dtype=torch.uint8, device="cuda")
+        pgcm.decrypt_verify_batch(self.key, ivb, None, None, [ct], [length], [out.data_ptr()],
+                                  tag, ok, stream=stream)
+        self.got.append((kind, addr, length, iv, out[:length], ok, ivb))
+
+
+@pytest.mark.parametrize("kind,noise", [("repetitive", 0.3), ("fifo", 0.2), ("lifo", 0.0)])
+def test_pipe_object_drives_the_batch_calls(kind, noise):
+    ev = workloads.swap_trace(kind, seed=4, rounds=5, noise=noise)
+    rng = np.random.default_rng(101)
+    keyb = rng.integers(0, 256, 32, dtype=np.uint8)
+    iv0 = rng.integers(0, 256, 12, dtype=np.uint8).tobytes()
+    key = pgcm.expand_key(keyb)
+    mem = _memory_for(ev, 8)
+    longest = max(c[1] for c in mem)
+    rx = CountingReceiver(keyb, iv0, 17)
+    pipe = pgcm.Pipe(key, iv0, rx.deliver, depth=4, iv_start=17, leeway=1 if noise else 0,
+                     max_chunk_bytes=longest)
+    # the model runs beside it on the same events: same transfers, same order, same IVs
+    from oracle.sequencer_oracle import SequencerOracle
+    model = SequencerOracle(iv_start=17, depth=4, leeway=1 if noise else 0)
+    asked = []
+    for e in ev:
+        if e[0] == "out":
+            pipe.swap_out(mem[e[1]].data_ptr(), e[1][1])
+            model.swap_out((mem[e[1]].data_ptr(), e[1][1]))
+        elif e[0] == "req":
+            pipe.request(mem[e[1]].data_ptr(), e[1][1])
+            model.request((mem[e[1]].data_ptr(), e[1][1]))
+            asked.append(e[1])
+        else:
+            pipe.sync()
+            model.sync()
+    torch.cuda.synchronize()
+    by_addr = {t.data_ptr(): c for c, t in mem.items()}
+    wire_model = [a for a in model.log if a[0] in ("send", "now", "nop")]
+    assert len(rx.got) == len(wire_model)
+    for k, ((kd, addr, length, iv, plain, ok, _), m) in enumerate(zip(rx.got, wire_model)):
+        assert int(ok.item()) == 1, k
+        assert iv == 17 + k and kd == m[0]
+        if kd == "nop":
+            assert (addr, length) == (0, 1) and m[1] == iv
+        else:
+            assert (addr, length) == m[1] and m[2] == iv
+            assert torch.equal(plain, mem[by_addr[addr]])
+    assert sorted(by_addr[g[1]] for g in rx.got if g[0] != "nop") == sorted(asked)
+    st = pipe.stats()
+    assert st["transfers"] == len(rx.got) and st["nops"] == sum(1 for g in rx.got if g[0] == "nop")
+    assert st["ahead_bytes"] == sum(g[2] for g in rx.got if g[0] == "send")
+    assert st["critical_bytes"] == sum(g[2] for g in rx.got if g[0] == "now")
+    assert st["pre_bytes"] == sum(a[1][1] for a in model.log if a[0] == "pre")
+    assert st["dropped_bytes"] == sum(a[1][1] for a in model.log if a[0] == "drop")
+    if kind != "lifo":
+        assert st["ahead_bytes"] > st["critical_bytes"]
+    # argument checks
+    with pytest.raises(pgcm.PgcmError) as e:
+        pipe.request(mem[asked[0]].data_ptr(), longest + 1)
+    assert e.value.status == -3
+    with pytest.raises(pgcm.PgcmError) as e:
+        pipe.request(mem[asked[0]].data_ptr() + 4, 64)
+    assert e.value.status == -2
+    pipe.destroy()
+    rx.key.free()
+    key.free()
