@@ -64,6 +64,81 @@ def cpu_baseline(w, chunks, threads):
                       "batch shape, %.1f s" % (len(idx), sum(sub_lens), dt)}
 
 
+def pipeline_bench(args):
+    """--pipeline: what the speculative pipeline takes off the critical path.  Synthetic swap
+    traces (weight offloading, FIFO and LIFO KV swapping) are fed to the library's pipe object
+    twice: speculating, and with speculation off (every transfer encrypted when asked for).  For
+    every swap the GPU time between the call that put it on the wire and its ciphertext being
+    complete is measured with events on the launch stream.  Prints ONE JSON line."""
+    import numpy as np
+    import torch
+
+    import workloads
+    import paper_2411_03357_amd as pgcm
+
+    torch.cuda.set_device(0)
+    rng = np.random.default_rng(workloads.BASE_SEED + 500)
+    keyb = rng.integers(0, 256, 32, dtype=np.uint8)
+    iv0 = rng.integers(0, 256, 12, dtype=np.uint8).tobytes()
+    key = pgcm.expand_key(keyb)
+    threshold = 128 * 1024
+    out = {}
+    for kind in ("repetitive", "fifo", "lifo"):
+        ev = workloads.swap_trace(kind, seed=11, rounds=args.steps, noise=0.0)
+        chunks = sorted({e[1] for e in ev if e[0] in ("req", "out")})
+        g = torch.Generator(device="cuda")
+        g.manual_seed(12)
+        mem = {c: torch.randint(0, 256, (c[1],), dtype=torch.uint8, device="cuda", generator=g)
+               for c in chunks}
+        longest = max(c[1] for c in chunks)
+        res = {}
+        for mode in ("speculative", "on_demand"):
+            made = []            # (kind, length, event at the start of the call, event at delivery)
+            call_start = [None]
+
+            def deliver(k, addr, length, iv, ct, tag, stream):
+                done = torch.cuda.Event(enable_timing=True)
+                done.record()
+                made.append((k, length, call_start[0], done))
+
+            pipe = pgcm.Pipe(key, iv0, deliver, depth=4, max_chunk_bytes=longest,
+                             swap_threshold=threshold if mode == "speculative" else 1 << 62)
+            for rep in range(2):                         # the first pass warms up
+                made.clear()
+                for e in ev:
+                    call_start[0] = torch.cuda.Event(enable_timing=True)
+                    call_start[0].record()
+                    if e[0] == "out":
+                        pipe.swap_out(mem[e[1]].data_ptr(), e[1][1])
+                    elif e[0] == "req":
+                        pipe.request(mem[e[1]].data_ptr(), e[1][1])
+                    else:
+                        pipe.sync()
+                torch.cuda.synchronize()
+            swaps = [(k, ln, a.elapsed_time(b) * 1e3) for k, ln, a, b in made
+                     if k != "nop" and ln >= threshold]
+            st = pipe.stats()
+            res[mode] = {"swaps": len(swaps),
+                         "critical_us_per_swap": round(sum(t for _, _, t in swaps) / len(swaps), 2),
+                         "served_ahead": round(sum(1 for k, _, _ in swaps if k == "send") /
+                                               len(swaps), 3),
+                         "nops": sum(1 for k, _, _, _ in made if k == "nop"),
+                         "pre_bytes_dropped_share": round(
+                             st["dropped_bytes"] / st["pre_bytes"], 3) if st["pre_bytes"] else 0.0}
+            pipe.destroy()
+        out[kind] = res
+    key.free()
+    spec = sum(out[k]["speculative"]["critical_us_per_swap"] for k in out) / len(out)
+    base = sum(out[k]["on_demand"]["critical_us_per_swap"] for k in out) / len(out)
+    print(json.dumps({
+        "metric": "GPU time on the critical path per swap (call to ciphertext complete), us",
+        "value": round(spec, 2), "unit": "us", "higher_is_better": False, "n_gpus": 1,
+        "on_demand_value": round(base, 2), "data": "synthetic",
+        "config": {"workload": "swap traces: repetitive 2 MiB layers, FIFO and LIFO 320 KiB KV "
+                               "blocks, %d rounds each, depth 4" % args.steps},
+        "traces": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,11 +159,18 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of the payload buffer (a kernel of known "
                          "traffic to scale hardware byte counters by)")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="measure the speculative pipeline on swap traces instead (its own JSON "
+                         "line; --steps is the number of rounds per trace)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (chunks are independent; a multi-GPU "
               "run would just split the chunk list); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.pipeline:
+        pipeline_bench(args)
+        return
 
     import numpy as np
     import torch

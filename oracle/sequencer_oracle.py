@@ -41,6 +41,8 @@ class SequencerOracle:
     # ------------------------------------------------------------------ events
     def swap_out(self, chunk):
         """a chunk left the GPU and may come back later"""
+        if chunk[1] < self.threshold:
+            return                  # small transfers are never pipelined
         if chunk in self.out:
             self.out.remove(chunk)
         self.out.append(chunk)

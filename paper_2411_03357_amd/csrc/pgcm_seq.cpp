@@ -182,6 +182,8 @@ void pgcm_seq_destroy(pgcm_seq_t* seq) { delete seq; }
 int pgcm_seq_swap_out(pgcm_seq_t* s, uint64_t addr, uint64_t len) {
     if (s == nullptr) return PGCM_ERR_ARG;
     try {
+        // only swaps are pipelined: a chunk too short to be one is not tracked
+        if (len < s->threshold) return PGCM_OK;
         const Chunk c{addr, len};
         auto it = std::find(s->swapped_out.begin(), s->swapped_out.end(), c);
         if (it != s->swapped_out.end()) s->swapped_out.erase(it);

@@ -132,3 +132,20 @@ def test_iv_bytes_and_argument_checks():
         assert pgcm.seq_iv_bytes(iv0, n) == want
     with pytest.raises(pgcm.PgcmError):
         pgcm.Sequencer(depth=0)
+
+
+def test_swapped_out_chunks_below_the_swap_size_are_not_pipelined():
+    """only swaps are worth pre-encrypting (section 4.2): a short chunk that leaves the device is
+    not tracked, so nothing is encrypted ahead for it and its later request is served on the spot"""
+    for make in (lambda: SequencerOracle(iv_start=5, depth=4),
+                 lambda: pgcm.Sequencer(iv_start=5, depth=4)):
+        s = make()
+        s.swap_out((0x1000, 4096))
+        s.swap_out((0x9000, 100))
+        s.request((0x1000, 4096))
+        s.sync()
+        log = s.log if hasattr(s, "log") else s.take_actions()
+        assert [a[0] for a in log] == ["now"] and log[0][1:] == ((0x1000, 4096), 5)
+        s.swap_out((0x100000, 1 << 20))
+        log = s.log[1:] if hasattr(s, "log") else s.take_actions()
+        assert [a[0] for a in log] == ["pre"]
