@@ -108,3 +108,39 @@ def aes_ecb_block(key: bytes, block: bytes) -> bytes:
 
 
 aes256_ecb_block = aes_ecb_block
+
+
+class GcmEncryptStream:
+    """libcrypto's GCM encryption fed piece by piece (for messages too long to hold twice in host
+    memory): update(numpy uint8 array) -> ciphertext array of the same length; tag() at the end"""
+
+    def __init__(self, key: bytes, iv: bytes, aad: bytes = b""):
+        self._ctx = _lc.EVP_CIPHER_CTX_new()
+        _check(_lc.EVP_EncryptInit_ex(self._ctx, _cipher(key, "gcm"), None, None, None), "init")
+        _check(_lc.EVP_CIPHER_CTX_ctrl(self._ctx, _SET_IVLEN, len(iv), None), "ivlen")
+        _check(_lc.EVP_EncryptInit_ex(self._ctx, None, None, bytes(key), bytes(iv)), "key")
+        if len(aad):
+            _update(_lc.EVP_EncryptUpdate, self._ctx, None, bytes(aad))
+
+    def update(self, piece, out=None):
+        import numpy as np
+        assert piece.dtype == np.uint8 and piece.flags["C_CONTIGUOUS"]
+        if out is None:
+            out = np.empty(piece.size, np.uint8)
+        n = C.c_int(0)
+        for off in range(0, piece.size, _STEP):
+            m = min(_STEP, piece.size - off)
+            _check(_lc.EVP_EncryptUpdate(self._ctx, C.c_void_p(out.ctypes.data + off), C.byref(n),
+                                         C.c_void_p(piece.ctypes.data + off), m), "update")
+            assert n.value == m
+        return out[:piece.size]
+
+    def tag(self) -> bytes:
+        n = C.c_int(0)
+        fin = C.create_string_buffer(16)
+        _check(_lc.EVP_EncryptFinal_ex(self._ctx, fin, C.byref(n)), "final")
+        t = C.create_string_buffer(16)
+        _check(_lc.EVP_CIPHER_CTX_ctrl(self._ctx, _GET_TAG, 16, t), "get tag")
+        _lc.EVP_CIPHER_CTX_free(self._ctx)
+        self._ctx = None
+        return t.raw
