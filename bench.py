@@ -23,11 +23,11 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 3
 # `rocprofv3 --pmc` (summaries and commands: profiles/).  They describe the kernel sources whose
 # hash is given; once the sources change they no longer apply and bench.py reports null.
 COUNTERS = {
-    "sources_sha256": "8212582dd1f5a068dc82c6fef0b0c6767056b5d7b56cc2bff7f66c4b87b12c4e",
+    "sources_sha256": "5f8d063bf0837b758a8a76227b380844485398b8b605f0224ac4538abdb44432",
     "workload": "c2_opt13b_kv_4096x320KiB",
-    "fetch_size_kib": 657230.4,     # FETCH_SIZE per launch
-    "fetch_scale": 1310720.0 / 655381.9,   # a 1 310 720 KiB device copy reads 655 381.9
-    "write_size_kib": 1395322.3,    # WRITE_SIZE per launch
+    "fetch_size_kib": 657230.7,     # FETCH_SIZE per launch
+    "fetch_scale": 1310720.0 / 655382.4,   # a 1 310 720 KiB device copy reads 655 382
+    "write_size_kib": 1395322.2,    # WRITE_SIZE per launch
     "write_scale": 1310720.0 / 1310720.0,  # the same copy writes 1 310 720.0
     "valu_wave_instructions": 609253376.0,  # SQ_INSTS_VALU per launch
     "lds_wave_instructions": 321931264.0,   # SQ_INSTS_LDS per launch
@@ -41,6 +41,51 @@ def sources_sha256():
         with open(os.path.join(ROOT, "paper_2411_03357_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def libcrypto_rates(w, seconds=1.0):
+    """the host's libcrypto (AES-NI / carry-less multiply), one GCM invocation per 8 MiB: what a
+    CPU-side transport like the paper's gets per core and with every core, for context"""
+    import threading
+    import numpy as np
+    import openssl_ref
+    size = 8 << 20
+    key, iv = w.key.tobytes(), w.ivs[0].tobytes()
+
+    def worker(rates, k):
+        data = np.random.default_rng(6 + k).integers(0, 256, size, dtype=np.uint8)
+        out = np.empty(size, np.uint8)
+        n, t0 = 0, time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            st = openssl_ref.GcmEncryptStream(key, iv)
+            st.update(data, out)             # the foreign call runs without the interpreter lock
+            st.tag()
+            n += 1
+        rates[k] = n * size / (time.perf_counter() - t0) / 1e9
+
+    one = [0.0]
+    worker(one, 0)
+    threads = min(16, os.cpu_count() or 1)
+    rates = [0.0] * threads
+    ts = [threading.Thread(target=worker, args=(rates, k)) for k in range(threads)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    return {"kind": "libcrypto EVP aes-%d-gcm, encrypt, 8 MiB per invocation" % (8 * len(key)),
+            "single_thread_GBps": round(one[0], 2), "all_threads_GBps": round(sum(rates), 2),
+            "threads": threads}
 
 
 def cpu_baseline(w, chunks, threads):
@@ -59,7 +104,7 @@ def cpu_baseline(w, chunks, threads):
     assert bool((ok == 1).all())
     nbytes = 2 * sum(sub_lens)
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": int(max(used, used2)),
-            "kind": "oracle",
+            "kind": "oracle", "nproc": os.cpu_count(), "cpu_model": cpu_model(),
             "sample": "encrypt + decrypt-verify of the first %d chunks (%d B each way) of the same "
                       "batch shape, %.1f s" % (len(idx), sum(sub_lens), dt)}
 
@@ -238,6 +283,14 @@ def main():
     enc_ms = timed_calls(b.encrypt, reps)
     dec_ms = timed_calls(b.decrypt, reps)
 
+    # what a plain device copy of the same buffer reaches on this machine, in the same run: the
+    # achievable ceiling for a kernel that reads and writes every payload byte once
+    copy_ms = None
+    if not args.host_bounce:
+        copy_ms = timed_calls(lambda _key: b.back.copy_(b.plain), reps)
+        b.decrypt(key)                       # b.back holds the decrypted batch again
+        torch.cuda.synchronize()
+
     kern_avg_ms = sum(launches) / len(launches)
     # algorithmic HBM bytes of one launch: every payload byte read once and written once, plus
     # per chunk its IV (12), tag (16), AAD and descriptor (64); what the implementation moves on
@@ -292,10 +345,22 @@ def main():
                      "dec_launch_ms": round(sum(kern["dec"]) / len(kern["dec"]), 4)},
     }
     out["roofline_alu"] = alu
+    if copy_ms is not None:
+        copy_gbs = 2.0 * w.total_bytes / (copy_ms[len(copy_ms) // 2] * 1e-3) / 1e9
+        out["copy_ceiling"] = {"kind": "device-to-device copy of the payload buffer (HBM read + "
+                                       "write), median of %d" % reps,
+                               "traffic_GBps": round(copy_gbs, 1),
+                               "bulk_kernel_frac_of_copy": round(achieved / copy_gbs, 4)}
+    import hashlib
+    h = hashlib.sha256()
+    for arr in (w.key, w.ivs, w.lens, w.aad if w.aad is not None else np.zeros(0, np.uint8)):
+        h.update(np.ascontiguousarray(arr).tobytes())
+    out["inputs_sha256"] = h.hexdigest()    # key, IVs, lengths, AAD (the payload is seeded too)
     if not args.no_cpu_baseline:
         chunks = args.cpu_chunks or max(1, int(40e6 // max(1, int(w.lens.mean()))))
         threads = min(16, os.cpu_count() or 1)
         out["cpu_baseline"] = cpu_baseline(w, chunks, threads)
+        out["cpu_libcrypto"] = libcrypto_rates(w)
     key.free()
     print(json.dumps(out))
 
