@@ -818,27 +818,37 @@ __device__ __forceinline__ uint32_t row_shift_down(uint32_t v) {
 // The 64 lane sums of a chunk -> its GHASH state, in every lane.  Lane j's sum still lacks
 // H^(64 - j).  Tree: with s = 32, 16, .., 1 lane j takes Y_j * H^s + Y_(j+s) (DPP inside rows of
 // 16 lanes, LDS permutes across them); lane 0 ends with sum_j Y_j * H^(63 - j); then one more H.
+// When only the last 2^levels lanes hold anything (a chunk of at most 2^levels blocks; levels is
+// wave-uniform) the steps with s >= 2^levels are skipped and lane 64 - 2^levels has the sum.
 // tree_tables: LDS address of the nibble tables of H^(2^k), k = 0 .. 5, 8 KiB apart.
-__device__ __forceinline__ void fold_lanes(uint32_t tree_tables, uint32_t y[4]) {
+__device__ __forceinline__ void fold_lanes(uint32_t tree_tables, uint32_t y[4],
+                                           uint32_t levels = 6) {
     auto tree_step = [&](uint32_t k, uint32_t n0, uint32_t n1, uint32_t n2, uint32_t n3) {
         ghash_mul_lds(tree_tables + k * kLdsGhBytes, y);
         y[0] ^= n0, y[1] ^= n1, y[2] ^= n2, y[3] ^= n3;
     };
-    tree_step(5, __shfl_down(y[0], 32, 64), __shfl_down(y[1], 32, 64), __shfl_down(y[2], 32, 64),
-              __shfl_down(y[3], 32, 64));
-    tree_step(4, __shfl_down(y[0], 16, 64), __shfl_down(y[1], 16, 64), __shfl_down(y[2], 16, 64),
-              __shfl_down(y[3], 16, 64));
-    tree_step(3, row_shift_down<8>(y[0]), row_shift_down<8>(y[1]), row_shift_down<8>(y[2]),
-              row_shift_down<8>(y[3]));
-    tree_step(2, row_shift_down<4>(y[0]), row_shift_down<4>(y[1]), row_shift_down<4>(y[2]),
-              row_shift_down<4>(y[3]));
-    tree_step(1, row_shift_down<2>(y[0]), row_shift_down<2>(y[1]), row_shift_down<2>(y[2]),
-              row_shift_down<2>(y[3]));
-    tree_step(0, row_shift_down<1>(y[0]), row_shift_down<1>(y[1]), row_shift_down<1>(y[2]),
-              row_shift_down<1>(y[3]));
+    if (levels > 5)
+        tree_step(5, __shfl_down(y[0], 32, 64), __shfl_down(y[1], 32, 64),
+                  __shfl_down(y[2], 32, 64), __shfl_down(y[3], 32, 64));
+    if (levels > 4)
+        tree_step(4, __shfl_down(y[0], 16, 64), __shfl_down(y[1], 16, 64),
+                  __shfl_down(y[2], 16, 64), __shfl_down(y[3], 16, 64));
+    if (levels > 3)
+        tree_step(3, row_shift_down<8>(y[0]), row_shift_down<8>(y[1]), row_shift_down<8>(y[2]),
+                  row_shift_down<8>(y[3]));
+    if (levels > 2)
+        tree_step(2, row_shift_down<4>(y[0]), row_shift_down<4>(y[1]), row_shift_down<4>(y[2]),
+                  row_shift_down<4>(y[3]));
+    if (levels > 1)
+        tree_step(1, row_shift_down<2>(y[0]), row_shift_down<2>(y[1]), row_shift_down<2>(y[2]),
+                  row_shift_down<2>(y[3]));
+    if (levels > 0)
+        tree_step(0, row_shift_down<1>(y[0]), row_shift_down<1>(y[1]), row_shift_down<1>(y[2]),
+                  row_shift_down<1>(y[3]));
     ghash_mul_lds(tree_tables, y);
-    // only lane 0 holds the chunk's sum: hand it to every lane
-    for (int k = 0; k < 4; ++k) y[k] = __builtin_amdgcn_readfirstlane(y[k]);
+    // only one lane holds the chunk's sum: hand it to every lane
+    const uint32_t holder = 64u - (1u << levels);
+    for (int k = 0; k < 4; ++k) y[k] = __builtin_amdgcn_readlane(y[k], holder);
 }
 
 // From the GHASH state over A and C (the same in every lane) to the end of the invocation:
@@ -1047,14 +1057,40 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
     uint8_t* __restrict__ ok) {
     __shared__ uint32_t te[4][256];
     __shared__ Block tables[7][kNibbleTableEntries];  // H^(2^k), k = 0 .. 6
+    __shared__ uint32_t tables_needed;                // bit k: some chunk here uses tables[k]
     const uint32_t tid = threadIdx.x, lane = tid & 63;
-    for (uint32_t i = tid; i < 4 * 256; i += blockDim.x) te[i >> 8][i & 255] = kt->te[i >> 8][i & 255];
-    for (uint32_t k = 0; k < 7; ++k) copy_power_table(tables[k], kt, k, tid, blockDim.x);
-    __syncthreads();
-
     const uint32_t i = blockIdx.x * kSmallChunksPerGroup + (tid >> 6);
-    if (i >= nchunks) return;
-    const ChunkDesc cd = chunks_host[i];
+    const bool have_chunk = i < nchunks;
+    ChunkDesc cd{};
+    if (have_chunk) cd = chunks_host[i];
+
+    // rows of 64 blocks aligned to the chunk's end; "block -1" (counter block J0) rides along
+    const int64_t nblk = (int64_t)((cd.len + 15) / 16);
+    const uint32_t nrows = (uint32_t)((nblk + 1 + kRowBlocks - 1) / kRowBlocks);
+    // a chunk of one row may fill only its last few lanes: the lane tree then starts lower down
+    uint32_t levels = 6;
+    if (nrows == 1) {
+        levels = 0;
+        while ((1u << levels) < (uint32_t)nblk) ++levels;
+    }
+
+    // only the tables this workgroup's chunks use are brought into LDS: H always, H^(2^k) for
+    // the lane tree's levels, H^64 for chunks of more than one row (a 1-byte transfer needs H only)
+    if (tid == 0) tables_needed = 0;
+    __syncthreads();
+    if (lane == 0 && have_chunk) {
+        uint32_t mine = 1u;
+        if (nblk != 0) mine |= (1u << levels) - 1u;
+        if (nrows > 1) mine |= 1u << kRowPower;
+        atomicOr(&tables_needed, mine);
+    }
+    for (uint32_t t = tid; t < 4 * 256; t += blockDim.x) te[t >> 8][t & 255] = kt->te[t >> 8][t & 255];
+    __syncthreads();
+    const uint32_t needed = tables_needed;
+    for (uint32_t k = 0; k < 7; ++k)
+        if (needed & (1u << k)) copy_power_table(tables[k], kt, k, tid, blockDim.x);
+    __syncthreads();
+    if (!have_chunk) return;
     const uint32_t* __restrict__ rk = kt->rk;
 
     uint32_t y[4] = {0, 0, 0, 0};
@@ -1063,9 +1099,6 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
     const Block j = j0_from_iv(kt, ivs + (uint64_t)cd.index * iv_len, iv_len);
     const uint32_t ctr1 = bswap32(j.w[3]) + 1u;
 
-    // rows of 64 blocks aligned to the chunk's end; "block -1" (counter block J0) rides along
-    const int64_t nblk = (int64_t)((cd.len + 15) / 16);
-    const uint32_t nrows = (uint32_t)((nblk + 1 + kRowBlocks - 1) / kRowBlocks);
     int64_t blk = nblk - (int64_t)nrows * kRowBlocks + lane;
     uint32_t mask[4] = {0, 0, 0, 0};  // E_K(J0), valid in the lane that holds block -1
     for (uint32_t r = 0; r < nrows; ++r, blk += kRowBlocks) {
@@ -1120,7 +1153,7 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
         // nothing was hashed yet: the state is what the AAD left
         for (int w = 0; w < 4; ++w) y[w] = aad_y.w[w];
     } else {
-        fold_lanes(lds_offset(tables[0]), y);
+        fold_lanes(lds_offset(tables[0]), y, levels);
     }
     finish_chunk<kDecrypt>(lds_offset(tables[0]), y, mask, cd, tags, ok, lane);
 }
