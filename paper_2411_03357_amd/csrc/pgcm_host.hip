@@ -165,8 +165,20 @@ void launch_bulk(int rounds, dim3 grid, hipStream_t stream, Args... args) {
         hipLaunchKernelGGL((bulk_kernel<kDecrypt, 14>), grid, dim3(kGroupThreads), 0, stream, args...);
 }
 
+// wide: a workgroup of eight wavefronts per chunk; otherwise a wavefront per chunk
 template <bool kDecrypt, class... Args>
-void launch_small(int rounds, dim3 grid, hipStream_t stream, Args... args) {
+void launch_small(int rounds, bool wide, uint32_t nchunks, hipStream_t stream, Args... args) {
+    if (wide) {
+        const dim3 grid(nchunks), block(kSmallWideWaves * 64);
+        if (rounds == 10)
+            hipLaunchKernelGGL((small_wide_kernel<kDecrypt, 10>), grid, block, 0, stream, args...);
+        else if (rounds == 12)
+            hipLaunchKernelGGL((small_wide_kernel<kDecrypt, 12>), grid, block, 0, stream, args...);
+        else
+            hipLaunchKernelGGL((small_wide_kernel<kDecrypt, 14>), grid, block, 0, stream, args...);
+        return;
+    }
+    const dim3 grid((nchunks + kSmallChunksPerGroup - 1) / kSmallChunksPerGroup);
     const dim3 block(kSmallChunksPerGroup * 64);
     if (rounds == 10)
         hipLaunchKernelGGL((small_kernel<kDecrypt, 10>), grid, block, 0, stream, args...);
@@ -233,6 +245,7 @@ inline void describe_chunk(const BatchArgs& a, size_t i, ChunkDesc& d) {
 // Sizes of a batch's schedule; filled by plan_batch, which also validates every chunk.
 struct BatchPlan {
     bool all_small;       // every chunk fits the small-transfer path
+    bool all_one_row;     // ... and its one-wavefront-per-chunk kernel
     uint32_t unit_power;  // log2 of the blocks per unit
     uint32_t nunits;
     uint32_t nslots;      // partial sets: one per unit and one per fold output
@@ -243,7 +256,7 @@ struct BatchPlan {
 int plan_batch(const pgcm_key* key, const BatchArgs& a, BatchPlan* plan) {
     plan->unit_power =
         key->forced_unit_power ? key->forced_unit_power : choose_unit_power(a.n, a.order, a.len);
-    plan->all_small = true;
+    plan->all_small = plan->all_one_row = true;
     uint64_t nunits = 0, nslots = 0;
     uint64_t fold_items[kMaxLevels] = {0, 0, 0, 0};
     for (size_t k = 0; k < a.n; ++k) {
@@ -251,6 +264,7 @@ int plan_batch(const pgcm_key* key, const BatchArgs& a, BatchPlan* plan) {
         const int rc = check_chunk(a, i);
         if (rc != PGCM_OK) return rc;
         if (a.len[i] > kSmallChunkBytes) plan->all_small = false;
+        if (a.len[i] > kSmallRowBytes) plan->all_one_row = false;
         const uint32_t nu = plan_chunk(a.len[i], plan->unit_power).nunits;
         uint32_t outs[kMaxLevels];
         const uint32_t levels = fold_levels(nu, outs);
@@ -360,23 +374,22 @@ int record_timing_stop(pgcm_key* key, hipStream_t stream) {
 
 // Small-transfer path: one kernel, descriptors read straight from the pinned staging buffer, no
 // device workspace.
-int run_small_batch(pgcm_key* key, const BatchArgs& a) {
+int run_small_batch(pgcm_key* key, const BatchArgs& a, bool wide) {
     const uint32_t nchunks = (uint32_t)a.n;
     const int s = key->next_stage;
     int rc = ensure_stage(key, s, sizeof(ChunkDesc) * a.n);
     if (rc != PGCM_OK) return rc;
     ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(key->stage[s]);
     for (size_t k = 0; k < a.n; ++k) describe_chunk(a, a.at(k), h_desc[k]);
-    const dim3 grid((nchunks + kSmallChunksPerGroup - 1) / kSmallChunksPerGroup);
     const KeyTables* kt = key->tables;
     rc = record_timing_start(key, a.stream);
     if (rc != PGCM_OK) return rc;
     if (a.decrypt)
-        launch_small<true>(key->rounds, grid, a.stream, kt, (const ChunkDesc*)h_desc, nchunks,
-                           a.ivs, a.iv_len, a.tags, a.ok);
+        launch_small<true>(key->rounds, wide, nchunks, a.stream, kt, (const ChunkDesc*)h_desc,
+                           nchunks, a.ivs, a.iv_len, a.tags, a.ok);
     else
-        launch_small<false>(key->rounds, grid, a.stream, kt, (const ChunkDesc*)h_desc, nchunks,
-                            a.ivs, a.iv_len, a.tags, (uint8_t*)nullptr);
+        launch_small<false>(key->rounds, wide, nchunks, a.stream, kt, (const ChunkDesc*)h_desc,
+                            nchunks, a.ivs, a.iv_len, a.tags, (uint8_t*)nullptr);
     rc = record_timing_stop(key, a.stream);
     if (rc != PGCM_OK) return rc;
     PGCM_HIP(hipGetLastError());
@@ -398,7 +411,7 @@ int run_batch(pgcm_key* key, const BatchArgs& a) {
     int cur_device = -1;
     PGCM_HIP(hipGetDevice(&cur_device));
     if (cur_device != key->device) return PGCM_ERR_ARG;  // the key lives on another GPU
-    if (p.all_small) return run_small_batch(key, a);
+    if (p.all_small) return run_small_batch(key, a, !p.all_one_row);
 
     const uint32_t nchunks = (uint32_t)a.n;
     const WorkLayout w = lay_out(a, p);

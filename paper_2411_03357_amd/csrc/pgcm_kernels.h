@@ -33,9 +33,17 @@ __global__ void final_kernel(const KeyTables* kt, const ChunkDesc* chunks, uint3
 
 constexpr uint32_t kSmallChunksPerGroup = 4;
 
+// chunks of at most kSmallRowBytes each
 template <bool kDecrypt, int kRounds>
 __global__ void small_kernel(const KeyTables* kt, const ChunkDesc* chunks_host, uint32_t nchunks,
                              const uint8_t* ivs, uint32_t iv_len, uint8_t* tags, uint8_t* ok);
+
+// chunks of at most kSmallChunkBytes each, one workgroup per chunk
+constexpr uint32_t kSmallWideWaves = 8;
+template <bool kDecrypt, int kRounds>
+__global__ void small_wide_kernel(const KeyTables* kt, const ChunkDesc* chunks_host,
+                                  uint32_t nchunks, const uint8_t* ivs, uint32_t iv_len,
+                                  uint8_t* tags, uint8_t* ok);
 
 __global__ void upload_kernel(uint4* dst, const uint4* src_host, uint32_t n16);
 

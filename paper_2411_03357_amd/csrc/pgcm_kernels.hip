@@ -1012,10 +1012,11 @@ template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, 
 // ------------------------------------------------------------------------------------------
 // The small-transfer path: a batch whose chunks are all at most kSmallChunkBytes long (the
 // paper's "other I/O", usually < 8 KB, and the 1-byte NOPs of its error handler, sections 4.2 and
-// 5.3) is done by ONE kernel, one wavefront per chunk from the first block to the tag, reading
-// its descriptor straight from pinned host memory: what matters here is the latency of the
-// call, not bandwidth.  LDS: the four round tables once (lookups may collide; there are few),
-// nibble tables of H^1 .. H^64.
+// 5.3) is done by ONE kernel from the first block to the tag, reading its descriptors straight
+// from pinned host memory: what matters here is the latency of the call, not bandwidth.  Two
+// shapes: a wavefront per chunk when every chunk fits one row, a workgroup of eight wavefronts
+// per chunk otherwise.  LDS: the four round tables once (lookups may collide; there are few)
+// and the nibble tables the chunks at hand need.
 namespace {
 
 template <int kRounds>
@@ -1046,8 +1047,76 @@ __device__ __forceinline__ void aes_block_lds_plain(const uint32_t* __restrict__
     s[3] = last(a3, a0, a1, a2) ^ rk[4 * kRounds + 3];
 }
 
+// One row of a short chunk: block `blk` (may be -1 or lower: idle) in this lane.  Reads and writes
+// the payload, returns the lane's keystream block in s and what it contributes to the hash in c
+// (the ciphertext block, zero-padded; for block 0 with the AAD state folded in; zero when idle).
+template <bool kDecrypt, int kRounds>
+__device__ __forceinline__ void small_row(const uint32_t* __restrict__ rk,
+                                          const uint32_t (*te)[256], const ChunkDesc& cd,
+                                          const Block& j, uint32_t ctr1, int64_t blk,
+                                          const Block& aad_y, uint32_t s[4], uint32_t c[4]) {
+    const bool active = blk >= 0;
+    uint32_t tail = 0;
+    if (active && (uint64_t)blk * 16 + 16 > cd.len) tail = (uint32_t)(cd.len & 15);
+    const bool whole = active && tail == 0;
+    uint32_t x[4] = {0, 0, 0, 0};
+    const uint8_t* sp = cd.src + blk * 16;
+    uint8_t* dp = cd.dst + blk * 16;
+    if (whole) {
+        u32x4 v = global_read128(sp);
+        x[0] = v.x, x[1] = v.y, x[2] = v.z, x[3] = v.w;
+    }
+    if (tail) {
+#pragma unroll
+        for (uint32_t b = 0; b < 15; ++b)
+            if (b < tail) x[b / 4] |= (uint32_t)sp[b] << (8 * (b % 4));
+    }
+    s[0] = j.w[0], s[1] = j.w[1], s[2] = j.w[2], s[3] = bswap32((uint32_t)blk + ctr1);
+    aes_block_lds_plain<kRounds>(rk, te, s);
+    uint32_t o[4] = {x[0] ^ s[0], x[1] ^ s[1], x[2] ^ s[2], x[3] ^ s[3]};
+    if (whole) {
+        u32x4 v = {o[0], o[1], o[2], o[3]};
+        global_write128(dp, v);
+    }
+    if (tail) {
+#pragma unroll
+        for (uint32_t b = 0; b < 15; ++b)
+            if (b < tail) dp[b] = (uint8_t)(o[b / 4] >> (8 * (b % 4)));
+        // bytes past the end count as zero in the hash
+#pragma unroll
+        for (uint32_t b = 1; b < 16; ++b)
+            if (b >= tail) o[b / 4] &= ~(0xFFu << (8 * (b % 4)));
+    }
+    for (int w = 0; w < 4; ++w) c[w] = kDecrypt ? x[w] : o[w];
+    if (blk == 0)
+        for (int w = 0; w < 4; ++w) c[w] ^= aad_y.w[w];
+    if (!active)
+        for (int w = 0; w < 4; ++w) c[w] = 0;
+}
+
+// levels of the lane tree a chunk of nblk <= 64 blocks in one row needs
+__device__ __forceinline__ uint32_t lane_tree_levels(uint32_t nblk) {
+    uint32_t levels = 0;
+    while ((1u << levels) < nblk) ++levels;
+    return levels;
+}
+
+// brings the round tables and the nibble tables named in `needed` (bit k: H^(2^k)) into LDS;
+// every thread of the workgroup calls it
+template <int kTables>
+__device__ __forceinline__ void load_small_tables(uint32_t (*te)[256],
+                                                  Block (*tables)[kNibbleTableEntries],
+                                                  const KeyTables* __restrict__ kt,
+                                                  uint32_t needed, uint32_t tid) {
+    for (uint32_t t = tid; t < 4 * 256; t += blockDim.x) te[t >> 8][t & 255] = kt->te[t >> 8][t & 255];
+    for (uint32_t k = 0; k < (uint32_t)kTables; ++k)
+        if (needed & (1u << k)) copy_power_table(tables[k], kt, k, tid, blockDim.x);
+}
+
 }  // namespace
 
+// Chunks of at most one row including "block -1" (63 blocks, 1008 bytes: the NOPs and most of the
+// small traffic): one wavefront per chunk, several chunks a workgroup.
 // ivs: IVs of iv_len bytes each, a chunk's at its `index`; J0 of an IV that is not 96 bits long is
 // hashed here.
 template <bool kDecrypt, int kRounds>
@@ -1056,98 +1125,39 @@ __global__ __launch_bounds__(kSmallChunksPerGroup * 64) void small_kernel(
     const uint8_t* __restrict__ ivs, uint32_t iv_len, uint8_t* __restrict__ tags,
     uint8_t* __restrict__ ok) {
     __shared__ uint32_t te[4][256];
-    __shared__ Block tables[7][kNibbleTableEntries];  // H^(2^k), k = 0 .. 6
+    __shared__ Block tables[6][kNibbleTableEntries];  // H^(2^k), k = 0 .. 5
     __shared__ uint32_t tables_needed;                // bit k: some chunk here uses tables[k]
     const uint32_t tid = threadIdx.x, lane = tid & 63;
     const uint32_t i = blockIdx.x * kSmallChunksPerGroup + (tid >> 6);
     const bool have_chunk = i < nchunks;
     ChunkDesc cd{};
     if (have_chunk) cd = chunks_host[i];
-
-    // rows of 64 blocks aligned to the chunk's end; "block -1" (counter block J0) rides along
-    const int64_t nblk = (int64_t)((cd.len + 15) / 16);
-    const uint32_t nrows = (uint32_t)((nblk + 1 + kRowBlocks - 1) / kRowBlocks);
-    // a chunk of one row may fill only its last few lanes: the lane tree then starts lower down
-    uint32_t levels = 6;
-    if (nrows == 1) {
-        levels = 0;
-        while ((1u << levels) < (uint32_t)nblk) ++levels;
-    }
+    const uint32_t nblk = (uint32_t)((cd.len + 15) / 16);  // <= 63, the host saw to that
+    // the chunk fills only the last nblk lanes of its row: the lane tree starts lower down
+    const uint32_t levels = lane_tree_levels(nblk);
 
     // only the tables this workgroup's chunks use are brought into LDS: H always, H^(2^k) for
-    // the lane tree's levels, H^64 for chunks of more than one row (a 1-byte transfer needs H only)
+    // the lane tree's levels (a 1-byte transfer needs H only)
     if (tid == 0) tables_needed = 0;
     __syncthreads();
-    if (lane == 0 && have_chunk) {
-        uint32_t mine = 1u;
-        if (nblk != 0) mine |= (1u << levels) - 1u;
-        if (nrows > 1) mine |= 1u << kRowPower;
-        atomicOr(&tables_needed, mine);
-    }
-    for (uint32_t t = tid; t < 4 * 256; t += blockDim.x) te[t >> 8][t & 255] = kt->te[t >> 8][t & 255];
+    if (lane == 0 && have_chunk) atomicOr(&tables_needed, 1u | ((1u << levels) - 1u));
     __syncthreads();
-    const uint32_t needed = tables_needed;
-    for (uint32_t k = 0; k < 7; ++k)
-        if (needed & (1u << k)) copy_power_table(tables[k], kt, k, tid, blockDim.x);
+    load_small_tables<6>(te, tables, kt, tables_needed, tid);
     __syncthreads();
     if (!have_chunk) return;
     const uint32_t* __restrict__ rk = kt->rk;
 
-    uint32_t y[4] = {0, 0, 0, 0};
     Block aad_y{{0, 0, 0, 0}};
     if (cd.aad_len != 0) aad_y = aad_hash(kt, cd.aad, cd.aad_len);
     const Block j = j0_from_iv(kt, ivs + (uint64_t)cd.index * iv_len, iv_len);
     const uint32_t ctr1 = bswap32(j.w[3]) + 1u;
 
-    int64_t blk = nblk - (int64_t)nrows * kRowBlocks + lane;
-    uint32_t mask[4] = {0, 0, 0, 0};  // E_K(J0), valid in the lane that holds block -1
-    for (uint32_t r = 0; r < nrows; ++r, blk += kRowBlocks) {
-        const bool active = blk >= 0;
-        uint32_t tail = 0;
-        if (active && (uint64_t)blk * 16 + 16 > cd.len) tail = (uint32_t)(cd.len & 15);
-        const bool whole = active && tail == 0;
-        uint32_t x[4] = {0, 0, 0, 0};
-        const uint8_t* sp = cd.src + blk * 16;
-        uint8_t* dp = cd.dst + blk * 16;
-        if (whole) {
-            u32x4 v = global_read128(sp);
-            x[0] = v.x, x[1] = v.y, x[2] = v.z, x[3] = v.w;
-        }
-        if (tail) {
-#pragma unroll
-            for (uint32_t b = 0; b < 15; ++b)
-                if (b < tail) x[b / 4] |= (uint32_t)sp[b] << (8 * (b % 4));
-        }
-        uint32_t s[4] = {j.w[0], j.w[1], j.w[2], bswap32((uint32_t)blk + ctr1)};
-        aes_block_lds_plain<kRounds>(rk, te, s);
-        if (r > 0) ghash_mul_lds(lds_offset(tables[kRowPower]), y);
-        uint32_t o[4] = {x[0] ^ s[0], x[1] ^ s[1], x[2] ^ s[2], x[3] ^ s[3]};
-        if (whole) {
-            u32x4 v = {o[0], o[1], o[2], o[3]};
-            global_write128(dp, v);
-        }
-        if (tail) {
-#pragma unroll
-            for (uint32_t b = 0; b < 15; ++b)
-                if (b < tail) dp[b] = (uint8_t)(o[b / 4] >> (8 * (b % 4)));
-            // bytes past the end count as zero in the hash
-#pragma unroll
-            for (uint32_t b = 1; b < 16; ++b)
-                if (b >= tail) o[b / 4] &= ~(0xFFu << (8 * (b % 4)));
-        }
-        uint32_t c[4];
-        for (int w = 0; w < 4; ++w) c[w] = kDecrypt ? x[w] : o[w];
-        if (blk == 0)
-            for (int w = 0; w < 4; ++w) c[w] ^= aad_y.w[w];
-        if (blk == -1)
-            for (int w = 0; w < 4; ++w) mask[w] = s[w];
-        if (!active)
-            for (int w = 0; w < 4; ++w) c[w] = 0;
-        for (int w = 0; w < 4; ++w) y[w] ^= c[w];
-    }
-    // block -1 sits in the first row, in lane (rows * 64 - nblk - 1)
-    const int mask_lane = (int)((int64_t)nrows * kRowBlocks - nblk - 1);
-    for (int w = 0; w < 4; ++w) mask[w] = __shfl(mask[w], mask_lane, 64);
+    // the row is aligned to the chunk's end; "block -1" (counter block J0) rides along in the
+    // lane before block 0, and its keystream is E_K(J0)
+    const int64_t blk = (int64_t)nblk - kRowBlocks + lane;
+    uint32_t s[4], y[4], mask[4];
+    small_row<kDecrypt, kRounds>(rk, te, cd, j, ctr1, blk, aad_y, s, y);
+    for (int w = 0; w < 4; ++w) mask[w] = __shfl(s[w], (int)(kRowBlocks - nblk - 1), 64);
 
     if (nblk == 0) {
         // nothing was hashed yet: the state is what the AAD left
@@ -1168,6 +1178,87 @@ PGCM_INSTANTIATE_SMALL(true, 10);
 PGCM_INSTANTIATE_SMALL(true, 12);
 PGCM_INSTANTIATE_SMALL(true, 14);
 #undef PGCM_INSTANTIATE_SMALL
+
+// Chunks of up to eight rows (8 KiB): one workgroup of eight wavefronts per chunk, a row each, so
+// that the rows' cipher passes run side by side; the rows' lane sums are then folded across the
+// wavefronts as a tree through LDS (H^64, H^128, H^256), and wavefront 0 finishes the chunk.
+// Rows are aligned to the chunk's end and sit in the last wavefronts of the smallest power of two
+// that holds them; E_K(J0) is one more cipher pass in wavefront 0.
+template <bool kDecrypt, int kRounds>
+__global__ __launch_bounds__(kSmallWideWaves * 64) void small_wide_kernel(
+    const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks_host, uint32_t nchunks,
+    const uint8_t* __restrict__ ivs, uint32_t iv_len, uint8_t* __restrict__ tags,
+    uint8_t* __restrict__ ok) {
+    constexpr uint32_t kTables = kRowPower + 3;  // H^(2^k), k = 0 .. 8
+    static_assert(kSmallWideWaves == 8, "three tree levels over the wavefronts");
+    __shared__ uint32_t te[4][256];
+    __shared__ Block tables[kTables][kNibbleTableEntries];
+    __shared__ Block partial[kSmallWideWaves][64];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (blockIdx.x >= nchunks) return;  // uniform over the workgroup
+    const ChunkDesc cd = chunks_host[blockIdx.x];
+    const uint32_t nblk = (uint32_t)((cd.len + 15) / 16);          // <= 512
+    const uint32_t nrows = (nblk + kRowBlocks - 1) / kRowBlocks;   // 0 .. 8, without block -1
+    uint32_t wave_levels = 0;                                      // tree levels over wavefronts
+    while ((1u << wave_levels) < nrows) ++wave_levels;
+    const uint32_t lane_levels = nrows > 1 ? 6u : lane_tree_levels(nblk);
+
+    uint32_t needed = 1u | ((1u << lane_levels) - 1u);
+    needed |= ((1u << wave_levels) - 1u) << kRowPower;
+    load_small_tables<kTables>(te, tables, kt, needed, tid);
+    __syncthreads();
+    const uint32_t* __restrict__ rk = kt->rk;
+    const Block j = j0_from_iv(kt, ivs + (uint64_t)cd.index * iv_len, iv_len);
+    const uint32_t ctr1 = bswap32(j.w[3]) + 1u;
+
+    // wavefront w of the first 2^wave_levels takes row w - (2^wave_levels - nrows), if there is one
+    uint32_t y[4] = {0, 0, 0, 0};
+    const int row = (int)wave - (int)((1u << wave_levels) - nrows);
+    if (wave < (1u << wave_levels) && row >= 0) {
+        Block aad_y{{0, 0, 0, 0}};
+        if (row == 0 && cd.aad_len != 0) aad_y = aad_hash(kt, cd.aad, cd.aad_len);
+        const int64_t blk = (int64_t)nblk - (int64_t)(nrows - (uint32_t)row) * kRowBlocks + lane;
+        uint32_t s[4];
+        small_row<kDecrypt, kRounds>(rk, te, cd, j, ctr1, blk, aad_y, s, y);
+    }
+    uint32_t mask[4] = {j.w[0], j.w[1], j.w[2], j.w[3]};
+    if (wave == 0) aes_block_lds_plain<kRounds>(rk, te, mask);  // E_K(J0)
+
+    // every wavefront passes every barrier; only the shrinking front has work to do
+    for (uint32_t l = 0; l < wave_levels; ++l) {
+        partial[wave][lane] = Block{{y[0], y[1], y[2], y[3]}};
+        __syncthreads();
+        if (wave < ((1u << wave_levels) >> (l + 1))) {
+            const Block a = partial[2 * wave][lane], b = partial[2 * wave + 1][lane];
+            y[0] = a.w[0], y[1] = a.w[1], y[2] = a.w[2], y[3] = a.w[3];
+            ghash_mul_lds(lds_offset(tables[kRowPower + l]), y);
+            y[0] ^= b.w[0], y[1] ^= b.w[1], y[2] ^= b.w[2], y[3] ^= b.w[3];
+        }
+        __syncthreads();
+    }
+    if (wave != 0) return;
+
+    if (nblk == 0) {
+        // nothing was hashed: the state is what the AAD left
+        const Block a = aad_hash(kt, cd.aad, cd.aad_len);
+        y[0] = a.w[0], y[1] = a.w[1], y[2] = a.w[2], y[3] = a.w[3];
+    } else {
+        fold_lanes(lds_offset(tables[0]), y, lane_levels);
+    }
+    finish_chunk<kDecrypt>(lds_offset(tables[0]), y, mask, cd, tags, ok, lane);
+}
+
+#define PGCM_INSTANTIATE_SMALL_WIDE(D, R)                                                   \
+    template __global__ void small_wide_kernel<D, R>(const KeyTables*, const ChunkDesc*,       \
+                                                     uint32_t, const uint8_t*, uint32_t,       \
+                                                     uint8_t*, uint8_t*)
+PGCM_INSTANTIATE_SMALL_WIDE(false, 10);
+PGCM_INSTANTIATE_SMALL_WIDE(false, 12);
+PGCM_INSTANTIATE_SMALL_WIDE(false, 14);
+PGCM_INSTANTIATE_SMALL_WIDE(true, 10);
+PGCM_INSTANTIATE_SMALL_WIDE(true, 12);
+PGCM_INSTANTIATE_SMALL_WIDE(true, 14);
+#undef PGCM_INSTANTIATE_SMALL_WIDE
 
 // Brings a batch's descriptors from pinned host memory into the device workspace.  Done by a
 // kernel so that the batch stays on one hardware queue: a DMA copy between kernels costs two

@@ -74,9 +74,12 @@ struct alignas(16) FoldItem {
     uint32_t pad_;
 };
 
-// A batch whose chunks are all at most this long takes the small-transfer path: one kernel, one
-// wavefront per chunk (the paper's non-swap transfers are usually < 8 KB, section 4.2).
+// A batch whose chunks are all at most this long takes the small-transfer path: one kernel (the
+// paper's non-swap transfers are usually < 8 KB, section 4.2): eight rows of 64 blocks.
 constexpr uint64_t kSmallChunkBytes = 8192;
+// ... and when they are all at most this long (63 blocks: one row together with "block -1") the
+// kernel is the one with a wavefront per chunk
+constexpr uint64_t kSmallRowBytes = 1008;
 
 // Items of the dynamic schedule are grabbed from a counter; to find an item's chunk a wavefront
 // starts at coarse_map[item >> kCoarseShift] and walks unit_base[] forward.
