@@ -411,7 +411,8 @@ int run_batch(pgcm_key* key, const BatchArgs& a) {
     int cur_device = -1;
     PGCM_HIP(hipGetDevice(&cur_device));
     if (cur_device != key->device) return PGCM_ERR_ARG;  // the key lives on another GPU
-    if (p.all_small) return run_small_batch(key, a, !p.all_one_row);
+    if (p.all_one_row) return run_small_batch(key, a, false);
+    if (p.all_small && a.n <= kSmallWideMaxChunks) return run_small_batch(key, a, true);
 
     const uint32_t nchunks = (uint32_t)a.n;
     const WorkLayout w = lay_out(a, p);

@@ -1,5 +1,6 @@
 // Structures shared by the host side of the library and its kernels.
 #pragma once
+#include <stddef.h>
 #include <stdint.h>
 
 namespace pgcm {
@@ -80,6 +81,10 @@ constexpr uint64_t kSmallChunkBytes = 8192;
 // ... and when they are all at most this long (63 blocks: one row together with "block -1") the
 // kernel is the one with a wavefront per chunk
 constexpr uint64_t kSmallRowBytes = 1008;
+// The kernel with a workgroup per chunk is there for the latency of a few transfers; a batch of
+// more chunks than this (two rounds of resident workgroups; measured crossover) longer than one
+// row goes through the unit schedule instead, which gets more chunks per second out of the chip.
+constexpr size_t kSmallWideMaxChunks = 512;
 
 // Items of the dynamic schedule are grabbed from a counter; to find an item's chunk a wavefront
 // starts at coarse_map[item >> kCoarseShift] and walks unit_base[] forward.

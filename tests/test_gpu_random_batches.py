@@ -100,3 +100,46 @@ def test_random_batches_against_libcrypto(first_seed):
         bad = np.flatnonzero(back != expect)
         assert bad.size == 0, "%s: plaintext byte %d" % (what, bad[0])
         key.free()
+
+
+def test_many_short_chunks():
+    """more short multi-row chunks than the workgroup-per-chunk kernel is used for: the batch goes
+    through the unit schedule, most chunks being a single short unit; and as many one-row chunks,
+    which stay on the wavefront-per-chunk kernel"""
+    for hi, seed in ((8192, 1), (1008, 2)):
+        rng = np.random.default_rng([workloads.BASE_SEED, 777, seed])
+        n = 700
+        lens = rng.integers(0, hi + 1, n).astype(np.uint64)
+        lens[:4] = [hi, 0, 1, hi - 1]
+        alens = rng.integers(0, 30, n)
+        offsets, total = workloads._layout(lens)
+        aad_off = np.zeros(n + 1, np.uint64)
+        aad_off[1:] = np.cumsum(alens)
+        w = workloads.Workload("many_short_%d" % hi, 950 + seed,
+                               rng.integers(0, 256, 32, dtype=np.uint8),
+                               workloads.iv_sequence(int(rng.integers(1, 1 << 62)), n), lens,
+                               offsets, total, "u8",
+                               rng.integers(0, 256, int(alens.sum()), dtype=np.uint8), aad_off)
+        host = w.payload_host()
+        key = expand(w)
+        b = DeviceBatch(w, torch.from_numpy(host).cuda())
+        b.encrypt(key)
+        bad_chunk = 123
+        torch.cuda.synchronize()
+        cipher = b.cipher.cpu().numpy()
+        tags = b.tags.cpu().numpy().reshape(-1, 16)
+        kb = w.key.tobytes()
+        for i in range(n):
+            ct, tag = openssl_ref.encrypt(kb, w.ivs[i].tobytes(), w.aad_of(i),
+                                          w.chunk(host, i).tobytes())
+            assert w.chunk(cipher, i).tobytes() == ct and tags[i].tobytes() == tag, (hi, i)
+        b.tags[16 * bad_chunk + 3] ^= 0x40
+        b.decrypt(key)
+        torch.cuda.synchronize()
+        ok = b.ok.cpu().numpy()
+        assert [int(i) for i in np.flatnonzero(ok == 0)] == [bad_chunk]
+        back = b.back.cpu().numpy()
+        for i in range(n):
+            expect = np.zeros(int(lens[i]), np.uint8) if i == bad_chunk else w.chunk(host, i)
+            assert np.array_equal(w.chunk(back, i), expect), (hi, i)
+        key.free()
