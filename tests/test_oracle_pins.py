@@ -54,7 +54,7 @@ def test_sbox_against_log_tables_and_printed_entries():
 
 def test_block_cipher_and_key_schedule_worked_examples():
     seen = set()
-    for rec in _records("aes256_block_vectors.txt"):
+    for rec in _records("aes_block_vectors.txt"):
         key = _hex(rec[1])
         seen.add((rec[0], len(key)))
         if rec[0] == "block":
