@@ -185,6 +185,18 @@ uint32_t pgcm_unit_bytes(void);
 uint32_t pgcm_batch_unit_bytes(size_t n, const uint64_t *len);
 
 /*
+ * Test aid: copies the key object's device tables to out (HOST), synchronising the device: 60
+ * round-key words (little-endian loads of the FIPS-197 bytes; unused ones zero), the round count
+ * and three zero words, the four round tables te[r][x] (256 words each), H (16 bytes), then for
+ * k = 0 .. 30 the nibble table of H^(2^k): entry [2 * byte + (0: high, 1: low nibble)][value] =
+ * (that nibble at that byte of an otherwise zero block) * H^(2^k), 16 bytes each.
+ * pgcm_key_tables_bytes() is the size of it all; a smaller `bytes` copies a prefix.
+ * The copy holds key material: wipe it after use.
+ */
+size_t pgcm_key_tables_bytes(void);
+int pgcm_copy_key_tables(pgcm_key_t *key, void *out, size_t bytes);
+
+/*
  * Tuning and test aid: fixes the unit size of every later batch under this key to unit_bytes
  * (a power of two from 1024 to pgcm_unit_bytes()), or returns to the per-batch choice with 0.
  * Anything else is PGCM_ERR_ARG.  With a forced small unit a chunk of more than 32^5 units is

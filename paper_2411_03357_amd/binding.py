@@ -12,7 +12,8 @@ EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_en
            "pgcm_decrypt_verify_batch", "pgcm_encrypt_batch_iv", "pgcm_decrypt_verify_batch_iv",
            "pgcm_encrypt_batch_keys", "pgcm_decrypt_verify_batch_keys",
            "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_units", "pgcm_unit_bytes",
-           "pgcm_batch_unit_bytes", "pgcm_set_unit_bytes",
+           "pgcm_batch_unit_bytes", "pgcm_set_unit_bytes", "pgcm_key_tables_bytes",
+           "pgcm_copy_key_tables",
            "pgcm_set_timing", "pgcm_last_bulk_kernel_ms", "pgcm_bulk_kernel_ms_history")
 
 
@@ -69,6 +70,10 @@ def load_library():
     lib.pgcm_unit_bytes.restype = C.c_uint32
     lib.pgcm_batch_unit_bytes.argtypes = [sz, vp]
     lib.pgcm_batch_unit_bytes.restype = C.c_uint32
+    lib.pgcm_key_tables_bytes.argtypes = []
+    lib.pgcm_key_tables_bytes.restype = sz
+    lib.pgcm_copy_key_tables.argtypes = [vp, vp, sz]
+    lib.pgcm_copy_key_tables.restype = C.c_int
     lib.pgcm_set_unit_bytes.argtypes = [vp, C.c_uint32]
     lib.pgcm_set_unit_bytes.restype = C.c_int
     lib.pgcm_set_timing.argtypes = [vp, C.c_int]
@@ -264,6 +269,21 @@ def plan_units(length):
     if total < 0:
         raise PgcmError(int(total))
     out["total"] = int(total)
+    return out
+
+
+def copy_key_tables(key: Key) -> dict:
+    """pgcm_copy_key_tables, taken apart: rk (60 uint32), rounds, te (4, 256) uint32, h (16 uint8),
+    ghash (31, 512, 16) uint8"""
+    n = int(load_library().pgcm_key_tables_bytes())
+    raw = np.zeros(n, np.uint8)
+    _check(load_library().pgcm_copy_key_tables(key.handle, raw.ctypes.data, n))
+    words = raw[:256].view(np.uint32)
+    out = {"rk": words[:60].copy(), "rounds": int(words[60]),
+           "te": raw[256:256 + 4096].view(np.uint32).reshape(4, 256).copy(),
+           "h": raw[4352:4368].copy(),
+           "ghash": raw[4368:].reshape(-1, 512, 16).copy()}
+    raw[:] = 0
     return out
 
 

@@ -708,6 +708,17 @@ uint32_t pgcm_batch_unit_bytes(size_t n, const uint64_t* len) {
     return 16u << choose_unit_power(n, nullptr, len);
 }
 
+size_t pgcm_key_tables_bytes(void) { return sizeof(KeyTables); }
+
+int pgcm_copy_key_tables(pgcm_key_t* key, void* out, size_t bytes) {
+    if (key == nullptr || key->tables == nullptr || (out == nullptr && bytes != 0))
+        return PGCM_ERR_ARG;
+    if (bytes > sizeof(KeyTables)) bytes = sizeof(KeyTables);
+    PGCM_HIP(hipDeviceSynchronize());
+    if (bytes != 0) PGCM_HIP(hipMemcpy(out, key->tables, bytes, hipMemcpyDeviceToHost));
+    return PGCM_OK;
+}
+
 int pgcm_set_unit_bytes(pgcm_key_t* key, uint32_t unit_bytes) {
     if (key == nullptr) return PGCM_ERR_ARG;
     if (unit_bytes == 0) {
