@@ -88,6 +88,31 @@ int pgcm_pipe_sync(pgcm_pipe_t *pipe, void *hip_stream);
 /* Counters since creation.  out: HOST. */
 int pgcm_pipe_get_stats(const pgcm_pipe_t *pipe, pgcm_pipe_stats *out);
 
+/*
+ * The other end: a peer that only counts.  It accepts transfer k under IV_0 + k and nothing else
+ * (paper section 4.1), so a replayed, dropped or re-ordered delivery fails authentication.
+ * Used with one thread and one stream, like the pipe.
+ */
+typedef struct pgcm_recv pgcm_recv_t;
+
+/* key as for the pipe; iv0: 12 bytes, HOST; iv_start: number of the first transfer expected. */
+int pgcm_recv_create(pgcm_key_t *key, const uint8_t iv0[12], uint64_t iv_start, pgcm_recv_t **out);
+void pgcm_recv_destroy(pgcm_recv_t *recv);
+
+/*
+ * Decrypts and verifies the next transfer (pgcm_decrypt_verify_batch with n = 1 under the next
+ * IV) and counts it, whatever the verdict turns out to be.
+ *   ciphertext DEVICE, 16-byte aligned, len bytes (may be pinned host memory: a bounce buffer);
+ *   tag        DEVICE, 16 bytes;   dst  DEVICE, 16-byte aligned, receives len bytes;
+ *   ok         DEVICE, 1 byte: 1 authentic, 0 rejected (dst then holds zeros).
+ * A NOP is accepted like any transfer (len 1); the caller discards its byte.
+ */
+int pgcm_recv_accept(pgcm_recv_t *recv, const void *ciphertext, uint64_t len, const uint8_t *tag,
+                     void *dst, uint8_t *ok, void *hip_stream);
+
+/* Number of the next transfer expected. */
+uint64_t pgcm_recv_next_iv(const pgcm_recv_t *recv);
+
 #ifdef __cplusplus
 }
 #endif

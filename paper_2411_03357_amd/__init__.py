@@ -8,4 +8,4 @@ from .binding import (PgcmError, Key, expand_key, expand_key_bytes, encrypt_batc
                       encrypt_batch_keys, decrypt_verify_batch_keys,
                       plan_units, unit_bytes, batch_unit_bytes, library_path, load_library, set_timing, set_unit_bytes, copy_key_tables,
                       last_bulk_kernel_ms, bulk_kernel_ms_history, EXPORTS, Sequencer, seq_iv_bytes, SEQ_EXPORTS, BouncePool,
-                      BOUNCE_EXPORTS, Pipe, PIPE_EXPORTS)
+                      BOUNCE_EXPORTS, Pipe, Receiver, PIPE_EXPORTS)

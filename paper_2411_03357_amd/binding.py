@@ -491,7 +491,8 @@ class BouncePool:
 # include/pgcm_pipe.h: the pipeline driver
 PIPE_EXPORTS = ("pgcm_pipe_create", "pgcm_pipe_destroy", "pgcm_pipe_swap_out",
                 "pgcm_pipe_notify_write", "pgcm_pipe_request", "pgcm_pipe_sync",
-                "pgcm_pipe_get_stats")
+                "pgcm_pipe_get_stats", "pgcm_recv_create", "pgcm_recv_destroy", "pgcm_recv_accept",
+                "pgcm_recv_next_iv")
 
 
 class _PipeConfig(C.Structure):
@@ -524,6 +525,14 @@ def _pipe_lib():
         lib.pgcm_pipe_sync.restype = C.c_int
         lib.pgcm_pipe_get_stats.argtypes = [vp, C.POINTER(_PipeStats)]
         lib.pgcm_pipe_get_stats.restype = C.c_int
+        lib.pgcm_recv_create.argtypes = [vp, vp, C.c_uint64, C.POINTER(vp)]
+        lib.pgcm_recv_create.restype = C.c_int
+        lib.pgcm_recv_destroy.argtypes = [vp]
+        lib.pgcm_recv_destroy.restype = None
+        lib.pgcm_recv_accept.argtypes = [vp, vp, C.c_uint64, vp, vp, vp, vp]
+        lib.pgcm_recv_accept.restype = C.c_int
+        lib.pgcm_recv_next_iv.argtypes = [vp]
+        lib.pgcm_recv_next_iv.restype = C.c_uint64
         lib._pipe_bound = True
     return lib
 
@@ -575,6 +584,41 @@ class Pipe:
     def destroy(self):
         if self._h is not None:
             _pipe_lib().pgcm_pipe_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class Receiver:
+    """Owns a pgcm_recv_t: the peer that accepts transfer k under IV_0 + k only."""
+
+    def __init__(self, key: Key, iv0: bytes, iv_start=0):
+        self._h = None
+        self._key = key
+        iv0 = bytes(iv0)
+        if len(iv0) != 12:
+            raise ValueError("iv0 is 12 bytes")
+        buf = (C.c_uint8 * 12)(*iv0)
+        out = C.c_void_p()
+        _check(_pipe_lib().pgcm_recv_create(key.handle, buf, iv_start, C.byref(out)))
+        self._h = out.value
+
+    def accept(self, ciphertext, length, tag, dst, ok, stream=None):
+        """ciphertext, tag: device addresses (or CUDA tensors); dst, ok: CUDA tensors"""
+        _check(_pipe_lib().pgcm_recv_accept(self._h, _dev_ptr(ciphertext), length, _dev_ptr(tag),
+                                            _dev_ptr(dst), _dev_ptr(ok), _stream_handle(stream)))
+
+    @property
+    def next_iv(self) -> int:
+        return int(_pipe_lib().pgcm_recv_next_iv(self._h))
+
+    def destroy(self):
+        if self._h is not None:
+            _pipe_lib().pgcm_recv_destroy(self._h)
             self._h = None
 
     def __del__(self):

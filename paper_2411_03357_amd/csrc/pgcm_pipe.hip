@@ -49,6 +49,14 @@ struct pgcm_pipe {
     uint8_t* nop_tag() const { return tag_mem + 16 * (slots.size() + 1); }
 };
 
+struct pgcm_recv {
+    pgcm_key_t* key = nullptr;
+    uint8_t iv0[12] = {};
+    uint64_t next_iv = 0;
+    uint8_t* iv_ring = nullptr;  // pinned host memory, as in the pipe
+    uint32_t iv_pos = 0;
+};
+
 namespace {
 
 // n consecutive ring entries holding IV_0 + iv[k]; returns the device-visible address of the first
@@ -279,6 +287,56 @@ int pgcm_pipe_get_stats(const pgcm_pipe_t* p, pgcm_pipe_stats* out) {
     *out = p->stats;
     return PGCM_OK;
 }
+
+int pgcm_recv_create(pgcm_key_t* key, const uint8_t iv0[12], uint64_t iv_start,
+                     pgcm_recv_t** out) {
+    if (out == nullptr) return PGCM_ERR_ARG;
+    *out = nullptr;
+    if (key == nullptr || iv0 == nullptr) return PGCM_ERR_ARG;
+    pgcm_recv* r = new (std::nothrow) pgcm_recv();
+    if (r == nullptr) return PGCM_ERR_NOMEM;
+    r->key = key;
+    memcpy(r->iv0, iv0, 12);
+    r->next_iv = iv_start;
+    if (hipHostMalloc((void**)&r->iv_ring, 16 * (size_t)kIvRing, hipHostMallocDefault) !=
+        hipSuccess) {
+        (void)hipGetLastError();
+        delete r;
+        return PGCM_ERR_NOMEM;
+    }
+    *out = r;
+    return PGCM_OK;
+}
+
+void pgcm_recv_destroy(pgcm_recv_t* r) {
+    if (r == nullptr) return;
+    (void)hipDeviceSynchronize();
+    if (r->iv_ring) (void)hipHostFree(r->iv_ring);
+    delete r;
+}
+
+int pgcm_recv_accept(pgcm_recv_t* r, const void* ciphertext, uint64_t len, const uint8_t* tag,
+                     void* dst, uint8_t* ok, void* hip_stream) {
+    if (r == nullptr) return PGCM_ERR_ARG;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (r->iv_pos == kIvRing) {
+        if (hipStreamSynchronize(stream) != hipSuccess) return PGCM_ERR_HIP;
+        r->iv_pos = 0;
+    }
+    uint8_t* iv = r->iv_ring + 16 * (size_t)r->iv_pos;
+    pgcm_seq_iv_bytes(r->iv0, r->next_iv, iv);
+    const void* srcs[1] = {ciphertext};
+    void* dsts[1] = {dst};
+    const uint64_t lens[1] = {len};
+    const int rc = pgcm_decrypt_verify_batch(r->key, 1, iv, nullptr, nullptr, srcs, lens, dsts,
+                                             tag, ok, stream);
+    if (rc != PGCM_OK) return rc;  // nothing was enqueued: the transfer does not count
+    ++r->iv_pos;
+    ++r->next_iv;
+    return PGCM_OK;
+}
+
+uint64_t pgcm_recv_next_iv(const pgcm_recv_t* r) { return r ? r->next_iv : 0; }
 
 #pragma GCC visibility pop
 }  // extern "C"

@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
     for n in seq_names:
         assert hasattr(lib, n), n
     pipe_names = _declared("pgcm_pipe.h")
-    assert len(pipe_names) == 7 and sorted(pgcm.PIPE_EXPORTS) == pipe_names
+    assert len(pipe_names) == 11 and sorted(pgcm.PIPE_EXPORTS) == pipe_names
     for n in pipe_names:
         assert hasattr(lib, n), n
     bounce_names = _declared("pgcm_bounce.h")
@@ -76,6 +76,10 @@ def test_strerror_and_null_arguments_without_gpu():
     assert pl.pgcm_pipe_sync(None, None) == -1
     assert pl.pgcm_pipe_get_stats(None, None) == -1
     pl.pgcm_pipe_destroy(None)
+    assert pl.pgcm_recv_create(None, None, 0, ctypes.byref(out)) == -1
+    assert pl.pgcm_recv_accept(None, None, 0, None, None, None, None) == -1
+    assert pl.pgcm_recv_next_iv(None) == 0
+    pl.pgcm_recv_destroy(None)
 
 
 def _check_plan(lens, unit):

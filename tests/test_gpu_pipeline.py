@@ -158,18 +158,15 @@ class CountingReceiver:
 
     def __init__(self, keyb, iv0, iv_start):
         self.key = pgcm.expand_key(keyb)
-        self.iv0, self.next_iv = iv0, iv_start
+        self.rx = pgcm.Receiver(self.key, iv0, iv_start)      # the library's counting peer
         self.got = []       # (kind, addr, length, iv, plaintext tensor, ok tensor)
 
     def deliver(self, kind, addr, length, iv, ct, tag, stream):
-        ivb = torch.from_numpy(np.frombuffer(pgcm.seq_iv_bytes(self.iv0, self.next_iv),
-                                             np.uint8).copy()).cuda()
-        self.next_iv += 1
+        assert self.rx.next_iv == iv
         out = torch.empty(max(16, (length + 15) // 16 * 16), dtype=torch.uint8, device="cuda")
         ok = torch.zeros(1, dtype=torch.uint8, device="cuda")
-        pgcm.decrypt_verify_batch(self.key, ivb, None, None, [ct], [length], [out.data_ptr()],
-                                  tag, ok, stream=stream)
-        self.got.append((kind, addr, length, iv, out[:length], ok, ivb))
+        self.rx.accept(ct, length, tag, out, ok, stream=stream)
+        self.got.append((kind, addr, length, iv, out[:length], ok, None))
 
 
 @pytest.mark.parametrize("kind,noise", [("repetitive", 0.3), ("fifo", 0.2), ("lifo", 0.0)])
@@ -227,6 +224,17 @@ def test_pipe_object_drives_the_batch_calls(kind, noise):
     with pytest.raises(pgcm.PgcmError) as e:
         pipe.request(mem[asked[0]].data_ptr() + 4, 64)
     assert e.value.status == -2
+    # a delivery offered twice: the second copy meets the next IV and is rejected
+    kd, addr, length, iv, plain, ok, _ = rx.got[-1]
+    stale = torch.zeros(1, dtype=torch.uint8, device="cuda")
+    dup = torch.empty(max(16, (length + 15) // 16 * 16), dtype=torch.uint8, device="cuda")
+    src = torch.zeros_like(dup)
+    src[:length] = plain            # not even ciphertext: any bytes are refused under a new IV
+    rx.rx.accept(src, length, torch.zeros(16, dtype=torch.uint8, device="cuda"), dup, stale)
+    torch.cuda.synchronize()
+    assert int(stale.item()) == 0 and int(dup[:length].max().item() if length else 0) == 0
+    assert rx.rx.next_iv == 17 + len(rx.got) + 1
     pipe.destroy()
+    rx.rx.destroy()
     rx.key.free()
     key.free()
