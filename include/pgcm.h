@@ -159,8 +159,9 @@ int pgcm_last_hip_error(void);
 /*
  * Host-only view of the chunk-to-wavefront schedule (section 5.1: requests arrive as batches of
  * copies of differing sizes).  Every chunk is cut into units of pgcm_batch_unit_bytes(n, len)
- * bytes counted back from its end, so only a chunk's first unit can be short; wavefronts take
- * units one at a time from a shared counter.  Every unit leaves 64 partial hash sums; a chunk's sums are folded
+ * bytes counted back from its end, so only a chunk's first unit can be short; every wavefront
+ * starts with a unit of its own and, when there are more units than wavefronts, takes further
+ * ones from a shared counter.  Every unit leaves 64 partial hash sums; a chunk's sums are folded
  * 32 units at a time, level by level, until at most 32 remain for the chunk's final step.
  * Fills, for chunk i: nunits[i] (0 for an empty chunk), first_blocks[i] (16-byte blocks in its
  * first unit), unit_base[i] (index of its first unit among all units of the batch),
@@ -171,7 +172,7 @@ int pgcm_last_hip_error(void);
 int64_t pgcm_plan_units(size_t n, const uint64_t *len, uint32_t *nunits, uint32_t *first_blocks,
                         uint32_t *unit_base, uint32_t *final_count, uint32_t *final_power);
 
-/* Bytes per full unit (a multiple of the 1 KiB a wavefront handles per step). */
+/* Bytes per unit of the dynamic schedule (a multiple of the 1 KiB a wavefront handles per step). */
 uint32_t pgcm_unit_bytes(void);
 
 /*
@@ -179,8 +180,8 @@ uint32_t pgcm_unit_bytes(void);
  * smallest power of two from 1 KiB to pgcm_unit_bytes() with which the batch has at most 4096
  * units (the chip's wavefront slots: every unit then has a wavefront of its own at once, so a
  * batch of a few swap-sized chunks spreads over the whole chip), and pgcm_unit_bytes() when none
- * has (wavefronts then take units in turn).  0 when len is NULL and n is not 0.  Batches that take the small-transfer path
- * (every chunk at most 8 KiB) are not cut into units at all.
+ * has (wavefronts then take further units in turn).  0 when len is NULL and n is not 0.  Batches
+ * that take the small-transfer path (every chunk at most 8 KiB) are not cut into units at all.
  */
 uint32_t pgcm_batch_unit_bytes(size_t n, const uint64_t *len);
 
@@ -198,9 +199,10 @@ int pgcm_copy_key_tables(pgcm_key_t *key, void *out, size_t bytes);
 
 /*
  * Tuning and test aid: fixes the unit size of every later batch under this key to unit_bytes
- * (a power of two from 1024 to pgcm_unit_bytes()), or returns to the per-batch choice with 0.
- * Anything else is PGCM_ERR_ARG.  With a forced small unit a chunk of more than 32^5 units is
- * refused with PGCM_ERR_LEN by the batch calls.
+ * (a power of two from 1 KiB to 16 MiB), or returns to the per-batch choice with 0.
+ * Anything else is PGCM_ERR_ARG.  A chunk that a forced unit cannot serve (more than 32^5 units
+ * of it; or more than 32 GiB with units of 32 KiB or 1 MiB, where the last fold would need a
+ * power of H the key object has no table for) is refused with PGCM_ERR_LEN by the batch calls.
  */
 int pgcm_set_unit_bytes(pgcm_key_t *key, uint32_t unit_bytes);
 

@@ -50,9 +50,26 @@ inline UnitPlan plan_chunk(uint64_t len, uint32_t unit_power) {
     return p;
 }
 
+// Partial sets of a chunk are folded kFan at a time until at most kFan remain for the final
+// step.  Returns the number of fold levels and, per level, the number of sets it produces.
+// More than kMaxLevels levels (only possible when a small unit is forced on a huge chunk) is
+// reported as kMaxLevels + 1 with nothing written past the array.
+inline uint32_t fold_levels(uint32_t nunits, uint32_t out_counts[kMaxLevels]) {
+    uint32_t levels = 0, c = nunits;
+    while (c > kFan) {
+        if (levels == kMaxLevels) return kMaxLevels + 1;
+        c = (c + kFan - 1) / kFan;
+        out_counts[levels++] = c;
+    }
+    return levels;
+}
+
 // Unit size of a batch: the smallest, from one row up, with which the batch has at most
-// kWaveSlots units, so that every unit gets a wavefront of its own at once; the full unit when
-// even that leaves more.  `order` as for run_batch.
+// kWaveSlots units, so that every unit gets a wavefront of its own at once; kUnitPower and the
+// dynamic schedule when even that leaves more.  (Larger units that would again give every
+// wavefront exactly one unit, e.g. a whole 320 KiB block each for 4096 of them, can be forced but
+// are never chosen: wavefronts do not all run at the same speed, and a launch that cannot hand
+// the slow ones less work ends when its slowest wavefront does.)  `order` as for run_batch.
 inline uint32_t choose_unit_power(size_t n, const uint32_t* order, const uint64_t* len) {
     constexpr uint32_t kChoices = kUnitPower - kMinUnitPower + 1;
     uint64_t units[kChoices] = {};
@@ -69,20 +86,6 @@ inline uint32_t choose_unit_power(size_t n, const uint32_t* order, const uint64_
     for (uint32_t c = 0; c < kChoices; ++c)
         if (units[c] <= kWaveSlots) return kMinUnitPower + c;
     return kUnitPower;
-}
-
-// Partial sets of a chunk are folded kFan at a time until at most kFan remain for the final
-// step.  Returns the number of fold levels and, per level, the number of sets it produces.
-// More than kMaxLevels levels (only possible when a small unit is forced on a huge chunk) is
-// reported as kMaxLevels + 1 with nothing written past the array.
-inline uint32_t fold_levels(uint32_t nunits, uint32_t out_counts[kMaxLevels]) {
-    uint32_t levels = 0, c = nunits;
-    while (c > kFan) {
-        if (levels == kMaxLevels) return kMaxLevels + 1;
-        c = (c + kFan - 1) / kFan;
-        out_counts[levels++] = c;
-    }
-    return levels;
 }
 
 }  // namespace
@@ -268,7 +271,10 @@ int plan_batch(const pgcm_key* key, const BatchArgs& a, BatchPlan* plan) {
         const uint32_t nu = plan_chunk(a.len[i], plan->unit_power).nunits;
         uint32_t outs[kMaxLevels];
         const uint32_t levels = fold_levels(nu, outs);
-        if (levels > kMaxLevels) return PGCM_ERR_LEN;  // a forced small unit on a huge chunk
+        // a forced unit the chunk cannot be cut into: too many fold levels, or sets of the last
+        // step further apart than the largest power of H with a table
+        if (levels > kMaxLevels || plan->unit_power + kFanPower * levels >= kNumPowers)
+            return PGCM_ERR_LEN;
         nunits += nu;
         nslots += nu;
         for (uint32_t l = 0; l < levels; ++l) {
@@ -725,7 +731,7 @@ int pgcm_set_unit_bytes(pgcm_key_t* key, uint32_t unit_bytes) {
         key->forced_unit_power = 0;
         return PGCM_OK;
     }
-    for (uint32_t u = kMinUnitPower; u <= kUnitPower; ++u)
+    for (uint32_t u = kMinUnitPower; u <= kMaxUnitPower; ++u)
         if (unit_bytes == (16u << u)) {
             key->forced_unit_power = u;
             return PGCM_OK;

@@ -8,12 +8,15 @@ namespace pgcm {
 // A wavefront handles 64 consecutive 16-byte blocks (one 1 KiB "row") per step, one block per
 // lane.  A unit is the piece of a chunk one wavefront walks in one go, and the granule of the
 // dynamic schedule; units are counted back from the chunk's end, so only a chunk's first unit
-// can be short.  A unit is 2^unit_power blocks, one to sixteen rows: sixteen for batches that fill
-// the chip; for smaller batches the smallest size that still gives every unit a wavefront of
-// its own, so that the batch spreads over as many wavefronts as there are and no unit waits.
+// can be short.  A unit is 2^unit_power blocks.  Batches that do not fill the chip get the
+// smallest size, from one row up, that still gives every unit a wavefront of its own, so that the
+// batch spreads over as many wavefronts as there are and no unit waits.  Batches that do fill it
+// get sixteen rows, handed out dynamically.  Larger units (up to 2^kMaxUnitPower blocks) can be
+// forced for measurements.
 constexpr uint32_t kRowBlocks = 64;
 constexpr uint32_t kRowPower = 6;      // H^64: one row further along a lane's stripe
-constexpr uint32_t kUnitPower = 10;    // the full unit: 1024 blocks = 16 KiB
+constexpr uint32_t kUnitPower = 10;    // the unit of the dynamic schedule: 1024 blocks = 16 KiB
+constexpr uint32_t kMaxUnitPower = 20; // the largest unit that can be forced: 2^20 blocks = 16 MiB
 constexpr uint32_t kMinUnitPower = kRowPower;
 constexpr uint32_t kUnitBlocks = 1u << kUnitPower;
 constexpr uint32_t kUnitBytes = kUnitBlocks * 16;
@@ -30,6 +33,8 @@ static_assert((1u << kRowPower) == kRowBlocks, "row power");
 constexpr uint32_t kFanPower = 5;
 constexpr uint32_t kFan = 1u << kFanPower;
 constexpr uint32_t kMaxLevels = 4;     // 2^22 units (the GCM length limit) / 32^4 <= 32
+// The sets a fold level or the final step works on lie 2^(unit_power + 5 * level) blocks apart;
+// that exponent must name one of the tables below.
 
 // GHASH tables hold, for one constant C = H^(2^k), the products of C with every value of every
 // nibble position of a block: entry [2 * byte + (0: high nibble, 1: low nibble)][value], 16 bytes

@@ -35,11 +35,13 @@ def _levels(nunits):
     return levels
 
 
-@pytest.mark.parametrize("forced_unit", [None, 16384, 1024])
-def test_fold_levels_against_the_oracle(forced_unit):
+@pytest.mark.parametrize("forced_unit,levels", [(None, 2), (16384, 2), (1024, 2), (32768, 1),
+                                                (512 * 1024, 1), (16 << 20, 0)])
+def test_fold_levels_against_the_oracle(forced_unit, levels):
     """a 16 MiB chunk: two fold levels with 16 KiB units (1025 sets -> 33, the first group short,
     -> 2), with the 8 KiB units a batch of this size gets by itself (2049 -> 65 -> 3) and with
-    1 KiB units (16385 -> 513 -> 17)"""
+    1 KiB units (16385 -> 513 -> 17); one with 32 KiB units (513 -> 17) and 512 KiB units
+    (33 -> 2, the first group a single short unit); none with 16 MiB units (2 sets)"""
     unit = pgcm.unit_bytes()
     big = 1024 * unit + 3 * 16 + 5
     w = _workload([big, 33 * unit + 1, 40], 0, 20)
@@ -52,7 +54,7 @@ def test_fold_levels_against_the_oracle(forced_unit):
         assert int(plan["nunits"][i]) == nunits
         assert int(plan["final_power"][i]) == up + 5 * _levels(nunits)
     use = forced_unit or auto
-    assert _levels(-(-big // use)) == 2
+    assert _levels(-(-big // use)) == levels
     key = pgcm.expand_key(w.key)
     if forced_unit:
         pgcm.set_unit_bytes(key, forced_unit)
@@ -76,6 +78,43 @@ def test_fold_levels_against_the_oracle(forced_unit):
     assert b.ok.cpu().tolist() == [0, 1, 1]
     assert int(b.chunk_host(b.back, 0).max()) == 0
     assert np.array_equal(b.chunk_host(b.back, 1), srcs[1])
+    key.free()
+
+
+def test_one_forced_large_unit_per_wavefront_against_libcrypto():
+    """4096 equal chunks of 20 KiB + 5 B are 8192 units of 16 KiB; with 32 KiB units forced
+    every chunk is one short unit, every wavefront takes exactly one and nothing is handed out.
+    Every chunk against libcrypto, a few against the oracle."""
+    n, ln = 4096, 20 * 1024 + 5
+    w = _workload([ln] * n, 2, 9)
+    assert pgcm.batch_unit_bytes(w.lens) == 16384 and pgcm.plan_units(w.lens)["total"] == 2 * n
+    key = pgcm.expand_key(w.key)
+    pgcm.set_unit_bytes(key, 32768)
+    b = DeviceBatch(w, w.payload_device())
+    b.encrypt(key)
+    b.decrypt(key)
+    torch.cuda.synchronize()
+    assert bool((b.ok == 1).all()) and torch.equal(b.back, b.plain)
+    got = b.tags.cpu().numpy().reshape(-1, 16)
+    kb = w.key.tobytes()
+    for i in range(n):
+        c, t = openssl_ref.encrypt(kb, w.ivs[i].tobytes(), w.aad_of(i),
+                                   b.chunk_host(b.plain, i).tobytes())
+        assert got[i].tobytes() == t, i
+        assert b.chunk_host(b.cipher, i).tobytes() == c, i
+    for i in (0, 1, 2047, n - 1):
+        c, t = oracle.encrypt(w.key, w.ivs[i], np.frombuffer(w.aad_of(i), np.uint8),
+                              b.chunk_host(b.plain, i))
+        assert got[i].tobytes() == t and b.chunk_host(b.cipher, i).tobytes() == c, i
+    # one flipped bit: that chunk alone is rejected and wiped
+    bad = b.cipher.clone()
+    bad[int(w.offsets[77]) + ln - 1] ^= 1
+    b.decrypt(key, src=bad)
+    torch.cuda.synchronize()
+    ok = b.ok.cpu().numpy()
+    assert int(ok[77]) == 0 and int(ok.sum()) == n - 1
+    assert int(b.chunk_host(b.back, 77).max()) == 0
+    assert np.array_equal(b.chunk_host(b.back, 78), b.chunk_host(b.plain, 78))
     key.free()
 
 

@@ -111,6 +111,41 @@ def _run(length, seed, aad_len):
     return plain, cipher
 
 
+def _same_with_one_unit_per_wavefront(plain, cipher, length):
+    """the chunk once more in 4096 forced units of 16 MiB, a wavefront each (4096 sets -> 128
+    -> 4, again 2^30 blocks apart): same tag (which covers every ciphertext byte) and the same
+    bytes where sampled as with the 2^22 units of 16 KiB taken from the counter, which _run has
+    compared with libcrypto"""
+    rng = np.random.default_rng(workloads.BASE_SEED + 99)
+    key = pgcm.expand_key(rng.integers(0, 256, 32, dtype=np.uint8))
+    ivs = torch.from_numpy(rng.integers(0, 256, 12, dtype=np.uint8)).cuda()
+    lens = np.array([length], np.uint64)
+    span = 1 << 22
+    spots = [0, span + 16, length // 2 - 5, length - span]
+    got = []
+    for unit in (0, 16 << 20):
+        pgcm.set_unit_bytes(key, unit)
+        tags = torch.zeros(16, dtype=torch.uint8, device="cuda")
+        pgcm.encrypt_batch(key, ivs, None, None, [plain.data_ptr()], lens, [cipher.data_ptr()],
+                           tags)
+        torch.cuda.synchronize()
+        got.append((tags.cpu(), [cipher[o:o + span].clone() for o in spots]))
+    assert torch.equal(got[0][0], got[1][0])
+    for a, b in zip(got[0][1], got[1][1]):
+        assert torch.equal(a, b)
+    # ... and what the large units wrote decrypts and verifies under the chosen unit
+    pgcm.set_unit_bytes(key, 0)
+    ok = torch.zeros(1, dtype=torch.uint8, device="cuda")
+    pgcm.decrypt_verify_batch(key, ivs, None, None, [cipher.data_ptr()], lens,
+                              [cipher.data_ptr()], got[1][0].cuda(), ok)
+    torch.cuda.synchronize()
+    assert int(ok.item()) == 1
+    for off in range(0, length, 8 * PIECE):
+        n = min(8 * PIECE, length - off)
+        assert torch.equal(cipher[off:off + n], plain[off:off + n]), off
+    key.free()
+
+
 def test_chunk_that_crosses_4_gib():
     plan = pgcm.plan_units([5 * GIB + 16 * 7 + 3])
     assert int(plan["nunits"][0]) == 327681 and int(plan["final_power"][0]) == 25
@@ -124,6 +159,7 @@ def test_chunk_of_the_maximum_length():
     assert int(plan["nunits"][0]) == 1 << 22 and int(plan["final_power"][0]) == 30
     assert int(plan["final_count"][0]) == 4
     plain, cipher = _run(length, 32, 0)
+    _same_with_one_unit_per_wavefront(plain, cipher, length)
     key = pgcm.expand_key(np.zeros(32, np.uint8))
     ivs = torch.zeros(12, dtype=torch.uint8, device="cuda")
     tags = torch.zeros(16, dtype=torch.uint8, device="cuda")

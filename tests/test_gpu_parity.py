@@ -95,7 +95,8 @@ def test_ragged_edge_cases_full_parity():
                           (0, 0, 0, "tag")])
 
 
-@pytest.mark.parametrize("unit_bytes", [1024, 2048, 4096, 8192, 16384])
+@pytest.mark.parametrize("unit_bytes", [1024, 2048, 4096, 8192, 16384, 32768, 128 * 1024,
+                                        16 << 20])
 def test_every_unit_size_full_parity(unit_bytes):
     """small batches get small units by themselves; here every unit size is forced on the
     edge-case batch and on a ragged mixed-size batch, so that unit boundaries, short first units
@@ -106,7 +107,7 @@ def test_every_unit_size_full_parity(unit_bytes):
                  unit_bytes=unit_bytes)
     _full_parity(workloads.mini(4), unit_bytes=unit_bytes)
     key = pgcm.expand_key(w.key)
-    for bad in (1, 512, 1000, 3000, 32768, 1 << 20):
+    for bad in (1, 512, 1000, 3000, 3 << 14, 1 << 25):
         with pytest.raises(pgcm.PgcmError) as e:
             pgcm.set_unit_bytes(key, bad)
         assert e.value.status == -1
