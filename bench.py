@@ -23,11 +23,11 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 3
 # `rocprofv3 --pmc` (summaries and commands: profiles/).  They describe the kernel sources whose
 # hash is given; once the sources change they no longer apply and bench.py reports null.
 COUNTERS = {
-    "sources_sha256": "6bdd5886032a72e8b94d91e779a706f2482a5833926fd8a6db4a8367c19fd797",
+    "sources_sha256": "98f09bea33180d15dea32221b5c3876723c37a38a4b0f1b8d0fe0c48d5c9deec",
     "workload": "c2_opt13b_kv_4096x320KiB",
-    "fetch_size_kib": 657184.4,     # FETCH_SIZE per launch
-    "fetch_scale": 1310720.0 / 655382.8,   # a 1 310 720 KiB device copy reads 655 383
-    "write_size_kib": 1395322.9,    # WRITE_SIZE per launch
+    "fetch_size_kib": 657232.3,     # FETCH_SIZE per launch
+    "fetch_scale": 1310720.0 / 655383.0,   # a 1 310 720 KiB device copy reads 655 383
+    "write_size_kib": 1395322.0,    # WRITE_SIZE per launch
     "write_scale": 1310720.0 / 1310720.0,  # the same copy writes 1 310 720.0
     "valu_wave_instructions": 609253376.0,  # SQ_INSTS_VALU per launch
     "lds_wave_instructions": 321931264.0,   # SQ_INSTS_LDS per launch

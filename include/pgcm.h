@@ -27,6 +27,9 @@
  *     a chunk is not an error (see pgcm_decrypt_verify_batch).
  *   - IV uniqueness per key is the caller's duty (the paper's transport uses a counter); it is
  *     not checked.
+ *   - The batch calls plan on the host, and they allocate (and wait for the stream) whenever a
+ *     batch needs more descriptor or workspace memory than any batch before it under the same
+ *     key: they are not meant to be recorded into a HIP graph.
  */
 #ifndef PGCM_H
 #define PGCM_H

@@ -147,6 +147,7 @@ int ensure_work(pgcm_key* k, size_t bytes, hipStream_t stream) {
         k->work = nullptr;
         k->work_cap = 0;
     }
+    k->counter_at = nullptr;  // new memory holds anything, even if it lands at the old address
     size_t cap = bytes + bytes / 2 + 65536;
     void* p = nullptr;
     if (hip_failed(hipMalloc(&p, cap))) return PGCM_ERR_NOMEM;
@@ -428,13 +429,21 @@ int run_batch(pgcm_key* key, const BatchArgs& a) {
     rc = ensure_work(key, w.bytes, a.stream);
     if (rc != PGCM_OK) return rc;
     fill_schedule(a, p, w, key->stage[s]);
+    uint32_t* d_counter = reinterpret_cast<uint32_t*>(key->work + w.counter);
     {
+        // the unit counter is left at zero by the last kernel of every batch; it only needs
+        // clearing when the workspace is new, the counter's place in it has moved, or an earlier
+        // batch was cut short
+        const bool clear = key->counter_at != d_counter || key->counter_dirty;
+        key->counter_at = d_counter;
+        key->counter_dirty = true;
         const uint32_t n16 = (uint32_t)(w.upload_bytes / 16);
         uint32_t groups = (n16 + 255) / 256;
         if (groups > 1024) groups = 1024;
         hipLaunchKernelGGL(upload_kernel, dim3(groups), dim3(256), 0, a.stream,
                            reinterpret_cast<uint4*>(key->work),
-                           reinterpret_cast<const uint4*>(key->stage[s]), n16);
+                           reinterpret_cast<const uint4*>(key->stage[s]), n16,
+                           clear ? d_counter : (uint32_t*)nullptr);
     }
     PGCM_HIP(hipEventRecord(key->stage_done[s], a.stream));
     key->stage_used[s] = true;
@@ -445,7 +454,6 @@ int run_batch(pgcm_key* key, const BatchArgs& a) {
     const uint32_t* d_ubase = reinterpret_cast<const uint32_t*>(key->work + w.ubase);
     const uint32_t* d_coarse = reinterpret_cast<const uint32_t*>(key->work + w.coarse);
     const FoldItem* d_fold = reinterpret_cast<const FoldItem*>(key->work + w.fold);
-    uint32_t* d_counter = reinterpret_cast<uint32_t*>(key->work + w.counter);
     Block* d_ekj0 = reinterpret_cast<Block*>(key->work + w.ekj0);
     Block* d_sets = reinterpret_cast<Block*>(key->work + w.sets);
     Block* d_j0 = a.iv_len == 12 ? nullptr : reinterpret_cast<Block*>(key->work + w.j0);
@@ -453,13 +461,6 @@ int run_batch(pgcm_key* key, const BatchArgs& a) {
         hipLaunchKernelGGL(j0_kernel, dim3((nchunks + 63) / 64), dim3(64), 0, a.stream, kt, d_desc,
                            a.ivs, a.iv_len, nchunks, d_j0);
 
-    // the unit counter is left at zero by the last kernel of every batch; it only needs clearing
-    // when the workspace is new (or has moved) or an earlier batch was cut short
-    if (key->counter_at != d_counter || key->counter_dirty) {
-        PGCM_HIP(hipMemsetAsync(d_counter, 0, sizeof(uint32_t), a.stream));
-        key->counter_at = d_counter;
-    }
-    key->counter_dirty = true;
 
     if (p.nunits > 0) {
         uint32_t groups = (p.nunits + kWavesPerGroup - 1) / kWavesPerGroup;

@@ -45,6 +45,6 @@ __global__ void small_wide_kernel(const KeyTables* kt, const ChunkDesc* chunks_h
                                   uint32_t nchunks, const uint8_t* ivs, uint32_t iv_len,
                                   uint8_t* tags, uint8_t* ok);
 
-__global__ void upload_kernel(uint4* dst, const uint4* src_host, uint32_t n16);
+__global__ void upload_kernel(uint4* dst, const uint4* src_host, uint32_t n16, uint32_t* clear);
 
 }  // namespace pgcm

@@ -1262,10 +1262,13 @@ PGCM_INSTANTIATE_SMALL_WIDE(true, 14);
 
 // Brings a batch's descriptors from pinned host memory into the device workspace.  Done by a
 // kernel so that the batch stays on one hardware queue: a DMA copy between kernels costs two
-// cross-queue hand-overs.
+// cross-queue hand-overs.  `clear`, when not null, is a word to set to zero as well (the unit
+// counter of a new workspace: a fill by a kernel, not a memset node, so that the stream's work
+// stays of one kind).
 __global__ __launch_bounds__(256) void upload_kernel(uint4* __restrict__ dst,
                                                      const uint4* __restrict__ src_host,
-                                                     uint32_t n16) {
+                                                     uint32_t n16, uint32_t* __restrict__ clear) {
+    if (clear != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *clear = 0;
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += gridDim.x * blockDim.x)
         dst[i] = src_host[i];
 }
