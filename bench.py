@@ -18,6 +18,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit op per lane-clock
+LDS_PEAK_GCYCLES = 256 * 2.4               # 256 CUs, one LDS pipe each, 2.4 GHz: port cycles per ns
 
 # Hardware counters of one bulk_kernel launch on the default workload, taken with
 # `rocprofv3 --pmc` (summaries and commands: profiles/).  They describe the kernel sources whose
@@ -31,6 +32,7 @@ COUNTERS = {
     "write_scale": 1310720.0 / 1310720.0,  # the same copy writes 1 310 720.0
     "valu_wave_instructions": 609253376.0,  # SQ_INSTS_VALU per launch
     "lds_wave_instructions": 321931264.0,   # SQ_INSTS_LDS per launch
+    "lds_active_cycles": 728154112.0,   # SQ_LDS_IDX_ACTIVE per launch, summed over the 256 CUs
 }
 
 
@@ -300,6 +302,7 @@ def main():
     achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
     traffic = None
     alu = None
+    lds = None
     if (COUNTERS["workload"] == w.name and COUNTERS["sources_sha256"] == sources_sha256()
             and not args.host_bounce and args.unit_bytes == 0):
         traffic = int(1024 * (COUNTERS["fetch_size_kib"] * COUNTERS["fetch_scale"] +
@@ -310,6 +313,13 @@ def main():
                "unit": "T 32-bit lane-ops/s", "frac": round(alu_achieved / VALU_PEAK_TOPS, 4),
                "valu_ops_per_payload_byte": round(lane_ops / payload, 2),
                "lds_lookups_per_payload_byte": round(COUNTERS["lds_wave_instructions"] * 64 / payload, 2)}
+        # the resource that binds: cycles in which a CU's LDS pipe is serving lookups (a 64-lane
+        # ds_read_b32 holds it for 2 cycles, a ds_read_b128 for 4), against one pipe per CU at
+        # the nominal clock
+        lds_achieved = COUNTERS["lds_active_cycles"] / (kern_avg_ms * 1e-3) / 1e9
+        lds = {"bound": "lds", "achieved": round(lds_achieved, 1), "peak": round(LDS_PEAK_GCYCLES, 1),
+               "unit": "G LDS-pipe cycles/s", "frac": round(lds_achieved / LDS_PEAK_GCYCLES, 4),
+               "lds_cycles_per_payload_byte": round(COUNTERS["lds_active_cycles"] / payload, 4)}
 
     out = {
         "metric": "AES-%d-GCM enc / dec+verify GB/s on 1 MI355X; %% of HBM roofline"
@@ -345,6 +355,7 @@ def main():
                      "dec_launch_ms": round(sum(kern["dec"]) / len(kern["dec"]), 4)},
     }
     out["roofline_alu"] = alu
+    out["roofline_lds"] = lds
     if copy_ms is not None:
         copy_gbs = 2.0 * w.total_bytes / (copy_ms[len(copy_ms) // 2] * 1e-3) / 1e9
         out["copy_ceiling"] = {"kind": "device-to-device copy of the payload buffer (HBM read + "
