@@ -233,6 +233,47 @@ def test_two_keys_on_two_streams_at_once():
     kb.free()
 
 
+def test_two_host_threads_each_with_its_key_and_stream():
+    """the library keeps no state outside its key objects (the last HIP error is per thread):
+    two host threads submit batches at the same time, each under its own key on its own stream"""
+    import threading
+    ws = [workloads.mini(3), workloads.mini(4)]
+    ws[1].key = np.random.default_rng(5).integers(0, 256, 32, dtype=np.uint8)
+    hosts = [w.payload_host() for w in ws]
+    keys = [pgcm.expand_key(w.key) for w in ws]
+    batches = [DeviceBatch(w, torch.from_numpy(h).cuda()) for w, h in zip(ws, hosts)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    errors = []
+    start = threading.Barrier(2)
+
+    def run(k):
+        try:
+            start.wait()
+            for _ in range(25):
+                batches[k].encrypt(keys[k], stream=streams[k])
+                batches[k].decrypt(keys[k], stream=streams[k])
+            streams[k].synchronize()
+        except Exception as e:      # noqa: BLE001 - reported by the main thread
+            errors.append((k, e))
+
+    threads = [threading.Thread(target=run, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for w, h, b in zip(ws, hosts, batches):
+        cts, tags = _oracle_encrypt(w, h)
+        ch = b.cipher.cpu().numpy()
+        for i in range(w.n):
+            assert np.array_equal(w.chunk(ch, i), cts[i])
+        assert np.array_equal(b.tags.cpu().numpy().reshape(-1, 16), tags)
+        assert bool((b.ok == 1).all()) and torch.equal(b.back, b.plain)
+    for k in keys:
+        k.free()
+
+
 def test_error_codes_and_empty_batch():
     w = workloads.config1(n=4, size=64)
     key = pgcm.expand_key(w.key)
