@@ -211,7 +211,7 @@ def main():
                          "line; --steps is the number of rounds per trace)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (chunks are independent; a multi-GPU "
+        print("bench.py: this benchmark measures one GPU only (chunks are independent; a multi-GPU "
               "run would just split the chunk list); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
