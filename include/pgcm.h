@@ -83,7 +83,9 @@ void pgcm_free_key(pgcm_key_t *key);
  *   ivs      DEVICE, n * 12 bytes; chunk i uses ivs[12 i .. 12 i + 11].
  *   aad      HOST array of n DEVICE pointers (any alignment); entries with aad_len[i] == 0 are
  *            not read.  Must be NULL exactly when aad_len is NULL.
- *   aad_len  HOST array of n byte counts, or NULL for "no chunk has AAD".
+ *   aad_len  HOST array of n byte counts, or NULL for "no chunk has AAD".  A chunk's AAD is
+ *            hashed block after block by one wavefront: meant for headers of tens of bytes
+ *            (any length is correct; a megabyte of AAD takes milliseconds).
  *   src      HOST array of n DEVICE pointers, each 16-byte aligned (unused when len[i] == 0).
  *   len      HOST array of n byte counts, 0 <= len[i] <= PGCM_MAX_CHUNK_BYTES; need not be a
  *            multiple of 16.  Exactly len[i] bytes are read and written, never more.
