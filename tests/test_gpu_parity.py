@@ -233,6 +233,24 @@ def test_two_keys_on_two_streams_at_once():
     kb.free()
 
 
+@pytest.mark.parametrize("lens", [[0, 40, 1000], [0, 3000, 8192], [0, 5, 70000, 1 << 20]])
+def test_long_aad_on_every_path(lens):
+    """AAD of thousands of bytes (ragged, block-aligned, and 70 001 bytes) with chunks that take
+    the one-row kernel, the workgroup-per-chunk kernel and the unit schedule; the empty chunk's
+    AAD is hashed by the final step"""
+    seed, rng, key, iv0 = workloads._base(11, len(lens))
+    alens = [4099, 4096, 70001, 17][:len(lens)]
+    la = np.array(lens, np.uint64)
+    offsets, total = workloads._layout(la)
+    aad_off = np.zeros(len(alens) + 1, np.uint64)
+    aad_off[1:] = np.cumsum(alens)
+    aad = rng.integers(0, 256, int(sum(alens)), dtype=np.uint8)
+    w = workloads.Workload("long_aad", seed, key, workloads.iv_sequence(iv0, la.size), la, offsets,
+                           total, "u8", aad, aad_off)
+    last = len(lens) - 1
+    _full_parity(w, flip=[(last, int(lens[last]) - 1, 0, "ct")])
+
+
 def test_two_host_threads_each_with_its_key_and_stream():
     """the library keeps no state outside its key objects (the last HIP error is per thread):
     two host threads submit batches at the same time, each under its own key on its own stream"""
