@@ -24,11 +24,11 @@ LDS_PEAK_GCYCLES = 256 * 2.4               # 256 CUs, one LDS pipe each, 2.4 GHz
 # `rocprofv3 --pmc` (summaries and commands: profiles/).  They describe the kernel sources whose
 # hash is given; once the sources change they no longer apply and bench.py reports null.
 COUNTERS = {
-    "sources_sha256": "98f09bea33180d15dea32221b5c3876723c37a38a4b0f1b8d0fe0c48d5c9deec",
+    "sources_sha256": "fe8984312c3d91b1d28d5afbb62eab3deef9dce2e15b2a13524384063f83da38",
     "workload": "c2_opt13b_kv_4096x320KiB",
-    "fetch_size_kib": 657232.3,     # FETCH_SIZE per launch
-    "fetch_scale": 1310720.0 / 655383.0,   # a 1 310 720 KiB device copy reads 655 383
-    "write_size_kib": 1395322.0,    # WRITE_SIZE per launch
+    "fetch_size_kib": 657226.9,     # FETCH_SIZE per launch
+    "fetch_scale": 1310720.0 / 655383.3,   # a 1 310 720 KiB device copy reads 655 383
+    "write_size_kib": 1395322.2,    # WRITE_SIZE per launch
     "write_scale": 1310720.0 / 1310720.0,  # the same copy writes 1 310 720.0
     "valu_wave_instructions": 609253376.0,  # SQ_INSTS_VALU per launch
     "lds_wave_instructions": 321931264.0,   # SQ_INSTS_LDS per launch

@@ -489,15 +489,19 @@ int run_batch(pgcm_key* key, const BatchArgs& a) {
             hipLaunchKernelGGL(fold_kernel, dim3(p.fold_count[l]), dim3(64), 0, a.stream, kt,
                                d_fold + p.fold_first[l], power, d_sets);
     }
-    const dim3 final_grid((nchunks + 15) / 16);
+    // one wavefront per chunk; few chunks are spread over the compute units rather than packed
+    // sixteen to a workgroup
+    uint32_t per_group = (nchunks + (uint32_t)key->num_cu - 1) / (uint32_t)key->num_cu;
+    if (per_group > kFinalWaves) per_group = kFinalWaves;
+    const dim3 final_grid((nchunks + per_group - 1) / per_group);
     if (a.decrypt)
-        hipLaunchKernelGGL(final_kernel<true>, final_grid, dim3(1024), 0, a.stream, kt, d_desc,
-                           nchunks, a.ivs, d_j0, d_ekj0, d_sets, a.tags, a.ok, p.unit_power,
-                           d_counter);
+        hipLaunchKernelGGL(final_kernel<true>, final_grid, dim3(kFinalWaves * 64), 0, a.stream, kt,
+                           d_desc, nchunks, a.ivs, d_j0, d_ekj0, d_sets, a.tags, a.ok,
+                           p.unit_power, d_counter, per_group);
     else
-        hipLaunchKernelGGL(final_kernel<false>, final_grid, dim3(1024), 0, a.stream, kt, d_desc,
-                           nchunks, a.ivs, d_j0, d_ekj0, d_sets, a.tags, (uint8_t*)nullptr,
-                           p.unit_power, d_counter);
+        hipLaunchKernelGGL(final_kernel<false>, final_grid, dim3(kFinalWaves * 64), 0, a.stream,
+                           kt, d_desc, nchunks, a.ivs, d_j0, d_ekj0, d_sets, a.tags,
+                           (uint8_t*)nullptr, p.unit_power, d_counter, per_group);
     PGCM_HIP(hipGetLastError());
     key->counter_dirty = false;
     return PGCM_OK;

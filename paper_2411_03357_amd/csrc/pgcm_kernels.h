@@ -29,7 +29,8 @@ template <bool kDecrypt>
 __global__ void final_kernel(const KeyTables* kt, const ChunkDesc* chunks, uint32_t nchunks,
                              const uint8_t* ivs, const Block* j0, const Block* ekj0,
                              const Block* sets, uint8_t* tags, uint8_t* ok, uint32_t unit_power,
-                             uint32_t* counter);
+                             uint32_t* counter, uint32_t chunks_per_group);
+constexpr uint32_t kFinalWaves = 16;  // wavefronts of a final_kernel workgroup
 
 constexpr uint32_t kSmallChunksPerGroup = 4;
 

@@ -951,19 +951,21 @@ __global__ __launch_bounds__(kFoldTreeWaves * 64) void fold_tree_kernel(
     if (wave == 0) sets[(uint64_t)it.out_slot * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
 }
 
-// Per chunk (one wavefront each, sixteen chunks a workgroup): fold the remaining sets, fold the 64
-// lanes, finish the tag.  Workgroup 0 also clears `counter` for the next batch.
+// Per chunk (one wavefront each): fold the remaining sets, fold the 64 lanes, finish the tag.
+// A workgroup is sixteen wavefronts; all of them bring the tables in, the first chunks_per_group
+// of them then take a chunk each (the host spreads a batch of few chunks over the compute units:
+// the wavefronts of one unit share its LDS pipe, and every chunk is a chain of dependent
+// multiplications).  Workgroup 0 also clears `counter` for the next batch.
 // LDS: nibble tables of H^1 .. H^32 (tree), and of the two most common fold distances.
 // unit_power: log2 of the blocks per unit the batch was cut into.
-constexpr uint32_t kFinalChunksPerGroup = 16;
 constexpr uint32_t kFinalTables = 8;
 
 template <bool kDecrypt>
-__global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
+__global__ __launch_bounds__(kFinalWaves * 64) void final_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks, uint32_t nchunks,
     const uint8_t* __restrict__ ivs, const Block* __restrict__ j0, const Block* __restrict__ ekj0,
     const Block* __restrict__ sets, uint8_t* __restrict__ tags, uint8_t* __restrict__ ok,
-    uint32_t unit_power, uint32_t* __restrict__ counter) {
+    uint32_t unit_power, uint32_t* __restrict__ counter, uint32_t chunks_per_group) {
     __shared__ Block tables[kFinalTables][kNibbleTableEntries];
     const uint32_t tid = threadIdx.x, lane = tid & 63;
     if (blockIdx.x == 0 && tid == 0) *counter = 0;
@@ -974,7 +976,8 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
     copy_power_table(tables[7], kt, unit_power + kFanPower, tid, blockDim.x);
     __syncthreads();
 
-    const uint32_t i = blockIdx.x * kFinalChunksPerGroup + (tid >> 6);
+    if ((tid >> 6) >= chunks_per_group) return;
+    const uint32_t i = blockIdx.x * chunks_per_group + (tid >> 6);
     if (i >= nchunks) return;
     const ChunkDesc cd = chunks[i];
 
@@ -1003,11 +1006,11 @@ __global__ __launch_bounds__(kFinalChunksPerGroup * 64) void final_kernel(
 template __global__ void final_kernel<false>(const KeyTables*, const ChunkDesc*, uint32_t,
                                              const uint8_t*, const Block*, const Block*,
                                              const Block*, uint8_t*, uint8_t*, uint32_t,
-                                             uint32_t*);
+                                             uint32_t*, uint32_t);
 template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, uint32_t,
                                             const uint8_t*, const Block*, const Block*,
                                             const Block*, uint8_t*, uint8_t*, uint32_t,
-                                            uint32_t*);
+                                            uint32_t*, uint32_t);
 
 // ------------------------------------------------------------------------------------------
 // The small-transfer path: a batch whose chunks are all at most kSmallChunkBytes long (the
