@@ -1,13 +1,19 @@
-"""The five configurations at full size, in the launch configuration bench.py times.
+"""The four large configurations at full size, in the launch configuration bench.py times,
+compared with the CPU oracle on EVERY chunk, in both directions.
 
-The oracle cannot hash gigabytes in a test, so each run is checked (a) bit for bit against the
-oracle on sampled chunks (first, last, extremes of length, ragged, tampered), (b) on every chunk,
-every ciphertext byte and every tag, against libcrypto (an independent implementation that the
-oracle itself is pinned to), and (c) through properties that hold at any size: decryption of
-the encryption is the identity, exactly the tampered chunks are rejected and wiped, bytes
-between chunks are never touched."""
+Encryption: every ciphertext byte and every tag of every chunk equals the oracle's; the bytes
+between chunks keep their fill value.  Decryption with verification (with the configuration's
+tampering applied to the ciphertext and tags): every verdict equals the oracle's, every output
+byte of every chunk equals the oracle's (plaintext where authentic, zeros where rejected), and
+the bytes between chunks keep their fill value.  Beside the oracle, libcrypto (an independent
+implementation the oracle itself is pinned to) checks every ciphertext and tag once more.
+
+The oracle is bit-serial by design (about 5 MB/s per core), so a direction of a configuration
+takes between twenty seconds and a minute on sixteen host cores; it is fed in slices of a few
+hundred megabytes and every slice reports on the terminal, so that a slow host shows progress
+instead of silence."""
+import time
 from concurrent.futures import ThreadPoolExecutor
-
 
 import numpy as np
 import pytest
@@ -22,16 +28,41 @@ import paper_2411_03357_amd as pgcm
 
 pytestmark = pytest.mark.gpu
 
+ORACLE_THREADS = 16
+SLICE_BYTES = 192 << 20
+CIPHER_FILL, BACK_FILL = 0xEE, 0xDD
 
-def _sample(w, k_oracle=6):
-    rng = np.random.default_rng(w.seed + 99)
-    must = {0, w.n - 1, int(np.argmin(w.lens)), int(np.argmax(w.lens))}
-    ragged = np.flatnonzero(w.lens % 16 != 0)
-    if ragged.size:
-        must |= {int(ragged[0]), int(ragged[-1])}
-    must |= {t.chunk for t in w.tampers[:2]}
-    extra = [int(i) for i in rng.permutation(w.n)[:k_oracle]]
-    return sorted(must | set(extra[:max(0, k_oracle - len(must))]))
+
+def _slices(w):
+    """runs of consecutive chunks of about SLICE_BYTES of payload each"""
+    out, lo, acc = [], 0, 0
+    for i in range(w.n):
+        acc += int(w.lens[i])
+        if acc >= SLICE_BYTES or i + 1 == w.n:
+            out.append((lo, i + 1))
+            lo, acc = i + 1, 0
+    return out
+
+
+def _say(capsys, text):
+    with capsys.disabled():
+        print(text, flush=True)
+
+
+def _aads(w, lo, hi):
+    if w.aad is None:
+        return None
+    return [np.frombuffer(w.aad_of(i), np.uint8) for i in range(lo, hi)]
+
+
+def _gaps_hold(w, host, fill):
+    """every byte between chunks (alignment padding) still has the fill value"""
+    ends = (w.offsets + w.lens).astype(np.int64)
+    nxt = np.append(w.offsets[1:].astype(np.int64), w.total_bytes)
+    for i in np.flatnonzero(nxt > ends):
+        if not (host[int(ends[i]):int(nxt[i])] == fill).all():
+            return int(i)
+    return None
 
 
 def _first_chunk_libcrypto_disagrees_with(w, plain, cipher, tags):
@@ -57,67 +88,79 @@ def _first_chunk_libcrypto_disagrees_with(w, plain, cipher, tags):
     return min(found) if found else None
 
 
-def _run_full(cfg):
-    w = workloads.FULL[cfg]()
+def _encrypt_on_gpu(w):
     key = pgcm.expand_key(w.key)
     b = DeviceBatch(w, w.payload_device())
-    b.cipher.fill_(0xEE)
+    b.cipher.fill_(CIPHER_FILL)
     b.encrypt(key)
     torch.cuda.synchronize()
-    ora = _sample(w)
+    return key, b
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_encrypt_every_chunk_against_the_oracle(cfg, capsys):
+    w = workloads.FULL[cfg]()
+    key, b = _encrypt_on_gpu(w)
+    plain, cipher = b.plain.cpu().numpy(), b.cipher.cpu().numpy()
     tags = b.tags.cpu().numpy().reshape(-1, 16)
-
-    # (a) oracle on sampled chunks
-    srcs = [b.chunk_host(b.plain, i) for i in ora]
-    aads = None if w.aad is None else [np.frombuffer(w.aad_of(i), np.uint8) for i in ora]
-    cts, otags, _ = oracle.encrypt_batch(w.key, w.ivs[ora], aads, srcs, nthreads=16)
-    for j, i in enumerate(ora):
-        assert np.array_equal(b.chunk_host(b.cipher, i), cts[j]), "ciphertext, chunk %d" % i
-        assert np.array_equal(tags[i], otags[j]), "tag, chunk %d" % i
-    # (b) libcrypto on every chunk
-    differs = _first_chunk_libcrypto_disagrees_with(w, b.plain.cpu().numpy(),
-                                                    b.cipher.cpu().numpy(), tags)
+    key.free()
+    t0 = time.time()
+    for lo, hi in _slices(w):
+        srcs = [w.chunk(plain, i) for i in range(lo, hi)]
+        cts, otags, _ = oracle.encrypt_batch(w.key, w.ivs[lo:hi], _aads(w, lo, hi), srcs,
+                                             nthreads=ORACLE_THREADS)
+        for j, i in enumerate(range(lo, hi)):
+            assert np.array_equal(w.chunk(cipher, i), cts[j]), "ciphertext, chunk %d" % i
+            assert np.array_equal(tags[i], otags[j]), "tag, chunk %d" % i
+        _say(capsys, "  config %d encrypt: chunks %d..%d of %d equal the oracle's (%.0f s)"
+             % (cfg, lo, hi - 1, w.n, time.time() - t0))
+    bad_gap = _gaps_hold(w, cipher, CIPHER_FILL)
+    assert bad_gap is None, "bytes after chunk %d were written" % bad_gap
+    differs = _first_chunk_libcrypto_disagrees_with(w, plain, cipher, tags)
     assert differs is None, "chunk %d: ciphertext or tag differs from libcrypto's" % differs
-    # gaps between chunks untouched
-    for i in ora:
-        end = int(w.offsets[i] + w.lens[i])
-        nxt = int(w.offsets[i + 1]) if i + 1 < w.n else w.total_bytes
-        assert bool((b.cipher[end:nxt] == 0xEE).all())
 
-    # (c) decrypt-verify with the configuration's tampering
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_decrypt_verify_every_chunk_against_the_oracle(cfg, capsys):
+    w = workloads.FULL[cfg]()
+    key, b = _encrypt_on_gpu(w)   # its output is checked by the test above
     cipher_t, tags_t = b.cipher, b.tags.clone()
     apply_tampers(w, cipher_t, tags_t)
-    b.back.fill_(0xDD)
+    b.back.fill_(BACK_FILL)
     b.decrypt(key, src=cipher_t, tags=tags_t)
     torch.cuda.synchronize()
+    key.free()
     ok = b.ok.cpu().numpy()
     bad = sorted({t.chunk for t in w.tampers})
     assert sorted(np.flatnonzero(ok == 0).tolist()) == bad
     assert int((ok == 1).sum()) == w.n - len(bad)
+
+    # the whole output buffer, exactly: plaintext where authentic, zeros where rejected, the
+    # fill value between chunks
     expect = b.plain.clone()
+    ends = (w.offsets + w.lens).astype(np.int64)
+    nxt = np.append(w.offsets[1:].astype(np.int64), w.total_bytes)
+    for i in np.flatnonzero(nxt > ends):
+        expect[int(ends[i]):int(nxt[i])] = BACK_FILL
     for i in bad:
         off, ln = int(w.offsets[i]), int(w.lens[i])
         expect[off:off + ln] = 0
-    # compare chunk payloads only (gaps hold the fill value)
-    same = (b.back == expect) | (b.back == 0xDD)
-    mism = int((~same).sum())
-    assert mism == 0, "%d plaintext bytes differ" % mism
-    for i in ora:
-        got = b.chunk_host(b.back, i)
-        assert np.array_equal(got, b.chunk_host(expect, i)), i
-        end = int(w.offsets[i] + w.lens[i])
-        nxt = int(w.offsets[i + 1]) if i + 1 < w.n else w.total_bytes
-        assert bool((b.back[end:nxt] == 0xDD).all())
-    # oracle's verdict and output on the sampled chunks, tampered ones included
-    srcs = [b.chunk_host(cipher_t, i) for i in ora]
-    pts, ook, _ = oracle.decrypt_verify_batch(w.key, w.ivs[ora], aads, srcs,
-                                              tags_t.cpu().numpy().reshape(-1, 16)[ora], 16)
-    for j, i in enumerate(ora):
-        assert ok[i] == ook[j], i
-        assert np.array_equal(b.chunk_host(b.back, i), pts[j]), i
-    key.free()
+    mism = int((b.back != expect).sum())
+    assert mism == 0, "%d output bytes differ from plaintext / zeros / fill" % mism
+    del expect
 
-
-@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
-def test_full_size_configuration(cfg):
-    _run_full(cfg)
+    # ... and every chunk and verdict against the oracle's decryption of the same ciphertext
+    cipher, back = cipher_t.cpu().numpy(), b.back.cpu().numpy()
+    tags = tags_t.cpu().numpy().reshape(-1, 16)
+    t0 = time.time()
+    for lo, hi in _slices(w):
+        srcs = [w.chunk(cipher, i) for i in range(lo, hi)]
+        pts, ook, _ = oracle.decrypt_verify_batch(w.key, w.ivs[lo:hi], _aads(w, lo, hi), srcs,
+                                                  tags[lo:hi], ORACLE_THREADS)
+        for j, i in enumerate(range(lo, hi)):
+            assert ok[i] == ook[j], "verdict, chunk %d" % i
+            assert np.array_equal(w.chunk(back, i), pts[j]), "output, chunk %d" % i
+        _say(capsys, "  config %d decrypt-verify: chunks %d..%d of %d equal the oracle's (%.0f s)"
+             % (cfg, lo, hi - 1, w.n, time.time() - t0))
+    bad_gap = _gaps_hold(w, back, BACK_FILL)
+    assert bad_gap is None, "bytes after chunk %d were written" % bad_gap
