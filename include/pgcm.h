@@ -21,15 +21,21 @@
  *   - Work is enqueued on `hip_stream` (a hipStream_t cast to void*, NULL = the null stream) and
  *     the call returns without synchronising.  Device outputs are valid once the stream has
  *     reached the end of the batch; device inputs must stay alive and unchanged until then.
- *   - One key object may be used by one stream at a time: its descriptor workspace is reused
- *     from call to call and successive batches are ordered by the stream.
- *   - Errors are return codes; nothing is enqueued when a call fails.  Authentication failure of
- *     a chunk is not an error (see pgcm_decrypt_verify_batch).
+ *   - One key object serves any number of streams and host threads at once (the paper's
+ *     transport uses one session key for both directions, section 2.2): every batch call takes a
+ *     context of the key (descriptor staging and device workspace), bound to the call's stream,
+ *     and batches that share a stream are ordered by it.  Not thread-safe: pgcm_free_key and the
+ *     test and measurement aids (pgcm_set_unit_bytes, pgcm_set_timing and its readers).
+ *   - Errors are return codes.  A call that fails its argument checks (every status but
+ *     PGCM_ERR_NOMEM and PGCM_ERR_HIP) has enqueued nothing; after PGCM_ERR_NOMEM or PGCM_ERR_HIP
+ *     part of the batch may be on the stream, and its outputs are undefined.  Authentication
+ *     failure of a chunk is not an error (see pgcm_decrypt_verify_batch).
  *   - IV uniqueness per key is the caller's duty (the paper's transport uses a counter); it is
  *     not checked.
  *   - The batch calls plan on the host, and they allocate (and wait for the stream) whenever a
- *     batch needs more descriptor or workspace memory than any batch before it under the same
- *     key: they are not meant to be recorded into a HIP graph.
+ *     batch needs more descriptor or workspace memory than its context has: the first batches on
+ *     a stream, and any batch larger than those before it.  pgcm_reserve does that work ahead of
+ *     time.
  */
 #ifndef PGCM_H
 #define PGCM_H
@@ -52,7 +58,8 @@ typedef enum {
                             forced unit size allows (pgcm_set_unit_bytes) */
     PGCM_ERR_NOMEM = -4, /* host or device allocation failed */
     PGCM_ERR_HIP = -5,   /* a HIP call failed; see pgcm_last_hip_error */
-    PGCM_ERR_BUSY = -6   /* pgcm_bounce.h: every buffer of a pool is held */
+    PGCM_ERR_BUSY = -6,  /* pgcm_bounce.h: every buffer of a pool is held */
+    PGCM_ERR_CAPACITY = -7 /* a buffer of fixed size is too small for what was asked */
 } pgcm_status;
 
 #define PGCM_MAX_CHUNK_BYTES ((((uint64_t)1) << 36) - 32)
@@ -111,6 +118,16 @@ int pgcm_decrypt_verify_batch(pgcm_key_t *key, size_t n, const uint8_t *ivs,
                               const void *const *aad, const uint32_t *aad_len,
                               const void *const *src, const uint64_t *len, void *const *dst,
                               const uint8_t *tags, uint8_t *ok, void *hip_stream);
+
+/*
+ * Prepares the key's context for `hip_stream` (section 5.1: the transport knows the sizes of the
+ * swaps it will be asked for) so that batch calls on that stream with at most n_max chunks and at
+ * most payload_bytes_max bytes in all neither allocate nor wait for the stream: pinned staging
+ * for the descriptors and device workspace for the schedule and the partial hash sums (about
+ * 1/16 of the payload).  May allocate and synchronise the stream itself.  Call it again after
+ * pgcm_set_unit_bytes.  PGCM_ERR_ARG when the numbers are beyond what a batch can be.
+ */
+int pgcm_reserve(pgcm_key_t *key, void *hip_stream, size_t n_max, uint64_t payload_bytes_max);
 
 /*
  * The two batch calls for IVs of any one length (SP 800-38D 7.1 step 2: an IV that is not 96 bits
@@ -183,12 +200,50 @@ uint32_t pgcm_unit_bytes(void);
 /*
  * Bytes per unit for a batch with these chunk lengths (len: HOST array of n byte counts): the
  * smallest power of two from 1 KiB to pgcm_unit_bytes() with which the batch has at most 4096
- * units (the chip's wavefront slots: every unit then has a wavefront of its own at once, so a
- * batch of a few swap-sized chunks spreads over the whole chip), and pgcm_unit_bytes() when none
- * has (wavefronts then take further units in turn).  0 when len is NULL and n is not 0.  Batches
- * that take the small-transfer path (every chunk at most 8 KiB) are not cut into units at all.
+ * units (the wavefront slots of an MI355X, sixteen on each of 256 compute units: every unit then
+ * has a wavefront of its own at once, so a batch of a few swap-sized chunks spreads over the
+ * whole chip), and pgcm_unit_bytes() when none has (wavefronts then take further units in turn).
+ * The batch calls count sixteen slots per compute unit of the key's device, so on a partition of
+ * the chip they choose accordingly; this function and pgcm_plan_units describe the whole chip.
+ * 0 when len is NULL and n is not 0.  Batches that take the small-transfer path (every chunk at
+ * most 8 KiB) are not cut into units at all.
  */
 uint32_t pgcm_batch_unit_bytes(size_t n, const uint64_t *len);
+
+/*
+ * Test aid, host only: the complete schedule the batch calls would upload for chunks of these
+ * lengths (section 5.1: batches of copies of differing sizes), so that its invariants can be
+ * checked without a GPU.
+ *   unit_bytes   0 = chosen for the batch, else a forced unit size as for pgcm_set_unit_bytes.
+ *   wave_slots   wavefront slots of the device (16 per compute unit); 0 = 4096, an MI355X.
+ *   info         HOST, filled: offsets of the four arrays inside the image, the image's size, the
+ *                device workspace the batch would need, the unit size as log2 of its 16-byte
+ *                blocks, the numbers of units, partial-set slots (units + fold outputs), coarse
+ *                map entries and fold items, per fold level the count of items and the index of
+ *                the first, and the path the batch would take (0: the unit schedule, 1: the
+ *                one-kernel path with a wavefront per chunk, 2: with a workgroup per chunk).
+ *   image        HOST or NULL; when given it receives, at the offsets in info:
+ *                descriptors, 64 bytes per chunk: src, dst, aad (pointers, here dummies), len
+ *                  (u64), then u32 aad_len, unit_base, nunits, first_blocks, final_base,
+ *                  final_count, final_power, index;
+ *                unit_base, u32[n + 1]: index of each chunk's first unit, then the total;
+ *                coarse map, u32[ncoarse]: for units 0, 16, 32, ..: a chunk at or before the one
+ *                  that holds the unit;
+ *                fold items, 16 bytes each: u32 in_base, in_count, out_slot, pad; level l's items
+ *                  are fold_first[l] .. fold_first[l] + fold_count[l] - 1.
+ *   image_capacity  bytes at image; PGCM_ERR_CAPACITY when smaller than info->image_bytes.
+ * Returns PGCM_OK or the status the batch calls would give for these lengths.
+ */
+typedef struct pgcm_schedule_info {
+    uint64_t desc_offset, unit_base_offset, coarse_map_offset, fold_items_offset;
+    uint64_t image_bytes, workspace_bytes;
+    uint32_t unit_power, nunits, nslots, ncoarse, nfold;
+    uint32_t fold_count[4], fold_first[4];
+    uint32_t path;
+} pgcm_schedule_info;
+int pgcm_describe_schedule(size_t n, const uint64_t *len, uint32_t unit_bytes,
+                           uint32_t wave_slots, pgcm_schedule_info *info, void *image,
+                           size_t image_capacity);
 
 /*
  * Test aid: copies the key object's device tables to out (HOST), synchronising the device: 60

@@ -10,6 +10,7 @@ _lib = None
 
 EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_encrypt_batch",
            "pgcm_decrypt_verify_batch", "pgcm_encrypt_batch_iv", "pgcm_decrypt_verify_batch_iv",
+           "pgcm_reserve", "pgcm_describe_schedule",
            "pgcm_encrypt_batch_keys", "pgcm_decrypt_verify_batch_keys",
            "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_units", "pgcm_unit_bytes",
            "pgcm_batch_unit_bytes", "pgcm_set_unit_bytes", "pgcm_key_tables_bytes",
@@ -47,6 +48,10 @@ def load_library():
     lib.pgcm_free_key.restype = None
     lib.pgcm_encrypt_batch.argtypes = [vp, sz, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.pgcm_encrypt_batch.restype = C.c_int
+    lib.pgcm_reserve.argtypes = [vp, vp, sz, C.c_uint64]
+    lib.pgcm_reserve.restype = C.c_int
+    lib.pgcm_describe_schedule.argtypes = [sz, vp, C.c_uint32, C.c_uint32, vp, vp, sz]
+    lib.pgcm_describe_schedule.restype = C.c_int
     lib.pgcm_decrypt_verify_batch.argtypes = [vp, sz, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.pgcm_decrypt_verify_batch.restype = C.c_int
     lib.pgcm_encrypt_batch_iv.argtypes = [vp, sz, vp, C.c_uint32, vp, vp, vp, vp, vp, vp, vp]
@@ -194,6 +199,54 @@ def encrypt_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, stream=No
     _check(load_library().pgcm_encrypt_batch(
         key.handle, n, _dev_ptr(ivs), _addr(aad_a), _addr(alen_a), _addr(src_a), _addr(len_a),
         _addr(dst_a), _dev_ptr(tags), _stream_handle(stream)))
+
+
+def reserve(key: Key, n_max: int, payload_bytes_max: int, stream=None):
+    """pgcm_reserve"""
+    _check(load_library().pgcm_reserve(key.handle, _stream_handle(stream), n_max,
+                                       payload_bytes_max))
+
+
+class _ScheduleInfo(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("desc_offset", "unit_base_offset", "coarse_map_offset",
+                                          "fold_items_offset", "image_bytes", "workspace_bytes")] + \
+               [(n, C.c_uint32) for n in ("unit_power", "nunits", "nslots", "ncoarse", "nfold")] + \
+               [("fold_count", C.c_uint32 * 4), ("fold_first", C.c_uint32 * 4),
+                ("path", C.c_uint32)]
+
+
+CHUNK_DESC_DTYPE = np.dtype([("src", "<u8"), ("dst", "<u8"), ("aad", "<u8"), ("len", "<u8"),
+                             ("aad_len", "<u4"), ("unit_base", "<u4"), ("nunits", "<u4"),
+                             ("first_blocks", "<u4"), ("final_base", "<u4"),
+                             ("final_count", "<u4"), ("final_power", "<u4"), ("index", "<u4")])
+FOLD_ITEM_DTYPE = np.dtype([("in_base", "<u4"), ("in_count", "<u4"), ("out_slot", "<u4"),
+                            ("pad", "<u4")])
+
+
+def describe_schedule(length, unit_bytes=0, wave_slots=0) -> dict:
+    """pgcm_describe_schedule, taken apart; host only.  -> dict with the info fields and the
+    arrays `desc` (CHUNK_DESC_DTYPE), `unit_base`, `coarse_map`, `fold_items` (FOLD_ITEM_DTYPE)."""
+    len_a = np.ascontiguousarray(length, dtype=np.uint64)
+    n = len_a.size
+    info = _ScheduleInfo()
+    lib = load_library()
+    _check(lib.pgcm_describe_schedule(n, _addr(len_a) if n else None, unit_bytes, wave_slots,
+                                      C.addressof(info), None, 0))
+    image = np.zeros(max(1, int(info.image_bytes)), np.uint8)
+    _check(lib.pgcm_describe_schedule(n, _addr(len_a) if n else None, unit_bytes, wave_slots,
+                                      C.addressof(info), image.ctypes.data, image.size))
+    out = {k: int(getattr(info, k)) for k, _ in _ScheduleInfo._fields_
+           if k not in ("fold_count", "fold_first")}
+    out["fold_count"] = [int(v) for v in info.fold_count]
+    out["fold_first"] = [int(v) for v in info.fold_first]
+    out["desc"] = image[out["desc_offset"]:out["desc_offset"] + 64 * n].view(CHUNK_DESC_DTYPE)
+    ub = out["unit_base_offset"]
+    out["unit_base"] = image[ub:ub + 4 * (n + 1)].view(np.uint32) if n else np.zeros(1, np.uint32)
+    cm = out["coarse_map_offset"]
+    out["coarse_map"] = image[cm:cm + 4 * out["ncoarse"]].view(np.uint32)
+    fi = out["fold_items_offset"]
+    out["fold_items"] = image[fi:fi + 16 * out["nfold"]].view(FOLD_ITEM_DTYPE)
+    return out
 
 
 def decrypt_verify_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, ok, stream=None,

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -28,8 +29,12 @@ inline bool hip_failed(hipError_t e) {
         if (hip_failed(call)) return PGCM_ERR_HIP; \
     } while (0)
 
-constexpr int kStages = 2;
+// descriptor staging buffers a context uses in turn; a buffer is free again once the batch that
+// used it has ended on its stream, so this is how many batches the host may run ahead of the GPU
+constexpr int kStages = 4;
 constexpr uint32_t kTimingRing = 256;
+// contexts a key keeps before it starts re-binding the least recently used one to a new stream
+constexpr size_t kMaxContexts = 16;
 // a fold level with at most this many items (one workgroup each fits the chip at once) is folded
 // by the tree kernel
 constexpr uint32_t kFoldTreeMaxItems = 256;
@@ -65,12 +70,14 @@ inline uint32_t fold_levels(uint32_t nunits, uint32_t out_counts[kMaxLevels]) {
 }
 
 // Unit size of a batch: the smallest, from one row up, with which the batch has at most
-// kWaveSlots units, so that every unit gets a wavefront of its own at once; kUnitPower and the
-// dynamic schedule when even that leaves more.  (Larger units that would again give every
+// wave_slots units (the wavefronts the device holds at once: sixteen per compute unit), so that
+// every unit gets a wavefront of its own at once; kUnitPower and the dynamic schedule when even
+// that leaves more.  (Larger units that would again give every
 // wavefront exactly one unit, e.g. a whole 320 KiB block each for 4096 of them, can be forced but
 // are never chosen: wavefronts do not all run at the same speed, and a launch that cannot hand
 // the slow ones less work ends when its slowest wavefront does.)  `order` as for run_batch.
-inline uint32_t choose_unit_power(size_t n, const uint32_t* order, const uint64_t* len) {
+inline uint32_t choose_unit_power(size_t n, const uint32_t* order, const uint64_t* len,
+                                  uint32_t wave_slots) {
     constexpr uint32_t kChoices = kUnitPower - kMinUnitPower + 1;
     uint64_t units[kChoices] = {};
     for (size_t k = 0; k < n; ++k) {
@@ -81,27 +88,28 @@ inline uint32_t choose_unit_power(size_t n, const uint32_t* order, const uint64_
             const uint32_t u = kMinUnitPower + c;
             units[c] += (nblk + ((uint64_t)1 << u) - 1) >> u;
         }
-        if (units[kChoices - 1] > kWaveSlots) return kUnitPower;
+        if (units[kChoices - 1] > wave_slots) return kUnitPower;
     }
     for (uint32_t c = 0; c < kChoices; ++c)
-        if (units[c] <= kWaveSlots) return kMinUnitPower + c;
+        if (units[c] <= wave_slots) return kMinUnitPower + c;
     return kUnitPower;
 }
 
 }  // namespace
 
-struct pgcm_key {
-    int device = -1;
-    int num_cu = 0;
-    int rounds = 0;  // 10, 12 or 14
-    uint32_t forced_unit_power = 0;  // 0: chosen per batch
-    KeyTables* tables = nullptr;  // device
-    // descriptor staging: pinned host buffers used in turn, each guarded by an event that marks
-    // the end of its last upload
-    uint8_t* stage[kStages] = {nullptr, nullptr};
-    size_t stage_cap[kStages] = {0, 0};
-    hipEvent_t stage_done[kStages] = {nullptr, nullptr};
-    bool stage_used[kStages] = {false, false};
+namespace {
+
+// What one batch in flight needs besides the key's tables: pinned staging buffers for the
+// descriptors the host writes, and the device workspace the kernels of the batch share.  Batches
+// that use one context are ordered by the stream the context is bound to, which is what makes
+// reusing its buffers from batch to batch safe; batches on different streams (or from different
+// host threads) take different contexts.
+struct Context {
+    bool growable = true;   // false: the buffers are fixed and a batch that needs more is refused
+    uint8_t* stage[kStages] = {};
+    size_t stage_cap[kStages] = {};
+    hipEvent_t stage_done[kStages] = {};  // end of the batch that last used the buffer
+    bool stage_used[kStages] = {};
     int next_stage = 0;
     // device workspace: descriptors, unit maps, fold lists, unit counter, per-chunk E_K(J0),
     // partial sets
@@ -109,6 +117,26 @@ struct pgcm_key {
     size_t work_cap = 0;
     uint32_t* counter_at = nullptr;  // where the unit counter was last known to be zero
     bool counter_dirty = true;
+    // binding
+    hipStream_t stream = nullptr;
+    bool bound = false;        // has run a batch on `stream`
+    bool in_call = false;      // a host thread is inside a batch call with it
+    int last_stage = -1;       // stage whose event marks the end of its most recent batch
+    uint64_t last_use = 0;
+};
+
+}  // namespace
+
+struct pgcm_key {
+    int device = -1;
+    int num_cu = 0;
+    uint32_t wave_slots = kWaveSlots;  // wavefronts the device holds at once: 16 per CU
+    int rounds = 0;  // 10, 12 or 14
+    uint32_t forced_unit_power = 0;  // 0: chosen per batch
+    KeyTables* tables = nullptr;  // device
+    std::mutex mu;                 // guards `contexts` and the binding fields of each context
+    std::vector<Context*> contexts;
+    uint64_t use_tick = 0;
     // optional timing of the bulk kernel alone (pgcm_set_timing)
     // a ring of event pairs, one pair per timed launch, so that a run of batches can be timed
     // without a host wait in between
@@ -119,44 +147,148 @@ struct pgcm_key {
 
 namespace {
 
-int ensure_stage(pgcm_key* k, int s, size_t bytes) {
-    if (k->stage_used[s]) {
-        PGCM_HIP(hipEventSynchronize(k->stage_done[s]));
-        k->stage_used[s] = false;
+int create_stage_events(Context* c) {
+    for (int s = 0; s < kStages; ++s)
+        PGCM_HIP(hipEventCreateWithFlags(&c->stage_done[s], hipEventDisableTiming));
+    return PGCM_OK;
+}
+
+void destroy_context(Context* c, bool wipe_work) {
+    if (c->work && c->growable) {
+        // the workspace holds key-dependent values (tag masks, partial hashes)
+        if (wipe_work) (void)hipMemset(c->work, 0, c->work_cap);
+        (void)hipFree(c->work);
     }
-    if (k->stage_cap[s] >= bytes) return PGCM_OK;
-    if (k->stage[s]) {
-        PGCM_HIP(hipHostFree(k->stage[s]));
-        k->stage[s] = nullptr;
-        k->stage_cap[s] = 0;
+    for (int s = 0; s < kStages; ++s) {
+        if (c->stage[s]) {
+            memset(c->stage[s], 0, c->stage_cap[s]);
+            (void)hipHostFree(c->stage[s]);
+        }
+        if (c->stage_done[s]) (void)hipEventDestroy(c->stage_done[s]);
+    }
+}
+
+// Makes stage s of the context free (waits for the batch that last used it) and at least `bytes`
+// large.
+int ensure_stage(Context* c, int s, size_t bytes) {
+    if (c->stage_used[s]) {
+        PGCM_HIP(hipEventSynchronize(c->stage_done[s]));
+        c->stage_used[s] = false;
+    }
+    if (c->stage_cap[s] >= bytes) return PGCM_OK;
+    if (!c->growable) return PGCM_ERR_CAPACITY;
+    if (c->stage[s]) {
+        PGCM_HIP(hipHostFree(c->stage[s]));
+        c->stage[s] = nullptr;
+        c->stage_cap[s] = 0;
     }
     size_t cap = bytes + bytes / 2 + 4096;
     void* p = nullptr;
     if (hip_failed(hipHostMalloc(&p, cap, hipHostMallocDefault))) return PGCM_ERR_NOMEM;
-    k->stage[s] = (uint8_t*)p;
-    k->stage_cap[s] = cap;
+    c->stage[s] = (uint8_t*)p;
+    c->stage_cap[s] = cap;
     return PGCM_OK;
 }
 
-int ensure_work(pgcm_key* k, size_t bytes, hipStream_t stream) {
-    if (k->work_cap >= bytes) return PGCM_OK;
-    if (k->work) {
+int ensure_work(Context* c, size_t bytes, hipStream_t stream) {
+    if (c->work_cap >= bytes) return PGCM_OK;
+    if (!c->growable) return PGCM_ERR_CAPACITY;
+    if (c->work) {
         // earlier batches on this stream may still read the old workspace
         PGCM_HIP(hipStreamSynchronize(stream));
-        PGCM_HIP(hipFree(k->work));
-        k->work = nullptr;
-        k->work_cap = 0;
+        PGCM_HIP(hipFree(c->work));
+        c->work = nullptr;
+        c->work_cap = 0;
     }
-    k->counter_at = nullptr;  // new memory holds anything, even if it lands at the old address
+    c->counter_at = nullptr;  // new memory holds anything, even if it lands at the old address
     size_t cap = bytes + bytes / 2 + 65536;
     void* p = nullptr;
     if (hip_failed(hipMalloc(&p, cap))) return PGCM_ERR_NOMEM;
-    k->work = (uint8_t*)p;
-    k->work_cap = cap;
+    c->work = (uint8_t*)p;
+    c->work_cap = cap;
     return PGCM_OK;
 }
 
-inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+// The context a batch on `stream` runs with.  In order of preference: a context already bound to
+// the stream; one whose last batch has ended (it is re-bound); a new one; and, once the key has
+// kMaxContexts of them, the least recently used one, after waiting for its last batch.  Contexts
+// that another host thread is using at this moment are never taken.
+int acquire_context(pgcm_key* key, hipStream_t stream, Context** out) {
+    std::unique_lock<std::mutex> lock(key->mu);
+    Context* pick = nullptr;
+    for (Context* c : key->contexts)
+        if (!c->in_call && c->bound && c->stream == stream) { pick = c; break; }
+    bool must_wait = false;
+    if (pick == nullptr) {
+        Context* lru = nullptr;
+        for (Context* c : key->contexts) {
+            if (c->in_call) continue;
+            // free for re-binding: never bound, or its last batch has ended.  (A context that
+            // pgcm_reserve has bound and no batch has used yet is left for its stream.)
+            if (!c->bound || (c->last_stage >= 0 &&
+                              hipEventQuery(c->stage_done[c->last_stage]) == hipSuccess)) {
+                pick = c;
+                break;
+            }
+            if (lru == nullptr || c->last_use < lru->last_use) lru = c;
+        }
+        (void)hipGetLastError();  // a query that said "not ready" is not an error of this call
+        if (pick == nullptr && lru != nullptr && key->contexts.size() >= kMaxContexts) {
+            pick = lru;
+            must_wait = pick->last_stage >= 0;
+        }
+    }
+    if (pick == nullptr) {
+        Context* c = new (std::nothrow) Context();
+        if (c == nullptr) return PGCM_ERR_NOMEM;
+        int rc = create_stage_events(c);
+        if (rc == PGCM_OK) {
+            try {
+                key->contexts.push_back(c);
+            } catch (const std::bad_alloc&) {
+                rc = PGCM_ERR_NOMEM;
+            }
+        }
+        if (rc != PGCM_OK) {
+            destroy_context(c, false);
+            delete c;
+            return rc;
+        }
+        pick = c;
+    }
+    pick->in_call = true;
+    pick->last_use = ++key->use_tick;
+    lock.unlock();
+    if (pick->bound && pick->stream != stream) {
+        // re-binding: everything it enqueued on its old stream must have ended
+        if (must_wait && hip_failed(hipEventSynchronize(pick->stage_done[pick->last_stage]))) {
+            std::lock_guard<std::mutex> relock(key->mu);
+            pick->in_call = false;
+            return PGCM_ERR_HIP;
+        }
+        for (int s = 0; s < kStages; ++s) pick->stage_used[s] = false;
+    }
+    pick->stream = stream;
+    *out = pick;
+    return PGCM_OK;
+}
+
+void release_context(pgcm_key* key, Context* c) {
+    std::lock_guard<std::mutex> lock(key->mu);
+    c->in_call = false;
+}
+
+// marks the end of a batch that used stage s of the context
+int end_of_batch(Context* c, int s, hipStream_t stream) {
+    PGCM_HIP(hipEventRecord(c->stage_done[s], stream));
+    c->stage_used[s] = true;
+    c->last_stage = s;
+    c->bound = true;
+    c->next_stage = (s + 1) % kStages;
+    return PGCM_OK;
+}
+
+constexpr size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // the kernels that run the cipher are compiled once per round count
 template <bool kDecrypt, class... Args>
@@ -257,9 +389,11 @@ struct BatchPlan {
     uint32_t ncoarse;
 };
 
-int plan_batch(const pgcm_key* key, const BatchArgs& a, BatchPlan* plan) {
-    plan->unit_power =
-        key->forced_unit_power ? key->forced_unit_power : choose_unit_power(a.n, a.order, a.len);
+// forced_unit_power: 0 = chosen for the batch; wave_slots: see choose_unit_power
+int plan_batch(uint32_t forced_unit_power, uint32_t wave_slots, const BatchArgs& a,
+               BatchPlan* plan) {
+    plan->unit_power = forced_unit_power ? forced_unit_power
+                                         : choose_unit_power(a.n, a.order, a.len, wave_slots);
     plan->all_small = plan->all_one_row = true;
     uint64_t nunits = 0, nslots = 0;
     uint64_t fold_items[kMaxLevels] = {0, 0, 0, 0};
@@ -315,6 +449,34 @@ WorkLayout lay_out(const BatchArgs& a, const BatchPlan& p) {
     w.sets = round_up(w.j0 + (a.iv_len == 12 ? 0 : sizeof(Block) * a.n), 1024);
     w.bytes = w.sets + sizeof(Block) * 64 * (size_t)p.nslots;
     return w;
+}
+
+// Upper bounds of a batch's staging and workspace bytes, for any batch of at most n chunks with
+// at most `bytes` bytes of payload in all.  False when the numbers are out of range.
+bool worst_case_sizes(uint32_t forced_unit_power, uint32_t wave_slots, size_t n, uint64_t bytes,
+                      size_t* stage_bytes, size_t* work_bytes) {
+    // units: with the unit chosen per batch a batch either has at most wave_slots units or is cut
+    // into full-size units, each chunk adding at most one short unit
+    const uint32_t up = forced_unit_power ? forced_unit_power : kUnitPower;
+    uint64_t units = (bytes >> (up + 4)) + n;
+    if (!forced_unit_power && units < wave_slots) units = wave_slots;
+    // every fold level leaves at most units / 32 + n sets; four levels
+    const uint64_t folds = units / (kFan - 1) + kMaxLevels * (uint64_t)n + 1;
+    const uint64_t slots = units + folds;
+    if (slots > 0xFFFFFFF0ull / 64 || n > 0x7FFFFFFFull) return false;
+    BatchArgs a{};
+    a.n = n;
+    a.iv_len = 16;  // any length but 12: room for the pre-counter blocks as well
+    BatchPlan p{};
+    p.nunits = (uint32_t)units;
+    p.nslots = (uint32_t)slots;
+    p.nfold = (uint32_t)folds;
+    p.ncoarse = (p.nunits >> kCoarseShift) + 1;
+    const WorkLayout w = lay_out(a, p);
+    const size_t small = sizeof(ChunkDesc) * n;  // the small-transfer path stages descriptors only
+    *stage_bytes = w.upload_bytes > small ? w.upload_bytes : small;
+    *work_bytes = w.bytes;
+    return true;
 }
 
 // Descriptors, unit maps and fold lists of the batch, written into the staging buffer.
@@ -381,12 +543,12 @@ int record_timing_stop(pgcm_key* key, hipStream_t stream) {
 
 // Small-transfer path: one kernel, descriptors read straight from the pinned staging buffer, no
 // device workspace.
-int run_small_batch(pgcm_key* key, const BatchArgs& a, bool wide) {
+int run_small_batch(pgcm_key* key, Context* ctx, const BatchArgs& a, bool wide) {
     const uint32_t nchunks = (uint32_t)a.n;
-    const int s = key->next_stage;
-    int rc = ensure_stage(key, s, sizeof(ChunkDesc) * a.n);
+    const int s = ctx->next_stage;
+    int rc = ensure_stage(ctx, s, sizeof(ChunkDesc) * a.n);
     if (rc != PGCM_OK) return rc;
-    ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(key->stage[s]);
+    ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(ctx->stage[s]);
     for (size_t k = 0; k < a.n; ++k) describe_chunk(a, a.at(k), h_desc[k]);
     const KeyTables* kt = key->tables;
     rc = record_timing_start(key, a.stream);
@@ -397,76 +559,59 @@ int run_small_batch(pgcm_key* key, const BatchArgs& a, bool wide) {
     else
         launch_small<false>(key->rounds, wide, nchunks, a.stream, kt, (const ChunkDesc*)h_desc,
                             nchunks, a.ivs, a.iv_len, a.tags, (uint8_t*)nullptr);
+    // from here on the stream will read the staging buffer: mark its end even if a later call
+    // fails, so that the buffer is not rewritten under a running kernel
+    const int rc_end = end_of_batch(ctx, s, a.stream);
     rc = record_timing_stop(key, a.stream);
     if (rc != PGCM_OK) return rc;
     PGCM_HIP(hipGetLastError());
-    PGCM_HIP(hipEventRecord(key->stage_done[s], a.stream));
-    key->stage_used[s] = true;
-    key->next_stage = (s + 1) % kStages;
-    return PGCM_OK;
+    return rc_end;
 }
 
-// One batch under one key: validate everything, then enqueue upload, J0 (if needed), bulk, fold
-// levels and final kernels on the stream.
-int run_batch(pgcm_key* key, const BatchArgs& a) {
-    if (key == nullptr || key->tables == nullptr) return PGCM_ERR_ARG;
-    int rc = check_batch(a);
-    if (rc != PGCM_OK || a.n == 0) return rc;
-    BatchPlan p;
-    rc = plan_batch(key, a, &p);  // nothing has been touched so far
-    if (rc != PGCM_OK) return rc;
-    int cur_device = -1;
-    PGCM_HIP(hipGetDevice(&cur_device));
-    if (cur_device != key->device) return PGCM_ERR_ARG;  // the key lives on another GPU
-    if (p.all_one_row) return run_small_batch(key, a, false);
-    if (p.all_small && a.n <= kSmallWideMaxChunks) return run_small_batch(key, a, true);
-
+// The kernels of one batch that goes through the unit schedule, enqueued with context `ctx`.
+int run_unit_batch(pgcm_key* key, Context* ctx, const BatchArgs& a, const BatchPlan& p) {
     const uint32_t nchunks = (uint32_t)a.n;
     const WorkLayout w = lay_out(a, p);
-    const int s = key->next_stage;
-    rc = ensure_stage(key, s, w.upload_bytes);
+    const int s = ctx->next_stage;
+    int rc = ensure_stage(ctx, s, w.upload_bytes);
     if (rc != PGCM_OK) return rc;
-    rc = ensure_work(key, w.bytes, a.stream);
+    rc = ensure_work(ctx, w.bytes, a.stream);
     if (rc != PGCM_OK) return rc;
-    fill_schedule(a, p, w, key->stage[s]);
-    uint32_t* d_counter = reinterpret_cast<uint32_t*>(key->work + w.counter);
+    fill_schedule(a, p, w, ctx->stage[s]);
+    uint32_t* d_counter = reinterpret_cast<uint32_t*>(ctx->work + w.counter);
     {
         // the unit counter is left at zero by the last kernel of every batch; it only needs
         // clearing when the workspace is new, the counter's place in it has moved, or an earlier
         // batch was cut short
-        const bool clear = key->counter_at != d_counter || key->counter_dirty;
-        key->counter_at = d_counter;
-        key->counter_dirty = true;
+        const bool clear = ctx->counter_at != d_counter || ctx->counter_dirty;
+        ctx->counter_at = d_counter;
+        ctx->counter_dirty = true;
         const uint32_t n16 = (uint32_t)(w.upload_bytes / 16);
         uint32_t groups = (n16 + 255) / 256;
         if (groups > 1024) groups = 1024;
         hipLaunchKernelGGL(upload_kernel, dim3(groups), dim3(256), 0, a.stream,
-                           reinterpret_cast<uint4*>(key->work),
-                           reinterpret_cast<const uint4*>(key->stage[s]), n16,
+                           reinterpret_cast<uint4*>(ctx->work),
+                           reinterpret_cast<const uint4*>(ctx->stage[s]), n16,
                            clear ? d_counter : (uint32_t*)nullptr);
     }
-    PGCM_HIP(hipEventRecord(key->stage_done[s], a.stream));
-    key->stage_used[s] = true;
-    key->next_stage = (s + 1) % kStages;
 
     const KeyTables* kt = key->tables;
-    const ChunkDesc* d_desc = reinterpret_cast<const ChunkDesc*>(key->work + w.desc);
-    const uint32_t* d_ubase = reinterpret_cast<const uint32_t*>(key->work + w.ubase);
-    const uint32_t* d_coarse = reinterpret_cast<const uint32_t*>(key->work + w.coarse);
-    const FoldItem* d_fold = reinterpret_cast<const FoldItem*>(key->work + w.fold);
-    Block* d_ekj0 = reinterpret_cast<Block*>(key->work + w.ekj0);
-    Block* d_sets = reinterpret_cast<Block*>(key->work + w.sets);
-    Block* d_j0 = a.iv_len == 12 ? nullptr : reinterpret_cast<Block*>(key->work + w.j0);
+    const ChunkDesc* d_desc = reinterpret_cast<const ChunkDesc*>(ctx->work + w.desc);
+    const uint32_t* d_ubase = reinterpret_cast<const uint32_t*>(ctx->work + w.ubase);
+    const uint32_t* d_coarse = reinterpret_cast<const uint32_t*>(ctx->work + w.coarse);
+    const FoldItem* d_fold = reinterpret_cast<const FoldItem*>(ctx->work + w.fold);
+    Block* d_ekj0 = reinterpret_cast<Block*>(ctx->work + w.ekj0);
+    Block* d_sets = reinterpret_cast<Block*>(ctx->work + w.sets);
+    Block* d_j0 = a.iv_len == 12 ? nullptr : reinterpret_cast<Block*>(ctx->work + w.j0);
     if (d_j0 != nullptr)
         hipLaunchKernelGGL(j0_kernel, dim3((nchunks + 63) / 64), dim3(64), 0, a.stream, kt, d_desc,
                            a.ivs, a.iv_len, nchunks, d_j0);
 
-
+    int rc_timing = PGCM_OK;
     if (p.nunits > 0) {
         uint32_t groups = (p.nunits + kWavesPerGroup - 1) / kWavesPerGroup;
         if (groups > (uint32_t)key->num_cu) groups = (uint32_t)key->num_cu;
-        rc = record_timing_start(key, a.stream);
-        if (rc != PGCM_OK) return rc;
+        rc_timing = record_timing_start(key, a.stream);
         if (a.decrypt)
             launch_bulk<true>(key->rounds, dim3(groups), a.stream, kt, d_desc, d_ubase, d_coarse,
                               p.nunits, p.unit_power, d_counter, a.ivs, (const Block*)d_j0, d_ekj0,
@@ -475,8 +620,7 @@ int run_batch(pgcm_key* key, const BatchArgs& a) {
             launch_bulk<false>(key->rounds, dim3(groups), a.stream, kt, d_desc, d_ubase, d_coarse,
                                p.nunits, p.unit_power, d_counter, a.ivs, (const Block*)d_j0,
                                d_ekj0, d_sets);
-        rc = record_timing_stop(key, a.stream);
-        if (rc != PGCM_OK) return rc;
+        if (rc_timing == PGCM_OK) rc_timing = record_timing_stop(key, a.stream);
     }
     for (uint32_t l = 0; l < kMaxLevels; ++l) {
         if (p.fold_count[l] == 0) continue;
@@ -502,9 +646,39 @@ int run_batch(pgcm_key* key, const BatchArgs& a) {
         hipLaunchKernelGGL(final_kernel<false>, final_grid, dim3(kFinalWaves * 64), 0, a.stream,
                            kt, d_desc, nchunks, a.ivs, d_j0, d_ekj0, d_sets, a.tags,
                            (uint8_t*)nullptr, p.unit_power, d_counter, per_group);
+    // the stream now reads the staging buffer and the workspace: their end is marked whatever
+    // else fails below
+    const int rc_end = end_of_batch(ctx, s, a.stream);
+    if (rc_timing != PGCM_OK) return rc_timing;
     PGCM_HIP(hipGetLastError());
-    key->counter_dirty = false;
+    if (rc_end != PGCM_OK) return rc_end;
+    ctx->counter_dirty = false;
     return PGCM_OK;
+}
+
+// One batch under one key: validate everything, pick a context, then enqueue upload, J0 (if
+// needed), bulk, fold levels and final kernels on the stream.
+int run_batch(pgcm_key* key, const BatchArgs& a) {
+    if (key == nullptr || key->tables == nullptr) return PGCM_ERR_ARG;
+    int rc = check_batch(a);
+    if (rc != PGCM_OK || a.n == 0) return rc;
+    BatchPlan p;
+    rc = plan_batch(key->forced_unit_power, key->wave_slots, a, &p);  // nothing touched so far
+    if (rc != PGCM_OK) return rc;
+    int cur_device = -1;
+    PGCM_HIP(hipGetDevice(&cur_device));
+    if (cur_device != key->device) return PGCM_ERR_ARG;  // the key lives on another GPU
+    Context* ctx = nullptr;
+    rc = acquire_context(key, a.stream, &ctx);
+    if (rc != PGCM_OK) return rc;
+    if (p.all_one_row)
+        rc = run_small_batch(key, ctx, a, false);
+    else if (p.all_small && a.n <= kSmallWideMaxChunks)
+        rc = run_small_batch(key, ctx, a, true);
+    else
+        rc = run_unit_batch(key, ctx, a, p);
+    release_context(key, ctx);
+    return rc;
 }
 
 // A batch whose chunks name their key: the chunks are grouped by key (keeping their order) and
@@ -575,12 +749,7 @@ int pgcm_expand_key_bytes(const uint8_t* key, uint32_t key_bytes, void* hip_stre
         if (k->num_cu < 1) k->num_cu = 1;
         if (hip_failed(hipMalloc((void**)&k->tables, sizeof(KeyTables)))) { rc = PGCM_ERR_NOMEM; break; }
         if (hip_failed(hipMalloc((void**)&d_key, 32))) { rc = PGCM_ERR_NOMEM; break; }
-        for (int s = 0; s < kStages; ++s)
-            if (hip_failed(hipEventCreateWithFlags(&k->stage_done[s], hipEventDisableTiming))) {
-                rc = PGCM_ERR_HIP;
-                break;
-            }
-        if (rc != PGCM_OK) break;
+        k->wave_slots = (uint32_t)k->num_cu * kWavesPerGroup;
         // a pageable copy of at most 32 bytes: staged by the runtime, complete on return for this size
         if (hip_failed(hipMemcpyAsync(d_key, key, key_bytes, hipMemcpyHostToDevice, stream))) { rc = PGCM_ERR_HIP; break; }
         k->rounds = (int)(key_bytes / 4 + 6);
@@ -605,17 +774,9 @@ void pgcm_free_key(pgcm_key_t* k) {
         (void)hipMemset(k->tables, 0, sizeof(KeyTables));
         (void)hipFree(k->tables);
     }
-    if (k->work) {
-        // the workspace holds key-dependent values (tag masks, partial hashes)
-        (void)hipMemset(k->work, 0, k->work_cap);
-        (void)hipFree(k->work);
-    }
-    for (int s = 0; s < kStages; ++s) {
-        if (k->stage[s]) {
-            memset(k->stage[s], 0, k->stage_cap[s]);
-            (void)hipHostFree(k->stage[s]);
-        }
-        if (k->stage_done[s]) (void)hipEventDestroy(k->stage_done[s]);
+    for (Context* c : k->contexts) {
+        destroy_context(c, true);
+        delete c;
     }
     for (uint32_t i = 0; i < kTimingRing; ++i) {
         if (k->bulk_start[i]) (void)hipEventDestroy(k->bulk_start[i]);
@@ -636,6 +797,30 @@ int pgcm_encrypt_batch_iv(pgcm_key_t* key, size_t n, const uint8_t* ivs, uint32_
                           const uint64_t* len, void* const* dst, uint8_t* tags, void* hip_stream) {
     return run_batch(key, BatchArgs{false, n, nullptr, ivs, iv_bytes, aad, aad_len, src, len, dst,
                                     tags, nullptr, (hipStream_t)hip_stream});
+}
+
+int pgcm_reserve(pgcm_key_t* key, void* hip_stream, size_t n_max, uint64_t payload_bytes_max) {
+    if (key == nullptr || key->tables == nullptr || n_max > 0x7FFFFFFFull) return PGCM_ERR_ARG;
+    int cur_device = -1;
+    PGCM_HIP(hipGetDevice(&cur_device));
+    if (cur_device != key->device) return PGCM_ERR_ARG;
+    size_t stage_bytes = 0, work_bytes = 0;
+    if (!worst_case_sizes(key->forced_unit_power, key->wave_slots, n_max, payload_bytes_max,
+                          &stage_bytes, &work_bytes))
+        return PGCM_ERR_ARG;
+    const hipStream_t stream = (hipStream_t)hip_stream;
+    Context* ctx = nullptr;
+    int rc = acquire_context(key, stream, &ctx);
+    if (rc != PGCM_OK) return rc;
+    for (int s = 0; s < kStages && rc == PGCM_OK; ++s) rc = ensure_stage(ctx, s, stage_bytes);
+    if (rc == PGCM_OK) rc = ensure_work(ctx, work_bytes, stream);
+    if (rc == PGCM_OK) {
+        // the context now belongs to this stream, so that the stream's batches find it
+        std::lock_guard<std::mutex> lock(key->mu);
+        ctx->bound = true;
+    }
+    release_context(key, ctx);
+    return rc;
 }
 
 int pgcm_decrypt_verify_batch(pgcm_key_t* key, size_t n, const uint8_t* ivs,
@@ -684,6 +869,7 @@ const char* pgcm_strerror(int status) {
         case PGCM_ERR_NOMEM: return "out of host or device memory";
         case PGCM_ERR_HIP: return "a HIP runtime call failed";
         case PGCM_ERR_BUSY: return "every buffer of the pool is held";
+        case PGCM_ERR_CAPACITY: return "a buffer of fixed size is too small for what was asked";
         default: return "unknown status";
     }
 }
@@ -694,7 +880,7 @@ int64_t pgcm_plan_units(size_t n, const uint64_t* len, uint32_t* nunits, uint32_
                         uint32_t* unit_base, uint32_t* final_count, uint32_t* final_power) {
     if (n != 0 && len == nullptr) return PGCM_ERR_ARG;
     uint64_t total = 0;
-    const uint32_t unit_power = choose_unit_power(n, nullptr, len);
+    const uint32_t unit_power = choose_unit_power(n, nullptr, len, kWaveSlots);
     for (size_t i = 0; i < n; ++i) {
         if (len[i] > PGCM_MAX_CHUNK_BYTES) return PGCM_ERR_LEN;
         UnitPlan p = plan_chunk(len[i], unit_power);
@@ -716,7 +902,55 @@ uint32_t pgcm_unit_bytes(void) { return kUnitBytes; }
 
 uint32_t pgcm_batch_unit_bytes(size_t n, const uint64_t* len) {
     if (n != 0 && len == nullptr) return 0;
-    return 16u << choose_unit_power(n, nullptr, len);
+    return 16u << choose_unit_power(n, nullptr, len, kWaveSlots);
+}
+
+int pgcm_describe_schedule(size_t n, const uint64_t* len, uint32_t unit_bytes, uint32_t wave_slots,
+                           pgcm_schedule_info* info, void* image, size_t image_capacity) {
+    if (info == nullptr || (n != 0 && len == nullptr) || n > 0x7FFFFFFFull) return PGCM_ERR_ARG;
+    uint32_t forced = 0;
+    if (unit_bytes != 0) {
+        for (uint32_t u = kMinUnitPower; u <= kMaxUnitPower; ++u)
+            if (unit_bytes == (16u << u)) forced = u;
+        if (forced == 0) return PGCM_ERR_ARG;
+    }
+    memset(info, 0, sizeof(*info));
+    // stand-ins for the device pointers a real batch carries (16-byte aligned, never followed)
+    std::vector<const void*> ptrs;
+    try {
+        ptrs.assign(n, reinterpret_cast<const void*>((uintptr_t)4096));
+    } catch (const std::bad_alloc&) {
+        return PGCM_ERR_NOMEM;
+    }
+    BatchArgs a{false, n, nullptr, reinterpret_cast<const uint8_t*>((uintptr_t)4096), 12, nullptr,
+                nullptr, ptrs.data(), len, const_cast<void* const*>(ptrs.data()),
+                reinterpret_cast<uint8_t*>((uintptr_t)4096), nullptr, nullptr};
+    BatchPlan p{};
+    int rc = plan_batch(forced, wave_slots ? wave_slots : kWaveSlots, a, &p);
+    if (rc != PGCM_OK) return rc;
+    const WorkLayout w = lay_out(a, p);
+    info->desc_offset = w.desc;
+    info->unit_base_offset = w.ubase;
+    info->coarse_map_offset = w.coarse;
+    info->fold_items_offset = w.fold;
+    info->image_bytes = w.upload_bytes;
+    info->workspace_bytes = w.bytes;
+    info->unit_power = p.unit_power;
+    info->nunits = p.nunits;
+    info->nslots = p.nslots;
+    info->ncoarse = p.ncoarse;
+    info->nfold = p.nfold;
+    for (uint32_t l = 0; l < kMaxLevels; ++l) {
+        info->fold_count[l] = p.fold_count[l];
+        info->fold_first[l] = p.fold_first[l];
+    }
+    info->path = n == 0 ? 0 : p.all_one_row ? 1 : (p.all_small && n <= kSmallWideMaxChunks) ? 2 : 0;
+    if (image != nullptr) {
+        if (image_capacity < w.upload_bytes) return PGCM_ERR_CAPACITY;
+        memset(image, 0, w.upload_bytes);
+        if (n != 0) fill_schedule(a, p, w, static_cast<uint8_t*>(image));
+    }
+    return PGCM_OK;
 }
 
 size_t pgcm_key_tables_bytes(void) { return sizeof(KeyTables); }

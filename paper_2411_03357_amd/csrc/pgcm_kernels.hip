@@ -17,6 +17,7 @@
 //     per chunk (powers H^(2^k) from tables, DPP reduction tree over the lanes).
 //   * A batch of short chunks only is done by one kernel, a wavefront per chunk.
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include <type_traits>
@@ -319,7 +320,9 @@ struct alignas(16) BulkLds {
     Block gh[kNibbleTableEntries];
     uint32_t te[kLdsTeBytes / 4];
 };
-static_assert(sizeof(BulkLds) == kLdsBytes, "LDS map");
+static_assert(sizeof(BulkLds) == kLdsBytes && offsetof(BulkLds, gh) == 0 &&
+                  offsetof(BulkLds, te) == kLdsTeBase,
+              "LDS map");
 
 typedef __attribute__((address_space(3))) const uint32_t* lds_u32_ptr;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -349,10 +352,13 @@ __device__ __forceinline__ u32x4 lds_read128(uint32_t addr) {
 }
 
 // Round-table reads.  `a` already is pair << 16 | x << 8 | lane byte; T selects the table of the
-// pair through the constant part of the address.
+// pair through the constant part of the address, which also carries `base`, the LDS address of
+// the kernel's BulkLds object (a link-time constant, 0 when it is the kernel's only LDS object,
+// so the sum lands in the instruction's offset field; a[] itself must stay free of it because
+// byte 1 of a[] is rewritten every round).
 template <int T>
-__device__ __forceinline__ uint32_t te_read(uint32_t a) {
-    return lds_read32(a + kLdsTeBase + 128u * (T & 1));
+__device__ __forceinline__ uint32_t te_read(uint32_t a, uint32_t base) {
+    return lds_read32(a + (base + kLdsTeBase + 128u * (T & 1)));
 }
 
 // a.byte1 = rk.byte[KS] ^ v.byte[KV], every other byte of a kept: one SDWA instruction folds the
@@ -405,17 +411,18 @@ struct CtrConsts {
 };
 
 __device__ __forceinline__ CtrConsts ctr_consts(const uint32_t* __restrict__ rk, uint32_t lane,
-                                                uint32_t iv0, uint32_t iv1, uint32_t iv2) {
+                                                uint32_t iv0, uint32_t iv1, uint32_t iv2,
+                                                uint32_t base) {
     const uint32_t lo = (lane & 31) * 4, hi = lo | 0x10000u;
     const uint32_t s0 = iv0 ^ rk[0], s1 = iv1 ^ rk[1], s2 = iv2 ^ rk[2];
     auto at = [&](uint32_t w, int k, uint32_t lane_bytes) {
         return (((w >> (8 * k)) & 0xFFu) << 8) | lane_bytes;
     };
     CtrConsts c;
-    c.k[0] = te_read<0>(at(s0, 0, lo)) ^ te_read<1>(at(s1, 1, lo)) ^ te_read<2>(at(s2, 2, hi));
-    c.k[1] = te_read<0>(at(s1, 0, lo)) ^ te_read<1>(at(s2, 1, lo)) ^ te_read<3>(at(s0, 3, hi));
-    c.k[2] = te_read<0>(at(s2, 0, lo)) ^ te_read<2>(at(s0, 2, hi)) ^ te_read<3>(at(s1, 3, hi));
-    c.k[3] = te_read<1>(at(s0, 1, lo)) ^ te_read<2>(at(s1, 2, hi)) ^ te_read<3>(at(s2, 3, hi));
+    c.k[0] = te_read<0>(at(s0, 0, lo), base) ^ te_read<1>(at(s1, 1, lo), base) ^ te_read<2>(at(s2, 2, hi), base);
+    c.k[1] = te_read<0>(at(s1, 0, lo), base) ^ te_read<1>(at(s2, 1, lo), base) ^ te_read<3>(at(s0, 3, hi), base);
+    c.k[2] = te_read<0>(at(s2, 0, lo), base) ^ te_read<2>(at(s0, 2, hi), base) ^ te_read<3>(at(s1, 3, hi), base);
+    c.k[3] = te_read<1>(at(s0, 1, lo), base) ^ te_read<2>(at(s1, 2, hi), base) ^ te_read<3>(at(s2, 3, hi), base);
     return c;
 }
 
@@ -446,6 +453,7 @@ __device__ __forceinline__ uint32_t nibble_offset(uint32_t v, uint32_t mask_f0) 
 // eight XORs each) so that the steps can be spread over the AES rounds of the same row: the
 // hash arithmetic then fills the time the wavefront would wait for round-table lookups.
 struct GhashRowMul {
+    uint32_t table; // LDS address of the nibble table of H^64
     uint32_t w[4];  // the multiplicand
     uint32_t t;     // current word << 4: its byte k carries the low nibble of byte k
     uint32_t z0 = 0, z1 = 0, z2 = 0, z3 = 0;
@@ -457,8 +465,8 @@ struct GhashRowMul {
         constexpr uint32_t pos = 2 * S;
         const uint32_t f0 = 0xF0u;
         if constexpr (k == 0) t = w[i] << 4;
-        ra = lds_read128(nibble_offset<k>(w[i], f0) + pos * 256);
-        rb = lds_read128(nibble_offset<k>(t, f0) + (pos + 1) * 256);
+        ra = lds_read128(nibble_offset<k>(w[i], f0) + (table + pos * 256));
+        rb = lds_read128(nibble_offset<k>(t, f0) + (table + (pos + 1) * 256));
     }
     __device__ __forceinline__ void consume() {
         z0 = xor3(z0, ra.x, rb.x);
@@ -484,15 +492,15 @@ struct GhashRowMul {
 template <int kRounds>
 __device__ __forceinline__ void aes_ctr_lds(const uint32_t* __restrict__ rk, AesAddr& A,
                                                const CtrConsts& C, uint32_t ctr, GhashRowMul& G,
-                                               uint32_t& o0, uint32_t& o1, uint32_t& o2,
-                                               uint32_t& o3) {
+                                               uint32_t base, uint32_t& o0, uint32_t& o1,
+                                               uint32_t& o2, uint32_t& o3) {
     // round 1: the counter is the last word, big endian: state byte k is counter byte 3 - k
     key_xor_into_addr<3, 0>(A.a[3][3], rk[3], ctr);
     key_xor_into_addr<2, 1>(A.a[3][2], rk[3], ctr);
     key_xor_into_addr<1, 2>(A.a[3][1], rk[3], ctr);
     key_xor_into_addr<0, 3>(A.a[3][0], rk[3], ctr);
-    uint32_t l0 = te_read<3>(A.a[3][3]), l1 = te_read<2>(A.a[3][2]), l2 = te_read<1>(A.a[3][1]),
-             l3 = te_read<0>(A.a[3][0]);
+    uint32_t l0 = te_read<3>(A.a[3][3], base), l1 = te_read<2>(A.a[3][2], base), l2 = te_read<1>(A.a[3][1], base),
+             l3 = te_read<0>(A.a[3][0], base);
     G.issue<0>();
     uint32_t u0 = C.k[0] ^ l0, u1 = C.k[1] ^ l1, u2 = C.k[2] ^ l2, u3 = C.k[3] ^ l3;
     G.consume();
@@ -521,14 +529,14 @@ __device__ __forceinline__ void aes_ctr_lds(const uint32_t* __restrict__ rk, Aes
         key_xor_into_addr<1, 1>(A.a[3][1], k[3], u3);
         key_xor_into_addr<2, 2>(A.a[3][2], k[3], u3);
         key_xor_into_addr<3, 3>(A.a[3][3], k[3], u3);
-        uint32_t t00 = te_read<0>(A.a[0][0]), t11 = te_read<1>(A.a[1][1]),
-                 t22 = te_read<2>(A.a[2][2]), t33 = te_read<3>(A.a[3][3]);
-        uint32_t t10 = te_read<0>(A.a[1][0]), t21 = te_read<1>(A.a[2][1]),
-                 t32 = te_read<2>(A.a[3][2]), t03 = te_read<3>(A.a[0][3]);
-        uint32_t t20 = te_read<0>(A.a[2][0]), t31 = te_read<1>(A.a[3][1]),
-                 t02 = te_read<2>(A.a[0][2]), t13 = te_read<3>(A.a[1][3]);
-        uint32_t t30 = te_read<0>(A.a[3][0]), t01 = te_read<1>(A.a[0][1]),
-                 t12 = te_read<2>(A.a[1][2]), t23 = te_read<3>(A.a[2][3]);
+        uint32_t t00 = te_read<0>(A.a[0][0], base), t11 = te_read<1>(A.a[1][1], base),
+                 t22 = te_read<2>(A.a[2][2], base), t33 = te_read<3>(A.a[3][3], base);
+        uint32_t t10 = te_read<0>(A.a[1][0], base), t21 = te_read<1>(A.a[2][1], base),
+                 t32 = te_read<2>(A.a[3][2], base), t03 = te_read<3>(A.a[0][3], base);
+        uint32_t t20 = te_read<0>(A.a[2][0], base), t31 = te_read<1>(A.a[3][1], base),
+                 t02 = te_read<2>(A.a[0][2], base), t13 = te_read<3>(A.a[1][3], base);
+        uint32_t t30 = te_read<0>(A.a[3][0], base), t01 = te_read<1>(A.a[0][1], base),
+                 t12 = te_read<2>(A.a[1][2], base), t23 = te_read<3>(A.a[2][3], base);
         G.template issue<step_begin>();
         if constexpr (r < kRounds) {
             u0 = xor3(t00, t11, t22) ^ t33;
@@ -594,7 +602,7 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
                                          const CtrConsts& C, uint32_t ctr1, const uint8_t* src,
                                          uint8_t* dst, uint64_t len, int64_t blk, bool edge,
                                          const Block& aad_y, Block* __restrict__ ekj0_out,
-                                         uint32_t y[4]) {
+                                         uint32_t lds_base, uint32_t y[4]) {
     bool active = true;
     uint32_t tail = 0;  // bytes in a ragged block, 0 = whole block
     if (edge) {
@@ -627,9 +635,10 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
     // blk + 1 modulo 2^32 (SP 800-38D 6.2, 7.1 step 3; ctr1 is that field plus 1, 2 for a 96-bit
     // IV) ... while the hash state moves one row along: Y <- Y * H^64
     GhashRowMul G;
+    G.table = lds_base;  // the nibble table is the first member of BulkLds
     G.w[0] = y[0], G.w[1] = y[1], G.w[2] = y[2], G.w[3] = y[3];
     uint32_t s0, s1, s2, s3;
-    aes_ctr_lds<kRounds>(rk, A, C, (uint32_t)blk + ctr1, G, s0, s1, s2, s3);
+    aes_ctr_lds<kRounds>(rk, A, C, (uint32_t)blk + ctr1, G, lds_base, s0, s1, s2, s3);
     uint32_t o0 = x0 ^ s0, o1 = x1 ^ s1, o2 = x2 ^ s2, o3 = x3 ^ s3;
 
     if (whole) {
@@ -691,8 +700,9 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     const uint8_t* __restrict__ ivs, const Block* __restrict__ j0, Block* __restrict__ ekj0,
     Block* __restrict__ sets) {
     __shared__ BulkLds lds;
-    // lookup addresses are formed as raw LDS addresses that assume this object starts at 0
-    if (lds_offset(&lds) != 0) return;
+    // lookups use raw LDS addresses relative to this object; its own address (0 as long as it
+    // is the kernel's only LDS object) rides in the constant part of every lookup address
+    const uint32_t lds_base = lds_offset(&lds);
 
     const uint32_t tid = threadIdx.x;
     // fill: 32 copies of every table entry, lane-interleaved
@@ -734,7 +744,7 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
         const uint32_t nrows = (uint32_t)((b1 - b0 + kRowBlocks - 1) / kRowBlocks);
 
         const Block j = chunk_j0(kt, ivs, j0, chunk, cd->index);
-        const CtrConsts C = ctr_consts(rk, lane, j.w[0], j.w[1], j.w[2]);
+        const CtrConsts C = ctr_consts(rk, lane, j.w[0], j.w[1], j.w[2], lds_base);
         const uint32_t ctr1 = bswap32(j.w[3]) + 1u;
 
         Block aad_y{{0, 0, 0, 0}};
@@ -747,7 +757,7 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
         for (uint32_t r = 0; r < nrows; ++r, row_blk += kRowBlocks) {
             const bool edge = row_blk <= 0 || (unit + 1 == nunits && r + 1 == nrows);
             bulk_row<kDecrypt, kRounds>(rk, A, C, ctr1, src, dst, len, row_blk + lane, edge, aad_y,
-                                        ekj0 + chunk, y);
+                                        ekj0 + chunk, lds_base, y);
         }
         sets[(uint64_t)item * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
         if (one_each) break;
