@@ -35,7 +35,7 @@
  *   - The batch calls plan on the host, and they allocate (and wait for the stream) whenever a
  *     batch needs more descriptor or workspace memory than its context has: the first batches on
  *     a stream, and any batch larger than those before it.  pgcm_reserve does that work ahead of
- *     time.
+ *     time; pgcm_encrypt_batch_static never allocates at all.
  */
 #ifndef PGCM_H
 #define PGCM_H
@@ -59,7 +59,8 @@ typedef enum {
     PGCM_ERR_NOMEM = -4, /* host or device allocation failed */
     PGCM_ERR_HIP = -5,   /* a HIP call failed; see pgcm_last_hip_error */
     PGCM_ERR_BUSY = -6,  /* pgcm_bounce.h: every buffer of a pool is held */
-    PGCM_ERR_CAPACITY = -7 /* a buffer of fixed size is too small for what was asked */
+    PGCM_ERR_CAPACITY = -7 /* pgcm_encrypt_batch_static: the batch needs more than the fixed
+                              buffers of that call hold */
 } pgcm_status;
 
 #define PGCM_MAX_CHUNK_BYTES ((((uint64_t)1) << 36) - 32)
@@ -118,6 +119,32 @@ int pgcm_decrypt_verify_batch(pgcm_key_t *key, size_t n, const uint8_t *ivs,
                               const void *const *aad, const uint32_t *aad_len,
                               const void *const *src, const uint64_t *len, void *const *dst,
                               const uint8_t *tags, uint8_t *ok, void *hip_stream);
+
+/*
+ * For callers that cannot allocate: code between hipStreamBeginCapture and hipStreamEndCapture,
+ * serving loops with a latency budget, harnesses that forbid hipMalloc.  pgcm_encrypt_batch with
+ * the same arguments and the same results, except that it never allocates, frees or waits for an
+ * allocation, in host or device memory: descriptors are staged in pinned buffers the key object
+ * got at pgcm_expand_key, and the kernels' workspace (descriptors, unit maps, per-chunk tag
+ * masks, partial hash sums) is one static device array of PGCM_STATIC_WORKSPACE_BYTES per GPU,
+ * which the GPU holds from the moment the library is loaded until the process ends.
+ * Limits: n <= PGCM_STATIC_MAX_CHUNKS, and descriptors and partial hash sums (1 KiB for every
+ * 16 KiB of payload, never fewer than the batch needs to spread over the whole chip: up to 4 MiB
+ * for a batch of a few megabytes) that fit the array: roughly 100 MB of payload per call.
+ * A batch beyond them is refused with PGCM_ERR_CAPACITY and nothing is enqueued.  (The call
+ * still waits on the host, without allocating, when it is more than four batches ahead of the
+ * GPU.)
+ * Every such call on one GPU, under any key and on any stream, uses the same array: calls whose
+ * GPU work can overlap (different streams without ordering between them) race and give wrong
+ * results; calls on one stream are safe.  The array keeps the last call's contents; what a call
+ * needs at zero it clears itself.  pgcm_free_key wipes the array if the key used it.
+ */
+#define PGCM_STATIC_WORKSPACE_BYTES ((size_t)8 << 20)
+#define PGCM_STATIC_MAX_CHUNKS ((size_t)1024)
+int pgcm_encrypt_batch_static(pgcm_key_t *key, size_t n, const uint8_t *ivs,
+                              const void *const *aad, const uint32_t *aad_len,
+                              const void *const *src, const uint64_t *len, void *const *dst,
+                              uint8_t *tags, void *hip_stream);
 
 /*
  * Prepares the key's context for `hip_stream` (section 5.1: the transport knows the sizes of the

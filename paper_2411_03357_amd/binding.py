@@ -10,7 +10,7 @@ _lib = None
 
 EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_encrypt_batch",
            "pgcm_decrypt_verify_batch", "pgcm_encrypt_batch_iv", "pgcm_decrypt_verify_batch_iv",
-           "pgcm_reserve", "pgcm_describe_schedule",
+           "pgcm_encrypt_batch_static", "pgcm_reserve", "pgcm_describe_schedule",
            "pgcm_encrypt_batch_keys", "pgcm_decrypt_verify_batch_keys",
            "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_units", "pgcm_unit_bytes",
            "pgcm_batch_unit_bytes", "pgcm_set_unit_bytes", "pgcm_key_tables_bytes",
@@ -48,6 +48,8 @@ def load_library():
     lib.pgcm_free_key.restype = None
     lib.pgcm_encrypt_batch.argtypes = [vp, sz, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.pgcm_encrypt_batch.restype = C.c_int
+    lib.pgcm_encrypt_batch_static.argtypes = [vp, sz, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.pgcm_encrypt_batch_static.restype = C.c_int
     lib.pgcm_reserve.argtypes = [vp, vp, sz, C.c_uint64]
     lib.pgcm_reserve.restype = C.c_int
     lib.pgcm_describe_schedule.argtypes = [sz, vp, C.c_uint32, C.c_uint32, vp, vp, sz]
@@ -197,6 +199,24 @@ def encrypt_batch(key: Key, ivs, aad, aad_len, src, length, dst, tags, stream=No
             _addr(len_a), _addr(dst_a), _dev_ptr(tags), _stream_handle(stream)))
         return
     _check(load_library().pgcm_encrypt_batch(
+        key.handle, n, _dev_ptr(ivs), _addr(aad_a), _addr(alen_a), _addr(src_a), _addr(len_a),
+        _addr(dst_a), _dev_ptr(tags), _stream_handle(stream)))
+
+
+STATIC_WORKSPACE_BYTES = 8 << 20   # PGCM_STATIC_WORKSPACE_BYTES
+STATIC_MAX_CHUNKS = 1024           # PGCM_STATIC_MAX_CHUNKS
+
+
+def encrypt_batch_static(key: Key, ivs, aad, aad_len, src, length, dst, tags, stream=None):
+    """pgcm_encrypt_batch_static: pgcm_encrypt_batch that allocates nothing; arguments as for
+    encrypt_batch.  (The arrays this wrapper builds are the caller's side of the call.)"""
+    n = len(length)
+    src_a = _host_array(src, np.uint64, n, "src")
+    dst_a = _host_array(dst, np.uint64, n, "dst")
+    len_a = _host_array(length, np.uint64, n, "length")
+    aad_a = _host_array(aad, np.uint64, n, "aad")
+    alen_a = _host_array(aad_len, np.uint32, n, "aad_len")
+    _check(load_library().pgcm_encrypt_batch_static(
         key.handle, n, _dev_ptr(ivs), _addr(aad_a), _addr(alen_a), _addr(src_a), _addr(len_a),
         _addr(dst_a), _dev_ptr(tags), _stream_handle(stream)))
 

@@ -35,6 +35,10 @@ constexpr int kStages = 4;
 constexpr uint32_t kTimingRing = 256;
 // contexts a key keeps before it starts re-binding the least recently used one to a new stream
 constexpr size_t kMaxContexts = 16;
+// limits of the entry point that allocates nothing (pgcm_encrypt_batch_static)
+constexpr size_t kScratchBytes = PGCM_STATIC_WORKSPACE_BYTES;
+constexpr size_t kFixedMaxChunks = PGCM_STATIC_MAX_CHUNKS;
+constexpr int kMaxDevices = 64;
 // a fold level with at most this many items (one workgroup each fits the chip at once) is folded
 // by the tree kernel
 constexpr uint32_t kFoldTreeMaxItems = 256;
@@ -137,6 +141,10 @@ struct pgcm_key {
     std::mutex mu;                 // guards `contexts` and the binding fields of each context
     std::vector<Context*> contexts;
     uint64_t use_tick = 0;
+    // the context of the entry point that allocates nothing: fixed staging buffers, and the
+    // device's static scratch array as workspace
+    Context fixed;
+    bool fixed_used = false;
     // optional timing of the bulk kernel alone (pgcm_set_timing)
     // a ring of event pairs, one pair per timed launch, so that a run of batches can be timed
     // without a host wait in between
@@ -145,7 +153,30 @@ struct pgcm_key {
     hipEvent_t bulk_start[kTimingRing] = {}, bulk_stop[kTimingRing] = {};
 };
 
+// Device workspace of the entry point that allocates nothing: one array per GPU, held from the
+// moment the library is loaded until the process ends, shared by every such call on that GPU.
+// Host code must never pass this name to a kernel: the address the device sees comes from
+// hipGetSymbolAddress (scratch_of_device) and is what the kernels get.
+static __device__ __align__(256) uint8_t scratch[kScratchBytes];
+
 namespace {
+
+std::mutex g_scratch_mu;
+uint8_t* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on `device`, which must be the current device; looked up once per device.
+int scratch_of_device(int device, uint8_t** out) {
+    if (device < 0 || device >= kMaxDevices) return PGCM_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_ptr[device] == nullptr) {
+        void* p = nullptr;
+        PGCM_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (p == nullptr) return PGCM_ERR_HIP;
+        g_scratch_ptr[device] = static_cast<uint8_t*>(p);
+    }
+    *out = g_scratch_ptr[device];
+    return PGCM_OK;
+}
 
 int create_stage_events(Context* c) {
     for (int s = 0; s < kStages; ++s)
@@ -274,6 +305,7 @@ int acquire_context(pgcm_key* key, hipStream_t stream, Context** out) {
 }
 
 void release_context(pgcm_key* key, Context* c) {
+    if (c == &key->fixed) return;
     std::lock_guard<std::mutex> lock(key->mu);
     c->in_call = false;
 }
@@ -340,6 +372,7 @@ struct BatchArgs {
     uint8_t* tags;
     uint8_t* ok;
     hipStream_t stream;
+    bool fixed = false;  // run in the key's fixed context: allocate nothing, refuse what does not fit
 
     size_t at(size_t k) const { return order ? order[k] : k; }
 };
@@ -479,6 +512,15 @@ bool worst_case_sizes(uint32_t forced_unit_power, uint32_t wave_slots, size_t n,
     return true;
 }
 
+// Staging bytes any batch can need that passes the fixed context's other limits: at most
+// kFixedMaxChunks descriptors and unit-map entries, and a coarse map and fold list for at most
+// kScratchBytes / 1024 partial sets.
+constexpr size_t kFixedStageBytes = round_up(
+    (sizeof(ChunkDesc) * kFixedMaxChunks + 256) + (4 * (kFixedMaxChunks + 1) + 256) +
+        (4 * (kScratchBytes / 1024 / 16 + 1) + 256) +
+        (sizeof(FoldItem) * (kScratchBytes / 1024) + 256),
+    4096);  // the staging buffers are slices of one block: each must start aligned
+
 // Descriptors, unit maps and fold lists of the batch, written into the staging buffer.
 void fill_schedule(const BatchArgs& a, const BatchPlan& p, const WorkLayout& w, uint8_t* stage) {
     ChunkDesc* h_desc = reinterpret_cast<ChunkDesc*>(stage + w.desc);
@@ -572,6 +614,8 @@ int run_small_batch(pgcm_key* key, Context* ctx, const BatchArgs& a, bool wide) 
 int run_unit_batch(pgcm_key* key, Context* ctx, const BatchArgs& a, const BatchPlan& p) {
     const uint32_t nchunks = (uint32_t)a.n;
     const WorkLayout w = lay_out(a, p);
+    if (!ctx->growable && (a.n > kFixedMaxChunks || w.bytes > ctx->work_cap))
+        return PGCM_ERR_CAPACITY;
     const int s = ctx->next_stage;
     int rc = ensure_stage(ctx, s, w.upload_bytes);
     if (rc != PGCM_OK) return rc;
@@ -581,9 +625,9 @@ int run_unit_batch(pgcm_key* key, Context* ctx, const BatchArgs& a, const BatchP
     uint32_t* d_counter = reinterpret_cast<uint32_t*>(ctx->work + w.counter);
     {
         // the unit counter is left at zero by the last kernel of every batch; it only needs
-        // clearing when the workspace is new, the counter's place in it has moved, or an earlier
-        // batch was cut short
-        const bool clear = ctx->counter_at != d_counter || ctx->counter_dirty;
+        // clearing when the workspace is new, the counter's place in it has moved, an earlier
+        // batch was cut short, or the workspace is shared with other keys (the fixed context)
+        const bool clear = ctx->counter_at != d_counter || ctx->counter_dirty || !ctx->growable;
         ctx->counter_at = d_counter;
         ctx->counter_dirty = true;
         const uint32_t n16 = (uint32_t)(w.upload_bytes / 16);
@@ -669,8 +713,14 @@ int run_batch(pgcm_key* key, const BatchArgs& a) {
     PGCM_HIP(hipGetDevice(&cur_device));
     if (cur_device != key->device) return PGCM_ERR_ARG;  // the key lives on another GPU
     Context* ctx = nullptr;
-    rc = acquire_context(key, a.stream, &ctx);
-    if (rc != PGCM_OK) return rc;
+    if (a.fixed) {
+        if (a.n > kFixedMaxChunks) return PGCM_ERR_CAPACITY;
+        ctx = &key->fixed;
+        key->fixed_used = true;
+    } else {
+        rc = acquire_context(key, a.stream, &ctx);
+        if (rc != PGCM_OK) return rc;
+    }
     if (p.all_one_row)
         rc = run_small_batch(key, ctx, a, false);
     else if (p.all_small && a.n <= kSmallWideMaxChunks)
@@ -750,6 +800,23 @@ int pgcm_expand_key_bytes(const uint8_t* key, uint32_t key_bytes, void* hip_stre
         if (hip_failed(hipMalloc((void**)&k->tables, sizeof(KeyTables)))) { rc = PGCM_ERR_NOMEM; break; }
         if (hip_failed(hipMalloc((void**)&d_key, 32))) { rc = PGCM_ERR_NOMEM; break; }
         k->wave_slots = (uint32_t)k->num_cu * kWavesPerGroup;
+        // the fixed context: one pinned block cut into the staging buffers, the device's static
+        // scratch array as workspace; nothing of it ever grows
+        k->fixed.growable = false;
+        if ((rc = create_stage_events(&k->fixed)) != PGCM_OK) break;
+        {
+            void* p = nullptr;
+            if (hip_failed(hipHostMalloc(&p, kStages * kFixedStageBytes, hipHostMallocDefault))) {
+                rc = PGCM_ERR_NOMEM;
+                break;
+            }
+            for (int s = 0; s < kStages; ++s) {
+                k->fixed.stage[s] = static_cast<uint8_t*>(p) + (size_t)s * kFixedStageBytes;
+                k->fixed.stage_cap[s] = kFixedStageBytes;
+            }
+        }
+        if ((rc = scratch_of_device(k->device, &k->fixed.work)) != PGCM_OK) break;
+        k->fixed.work_cap = kScratchBytes;
         // a pageable copy of at most 32 bytes: staged by the runtime, complete on return for this size
         if (hip_failed(hipMemcpyAsync(d_key, key, key_bytes, hipMemcpyHostToDevice, stream))) { rc = PGCM_ERR_HIP; break; }
         k->rounds = (int)(key_bytes / 4 + 6);
@@ -778,6 +845,15 @@ void pgcm_free_key(pgcm_key_t* k) {
         destroy_context(c, true);
         delete c;
     }
+    // the fixed context: its staging buffers are slices of one allocation, and its workspace is
+    // the device's static array, which is wiped (it holds tag masks and partial hashes) but stays
+    if (k->fixed.work && k->fixed_used) (void)hipMemset(k->fixed.work, 0, kScratchBytes);
+    if (k->fixed.stage[0]) {
+        memset(k->fixed.stage[0], 0, kStages * kFixedStageBytes);
+        (void)hipHostFree(k->fixed.stage[0]);
+    }
+    for (int s = 0; s < kStages; ++s)
+        if (k->fixed.stage_done[s]) (void)hipEventDestroy(k->fixed.stage_done[s]);
     for (uint32_t i = 0; i < kTimingRing; ++i) {
         if (k->bulk_start[i]) (void)hipEventDestroy(k->bulk_start[i]);
         if (k->bulk_stop[i]) (void)hipEventDestroy(k->bulk_stop[i]);
@@ -797,6 +873,16 @@ int pgcm_encrypt_batch_iv(pgcm_key_t* key, size_t n, const uint8_t* ivs, uint32_
                           const uint64_t* len, void* const* dst, uint8_t* tags, void* hip_stream) {
     return run_batch(key, BatchArgs{false, n, nullptr, ivs, iv_bytes, aad, aad_len, src, len, dst,
                                     tags, nullptr, (hipStream_t)hip_stream});
+}
+
+int pgcm_encrypt_batch_static(pgcm_key_t* key, size_t n, const uint8_t* ivs,
+                              const void* const* aad, const uint32_t* aad_len,
+                              const void* const* src, const uint64_t* len, void* const* dst,
+                              uint8_t* tags, void* hip_stream) {
+    BatchArgs a{false, n, nullptr, ivs, 12, aad, aad_len, src, len, dst, tags, nullptr,
+                (hipStream_t)hip_stream};
+    a.fixed = true;
+    return run_batch(key, a);
 }
 
 int pgcm_reserve(pgcm_key_t* key, void* hip_stream, size_t n_max, uint64_t payload_bytes_max) {
@@ -869,7 +955,7 @@ const char* pgcm_strerror(int status) {
         case PGCM_ERR_NOMEM: return "out of host or device memory";
         case PGCM_ERR_HIP: return "a HIP runtime call failed";
         case PGCM_ERR_BUSY: return "every buffer of the pool is held";
-        case PGCM_ERR_CAPACITY: return "a buffer of fixed size is too small for what was asked";
+        case PGCM_ERR_CAPACITY: return "the batch needs more than the fixed buffers of an entry point that does not allocate";
         default: return "unknown status";
     }
 }
