@@ -15,6 +15,11 @@
  * only counts transfers does (section 4.1).
  *
  * One pipe is used by one thread with one stream.  Status codes are those of pgcm.h.
+ * A call that is refused for its arguments changes nothing.  A call that fails later, while the
+ * pipe is carrying out what the state machine decided (an allocation or a HIP call inside the
+ * batch calls), leaves the pipe FAILED: the state machine has counted transfers that never went
+ * on the wire, so every later call returns that same status and does nothing; destroy the pipe,
+ * and re-establish the IV with the peer (as after any lost transfer) before creating another.
  */
 #ifndef PGCM_PIPE_H
 #define PGCM_PIPE_H

@@ -72,9 +72,11 @@ class SequencerOracle:
         """the application asks for `chunk` = (address, length) to be transferred"""
         addr, length = chunk
         if length < self.threshold:
-            # small transfer: encrypted on the spot with the current IV
+            # small transfer: encrypted on the spot with the current IV, which may bring the IV
+            # to that of a held request
             self.log.append(("now", chunk, self.iv_cur))
             self.iv_cur += 1
+            self._release_pending()
             self._drop_stale()
             return
         self._note_swap_in(chunk)
@@ -91,6 +93,7 @@ class SequencerOracle:
                          if any(c == pc for pc, _ in self.pending)}
             self.log.append(("now", chunk, self.iv_cur))
             self.iv_cur += 1
+            self._release_pending()
             self._drop_stale()
         elif iv == self.iv_cur:
             del self.spec[chunk]
@@ -103,20 +106,22 @@ class SequencerOracle:
         self._speculate()
 
     def sync(self):
-        """end of a batch: held requests are committed in IV order, NOPs fill the gaps"""
-        for chunk, iv in sorted(self.pending, key=lambda e: e[1]):
-            if iv < self.iv_cur:
-                # overtaken while waiting: its IV is gone
-                self.spec.pop(chunk, None)
-                self.log.append(("drop", chunk, iv))
-                self.log.append(("now", chunk, self.iv_cur))
-                self.iv_cur += 1
-                continue
+        """end of a batch: held requests whose IV still lies ahead are committed in IV order,
+        NOPs fill the gaps (inside a batch the order is free: swap re-ordering); those whose IV
+        the transfers of the batch have passed are encrypted afresh after them"""
+        ahead = sorted((e for e in self.pending if e[1] >= self.iv_cur), key=lambda e: e[1])
+        passed = sorted((e for e in self.pending if e[1] < self.iv_cur), key=lambda e: e[1])
+        for chunk, iv in ahead:
             while self.iv_cur < iv:
                 self.log.append(("nop", self.iv_cur))
                 self.iv_cur += 1
             del self.spec[chunk]
             self.log.append(("send", chunk, iv))
+            self.iv_cur += 1
+        for chunk, iv in passed:
+            self.spec.pop(chunk, None)
+            self.log.append(("drop", chunk, iv))
+            self.log.append(("now", chunk, self.iv_cur))
             self.iv_cur += 1
         self.pending = []
         self._drop_stale()

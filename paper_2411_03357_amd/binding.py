@@ -410,8 +410,10 @@ class _SeqAction(C.Structure):
                 ("len", C.c_uint64), ("iv", C.c_uint64)]
 
 
-def _seq_lib():
-    lib = load_library()
+def _seq_lib(lib=None):
+    """declares the pgcm_seq_* entry points on the library (or on another build of the host-only
+    sequencer handed in as a ctypes.CDLL)"""
+    lib = load_library() if lib is None else lib
     if not getattr(lib, "_seq_bound", False):
         vp = C.c_void_p
         lib.pgcm_seq_create.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint32,
@@ -437,8 +439,10 @@ def _seq_lib():
 class Sequencer:
     """pgcm_seq_t: events in, actions out (tuples (kind, (addr, len), iv); NOPs are (kind, iv))"""
 
-    def __init__(self, iv_start=0, depth=4, leeway=0, threshold=128 * 1024, history_limit=512):
-        self._lib = _seq_lib()
+    def __init__(self, iv_start=0, depth=4, leeway=0, threshold=128 * 1024, history_limit=512,
+                 lib=None):
+        self._h = None
+        self._lib = _seq_lib(lib)
         h = C.c_void_p()
         _check(self._lib.pgcm_seq_create(iv_start, depth, leeway, threshold, history_limit,
                                          C.byref(h)))

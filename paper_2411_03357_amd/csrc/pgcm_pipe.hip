@@ -40,6 +40,10 @@ struct pgcm_pipe {
     uint32_t iv_pos = 0;
     // PRE actions wait here until something else has to happen, so that they go out as one batch
     std::vector<uint32_t> pending_pre;
+    // Set when carrying out the state machine's actions failed half way: the state machine has
+    // then moved on (its IV, what it believes is kept) while the slots and the wire have not, so
+    // nothing it says afterwards can be trusted.  Every later call returns this status.
+    int failed = PGCM_OK;
 
     uint8_t* slot_cipher(size_t i) const { return cipher_mem + i * slot_bytes; }
     uint8_t* slot_tag(size_t i) const { return tag_mem + 16 * i; }
@@ -125,7 +129,17 @@ int find_slot(const pgcm_pipe* p, const pgcm_seq_action& a) {
     return -1;
 }
 
+int carry_out_actions(pgcm_pipe* p, hipStream_t stream);
+
+// Carries out every action the state machine has queued.  A failure in the middle leaves the
+// pipe unusable (see pgcm_pipe::failed).
 int carry_out(pgcm_pipe* p, hipStream_t stream) {
+    const int rc = carry_out_actions(p, stream);
+    if (rc != PGCM_OK) p->failed = rc;
+    return rc;
+}
+
+int carry_out_actions(pgcm_pipe* p, hipStream_t stream) {
     pgcm_seq_action acts[64];
     for (;;) {
         const size_t n = pgcm_seq_take_actions(p->seq, acts, 64);
@@ -184,6 +198,7 @@ int carry_out(pgcm_pipe* p, hipStream_t stream) {
 
 int check_chunk_arg(const pgcm_pipe* p, const void* addr, uint64_t len) {
     if (p == nullptr) return PGCM_ERR_ARG;
+    if (p->failed != PGCM_OK) return p->failed;
     if (len > p->cfg.max_chunk_bytes) return PGCM_ERR_LEN;
     if (len != 0 && addr == nullptr) return PGCM_ERR_ARG;
     if ((uintptr_t)addr & 15) return PGCM_ERR_ALIGN;
@@ -262,6 +277,7 @@ int pgcm_pipe_swap_out(pgcm_pipe_t* p, const void* addr, uint64_t len, void* hip
 
 int pgcm_pipe_notify_write(pgcm_pipe_t* p, const void* addr, uint64_t len, void* hip_stream) {
     if (p == nullptr) return PGCM_ERR_ARG;
+    if (p->failed != PGCM_OK) return p->failed;
     int rc = pgcm_seq_notify_write(p->seq, (uint64_t)(uintptr_t)addr, len);
     if (rc != PGCM_OK) return rc;
     return carry_out(p, (hipStream_t)hip_stream);
@@ -277,6 +293,7 @@ int pgcm_pipe_request(pgcm_pipe_t* p, const void* addr, uint64_t len, void* hip_
 
 int pgcm_pipe_sync(pgcm_pipe_t* p, void* hip_stream) {
     if (p == nullptr) return PGCM_ERR_ARG;
+    if (p->failed != PGCM_OK) return p->failed;
     int rc = pgcm_seq_sync(p->seq);
     if (rc != PGCM_OK) return rc;
     return carry_out(p, (hipStream_t)hip_stream);

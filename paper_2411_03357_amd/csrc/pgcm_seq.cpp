@@ -231,9 +231,11 @@ int pgcm_seq_request(pgcm_seq_t* s, uint64_t addr, uint64_t len) {
     try {
         const Chunk c{addr, len};
         if (len < s->threshold) {
-            // small transfer: never pipelined, takes the current IV
+            // small transfer: never pipelined, takes the current IV (which may bring the wire to
+            // the IV a held request waits for)
             s->emit(PGCM_SEQ_NOW, c, s->iv_cur);
             ++s->iv_cur;
+            s->release_held();
             s->drop_passed();
             return PGCM_OK;
         }
@@ -251,6 +253,7 @@ int pgcm_seq_request(pgcm_seq_t* s, uint64_t addr, uint64_t len) {
             }
             s->emit(PGCM_SEQ_NOW, c, s->iv_cur);
             ++s->iv_cur;
+            s->release_held();
             s->drop_passed();
         } else if (it->second == s->iv_cur) {
             s->kept.erase(it);
@@ -270,14 +273,16 @@ int pgcm_seq_request(pgcm_seq_t* s, uint64_t addr, uint64_t len) {
 int pgcm_seq_sync(pgcm_seq_t* s) {
     if (s == nullptr) return PGCM_ERR_ARG;
     try {
+        // Inside a batch the order is free (section 5.3, swap re-ordering): held requests whose
+        // IV still lies ahead are committed first, in IV order, NOPs filling the gaps, so that
+        // none of them is overtaken by the others; those the wire had already passed are
+        // encrypted afresh after them.
         std::stable_sort(s->held.begin(), s->held.end(),
                          [](const auto& a, const auto& b) { return a.second < b.second; });
+        std::vector<std::pair<Chunk, uint64_t>> late;
         for (const auto& h : s->held) {
             if (h.second < s->iv_cur) {
-                s->kept.erase(h.first);
-                s->emit(PGCM_SEQ_DROP, h.first, h.second);
-                s->emit(PGCM_SEQ_NOW, h.first, s->iv_cur);
-                ++s->iv_cur;
+                late.push_back(h);
                 continue;
             }
             while (s->iv_cur < h.second) {
@@ -286,6 +291,12 @@ int pgcm_seq_sync(pgcm_seq_t* s) {
             }
             s->kept.erase(h.first);
             s->emit(PGCM_SEQ_SEND, h.first, h.second);
+            ++s->iv_cur;
+        }
+        for (const auto& h : late) {
+            s->kept.erase(h.first);
+            s->emit(PGCM_SEQ_DROP, h.first, h.second);
+            s->emit(PGCM_SEQ_NOW, h.first, s->iv_cur);
             ++s->iv_cur;
         }
         s->held.clear();
