@@ -4,7 +4,10 @@
 A step is one pass of the whole path over one batch: pgcm_encrypt_batch followed by
 pgcm_decrypt_verify_batch of the same chunks, payload resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+`value` and `roofline` are quoted on the KV-cache swap shape (configuration 2); `configs` holds
+the same measurement for all five configurations.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--only] [--no-cpu-baseline]
 """
 import argparse
 import json
@@ -14,15 +17,15 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit op per lane-clock
 LDS_PEAK_GCYCLES = 256 * 2.4               # 256 CUs, one LDS pipe each, 2.4 GHz: port cycles per ns
 
 # Hardware counters of one bulk_kernel launch on the default workload, taken with
-# `rocprofv3 --pmc` (summaries and commands: profiles/).  They describe the kernel sources whose
-# hash is given; once the sources change they no longer apply and bench.py reports null.
+# `rocprofv3 --pmc` (summaries and commands: profiles/).  They describe the kernel sources
+# (pgcm_kernels.hip and the two headers it includes) whose hash is given; once those change the
+# counters no longer apply and bench.py reports null.
 COUNTERS = {
     "sources_sha256": "fe8984312c3d91b1d28d5afbb62eab3deef9dce2e15b2a13524384063f83da38",
     "workload": "c2_opt13b_kv_4096x320KiB",
@@ -33,13 +36,15 @@ COUNTERS = {
     "valu_wave_instructions": 609253376.0,  # SQ_INSTS_VALU per launch
     "lds_wave_instructions": 321931264.0,   # SQ_INSTS_LDS per launch
     "lds_active_cycles": 728154112.0,   # SQ_LDS_IDX_ACTIVE per launch, summed over the 256 CUs
+    "gui_active_cycles": 1.0,           # GRBM_GUI_ACTIVE per launch ...
+    "pmc_launch_ms": 1.0,               # ... and the launch's duration in that same run
 }
 
 
 def sources_sha256():
     import hashlib
     h = hashlib.sha256()
-    for f in ("pgcm_types.h", "pgcm_kernels.h", "pgcm_kernels.hip", "pgcm_host.hip"):
+    for f in ("pgcm_types.h", "pgcm_kernels.h", "pgcm_kernels.hip"):
         with open(os.path.join(ROOT, "paper_2411_03357_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()
@@ -186,12 +191,90 @@ def pipeline_bench(args):
         "traces": out}))
 
 
+def measure_workload(pgcm, torch, w, args, steps, warmup, headline):
+    """One workload through the library's own timing loop.  Returns (results dict, batch, key);
+    the caller frees them.  steps passes (encrypt + decrypt-verify) are timed by the host clock,
+    synchronised on both sides, with a pair of events around every bulk kernel; then each
+    direction alone."""
+    import numpy as np
+    from device_batch import DeviceBatch, apply_tampers
+
+    key = pgcm.expand_key(w.key) if w.key.size == 32 else pgcm.expand_key_bytes(w.key)
+    pgcm.set_unit_bytes(key, args.unit_bytes)
+    b = DeviceBatch(w, w.payload_device())
+    if args.host_bounce:
+        b.cipher = torch.zeros(w.total_bytes, dtype=torch.uint8, pin_memory=True)
+    payload = w.payload_bytes
+    pgcm.reserve(key, w.n, payload, torch.cuda.current_stream())
+    b.measure(key, warmup)
+    if headline and args.calibrate_copy:
+        scratch = torch.empty_like(b.plain)
+        scratch.copy_(b.plain)          # reads and writes w.total_bytes each
+        torch.cuda.synchronize()
+        del scratch
+
+    pgcm.set_timing(key, True)
+    ms = b.measure(key, steps)
+    launches = pgcm.bulk_kernel_ms_history(key, 2 * steps)
+    pgcm.set_timing(key, False)
+    assert len(launches) == min(2 * steps, 256) and len(launches) % 2 == 0
+    assert bool((b.ok == 1).all()) and torch.equal(b.back, b.plain), "round trip failed"
+
+    # each direction alone, again by the library's loop; a series starts with untimed passes
+    # because the checks in between leave the GPU idle long enough for its clocks to drop.
+    # Decrypt-verify runs on the workload's own ciphertext: with its tampering where it has any
+    # (the rejected chunks are wiped inside the timed calls)
+    reps = max(5, min(steps, 20))
+    b.measure(key, min(warmup, 12), direction=1)
+    enc_ms = b.measure(key, reps, direction=1) / reps
+    rejected = sorted({t.chunk for t in w.tampers})
+    if rejected:
+        apply_tampers(w, b.cipher, b.tags)
+    b.measure(key, min(warmup, 12), direction=2)
+    dec_ms = b.measure(key, reps, direction=2) / reps
+    if rejected:
+        ok = b.ok.cpu().numpy()
+        assert sorted(np.flatnonzero(ok == 0).tolist()) == rejected, "verdicts"
+
+    kern_avg_ms = sum(launches) / len(launches)
+    # algorithmic HBM bytes of one launch: every payload byte read once and written once, plus
+    # per chunk its IV, tag (16), AAD and descriptor (64); what the implementation moves on
+    # top of that (1 KiB of partial hash sums per 16 KiB unit) is overhead, not counted here
+    aad_total = 0 if w.aad is None else int(w.aad.size)
+    algo_bytes = 2 * payload + w.n * (int(w.ivs.shape[1]) + 16 + 64) + aad_total
+    achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
+    res = {"workload": w.name, "chunks": w.n, "payload_bytes": payload,
+           "value": round(2.0 * payload * steps / (ms * 1e-3) / 1e9, 2), "unit": "GB/s",
+           "steps": steps, "ms_per_step": round(ms / steps, 4),
+           "enc_GBps": round(payload / (enc_ms * 1e-3) / 1e9, 2),
+           "dec_verify_GBps": round(payload / (dec_ms * 1e-3) / 1e9, 2),
+           "chunks_rejected_in_dec_verify": len(rejected),
+           "unit_bytes": args.unit_bytes or pgcm.batch_unit_bytes(w.lens),
+           "avg_launch_ms": round(kern_avg_ms, 4),
+           "roofline_frac": round(achieved / HBM_PEAK_GBS, 4)}
+    detail = {"launches": launches, "algo_bytes": algo_bytes, "achieved": achieved,
+              "kern_avg_ms": kern_avg_ms, "reps": reps}
+    return res, detail, b, key
+
+
+def timed_kernel_name(w):
+    longest = int(w.lens.max())
+    if longest <= 1008:
+        return "small_kernel (one wavefront per chunk: the whole invocation)"
+    if longest <= 8192 and w.n <= 512:
+        return "small_wide_kernel (one workgroup per chunk: the whole invocation)"
+    return "bulk_kernel (CTR keystream + XOR + GHASH)"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="the workload `value` and `roofline` are quoted on (default: the KV-cache "
+                         "swap shape); the other four are measured too, into `configs`")
+    ap.add_argument("--only", action="store_true", help="measure --config alone")
     ap.add_argument("--key-bytes", type=int, default=32, choices=[16, 24, 32],
                     help="AES key length; the headline (and the paper's transport) is 32")
     ap.add_argument("--iv-bytes", type=int, default=12,
@@ -224,86 +307,37 @@ def main():
 
     import workloads
     import paper_2411_03357_amd as pgcm
-    from gpu_harness import DeviceBatch
 
     torch.cuda.set_device(0)
-    w = workloads.FULL[args.config]()
-    headline_cipher = args.key_bytes == 32 and args.iv_bytes == 12
-    if not headline_cipher:
-        w = workloads.with_cipher(w, args.key_bytes, args.iv_bytes)
-    key = pgcm.expand_key(w.key) if args.key_bytes == 32 else pgcm.expand_key_bytes(w.key)
-    pgcm.set_unit_bytes(key, args.unit_bytes)
-    b = DeviceBatch(w, w.payload_device())
-    if args.host_bounce:
-        b.cipher = torch.zeros(w.total_bytes, dtype=torch.uint8, pin_memory=True)
+
+    def workload(cfg):
+        w = workloads.FULL[cfg]()
+        if not (args.key_bytes == 32 and args.iv_bytes == 12):
+            w = workloads.with_cipher(w, args.key_bytes, args.iv_bytes)
+        return w
+
+    w = workload(args.config)
+    res, det, b, key = measure_workload(pgcm, torch, w, args, args.steps, args.warmup, True)
     payload = w.payload_bytes
-    stream = torch.cuda.current_stream()
-
-    def step():
-        b.encrypt(key)
-        b.decrypt(key)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    if args.calibrate_copy:
-        scratch = torch.empty_like(b.plain)
-        scratch.copy_(b.plain)          # reads and writes w.total_bytes each
-        torch.cuda.synchronize()
-        del scratch
-
-    # whole-path timing: host clock around K steps, synchronised on both sides.  Inside the timed
-    # region the library also records a pair of HIP events around every bulk kernel, on the
-    # stream it launches on (no host wait in between); they are read after the region.
-    pgcm.set_timing(key, True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    value = 2.0 * payload * args.steps / dt / 1e9
-    launches = pgcm.bulk_kernel_ms_history(key, 2 * args.steps)
-    pgcm.set_timing(key, False)
-    assert len(launches) == min(2 * args.steps, 256) and len(launches) % 2 == 0
-    kern = {"enc": launches[0::2], "dec": launches[1::2]}      # a step is encrypt, then decrypt
-    assert bool((b.ok == 1).all()) and torch.equal(b.back, b.plain), "round trip failed"
-
-    # per-direction whole-call timing with events on the launch stream; every series starts
-    # with untimed calls, because the checks in between leave the GPU idle long enough for its
-    # clocks to drop (the first ten launches after 100 ms of idling run up to 20 % slower)
-    def timed_calls(fn, reps):
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range(reps)]
-        for _ in range(min(args.warmup, 12)):
-            fn(key)
-        for s, e in ev:
-            s.record(stream)
-            fn(key)
-            e.record(stream)
-        torch.cuda.synchronize()
-        return sorted(s.elapsed_time(e) for s, e in ev)
-
-    reps = max(5, min(args.steps, 20))
-    enc_ms = timed_calls(b.encrypt, reps)
-    dec_ms = timed_calls(b.decrypt, reps)
+    launches, achieved, kern_avg_ms = det["launches"], det["achieved"], det["kern_avg_ms"]
+    kern = {"enc": launches[0::2], "dec": launches[1::2]}      # a pass is encrypt, then decrypt
 
     # what a plain device copy of the same buffer reaches on this machine, in the same run: the
     # achievable ceiling for a kernel that reads and writes every payload byte once
-    copy_ms = None
+    copy_gbs = None
     if not args.host_bounce:
-        copy_ms = timed_calls(lambda _key: b.back.copy_(b.plain), reps)
-        b.decrypt(key)                       # b.back holds the decrypted batch again
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(det["reps"])]
+        for _ in range(5):
+            b.back.copy_(b.plain)
+        for s, e in ev:
+            s.record()
+            b.back.copy_(b.plain)
+            e.record()
         torch.cuda.synchronize()
+        copy_ms = sorted(s.elapsed_time(e) for s, e in ev)
+        copy_gbs = 2.0 * w.total_bytes / (copy_ms[len(copy_ms) // 2] * 1e-3) / 1e9
 
-    kern_avg_ms = sum(launches) / len(launches)
-    # algorithmic HBM bytes of one launch: every payload byte read once and written once, plus
-    # per chunk its IV (12), tag (16), AAD and descriptor (64); what the implementation moves on
-    # top of that (1 KiB of partial hash sums per 16 KiB unit) is overhead, not counted here
-    aad_total = 0 if w.aad is None else int(w.aad.size)
-    algo_bytes = 2 * payload + w.n * (args.iv_bytes + 16 + 64) + aad_total
-    achieved = algo_bytes / (kern_avg_ms * 1e-3) / 1e9
     traffic = None
     alu = None
     lds = None
@@ -311,53 +345,54 @@ def main():
             and not args.host_bounce and args.unit_bytes == 0):
         traffic = int(1024 * (COUNTERS["fetch_size_kib"] * COUNTERS["fetch_scale"] +
                               COUNTERS["write_size_kib"] * COUNTERS["write_scale"]))
+        # the clock the chip ran at under this kernel, as measured in the counter run:
+        # GRBM_GUI_ACTIVE (cycles of the graphics clock while the launch was in flight) over the
+        # launch's duration in the same run
+        clock_ghz = COUNTERS["gui_active_cycles"] / (COUNTERS["pmc_launch_ms"] * 1e-3) / 1e9
         lane_ops = COUNTERS["valu_wave_instructions"] * 64
         alu_achieved = lane_ops / (kern_avg_ms * 1e-3) / 1e12
         alu = {"bound": "alu", "achieved": round(alu_achieved, 2), "peak": round(VALU_PEAK_TOPS, 2),
                "unit": "T 32-bit lane-ops/s", "frac": round(alu_achieved / VALU_PEAK_TOPS, 4),
+               "measured_clock_GHz": round(clock_ghz, 3),
+               "frac_at_measured_clock": round(alu_achieved / (256 * 64 * clock_ghz / 1e3), 4),
                "valu_ops_per_payload_byte": round(lane_ops / payload, 2),
                "lds_lookups_per_payload_byte": round(COUNTERS["lds_wave_instructions"] * 64 / payload, 2)}
         # the resource that binds: cycles in which a CU's LDS pipe is serving lookups (a 64-lane
-        # ds_read_b32 holds it for 2 cycles, a ds_read_b128 for 4), against one pipe per CU at
-        # the nominal clock
+        # ds_read_b32 holds it for 2 cycles, a ds_read_b128 for 4), against one pipe per CU
         lds_achieved = COUNTERS["lds_active_cycles"] / (kern_avg_ms * 1e-3) / 1e9
         lds = {"bound": "lds", "achieved": round(lds_achieved, 1), "peak": round(LDS_PEAK_GCYCLES, 1),
                "unit": "G LDS-pipe cycles/s", "frac": round(lds_achieved / LDS_PEAK_GCYCLES, 4),
+               "measured_clock_GHz": round(clock_ghz, 3),
+               "frac_at_measured_clock": round(lds_achieved / (256 * clock_ghz), 4),
                "lds_cycles_per_payload_byte": round(COUNTERS["lds_active_cycles"] / payload, 4)}
 
-    # the launch the library's events bracket (the kernel that touches the payload)
-    longest = int(w.lens.max())
-    if longest <= 1008:
-        timed_kernel = "small_kernel (one wavefront per chunk: the whole invocation)"
-    elif longest <= 8192 and w.n <= 512:
-        timed_kernel = "small_wide_kernel (one workgroup per chunk: the whole invocation)"
-    else:
-        timed_kernel = "bulk_kernel (CTR keystream + XOR + GHASH)"
     out = {
         "metric": "AES-%d-GCM enc / dec+verify GB/s on 1 MI355X; %% of HBM roofline"
                   % (8 * args.key_bytes),
-        "value": round(value, 2),
+        "value": res["value"],
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": res["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": w.name, "chunks": w.n, "payload_bytes": payload,
-                   "step": "encrypt batch + decrypt-verify batch", "unit_bytes": args.unit_bytes or pgcm.batch_unit_bytes(w.lens),
+                   "step": "encrypt batch + decrypt-verify batch, enqueued by the library's own "
+                           "loop (pgcm_measure_passes)",
+                   "unit_bytes": res["unit_bytes"],
                    "key_bytes": args.key_bytes, "iv_bytes": args.iv_bytes,
                    "ciphertext": "pinned host memory" if args.host_bounce else "device memory"},
-        "enc_GBps": round(payload / (enc_ms[len(enc_ms) // 2] * 1e-3) / 1e9, 2),
-        "dec_verify_GBps": round(payload / (dec_ms[len(dec_ms) // 2] * 1e-3) / 1e9, 2),
-        "pct_hbm_roofline": round(100.0 * 2.0 * value / HBM_PEAK_GBS, 2),
-        "roofline": {"bound": "hbm", "kernel": timed_kernel,
+        "enc_GBps": res["enc_GBps"],
+        "dec_verify_GBps": res["dec_verify_GBps"],
+        "pct_hbm_roofline": round(100.0 * 2.0 * res["value"] / HBM_PEAK_GBS, 2),
+        "roofline": {"bound": "hbm", "kernel": timed_kernel_name(w),
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "algorithmic_bytes": algo_bytes,
+                     "algorithmic_bytes": det["algo_bytes"],
                      "avg_launch_ms": round(kern_avg_ms, 4),
                      "launches_timed": len(launches),
                      "min_launch_ms": round(min(launches), 4),
@@ -368,10 +403,9 @@ def main():
     }
     out["roofline_alu"] = alu
     out["roofline_lds"] = lds
-    if copy_ms is not None:
-        copy_gbs = 2.0 * w.total_bytes / (copy_ms[len(copy_ms) // 2] * 1e-3) / 1e9
+    if copy_gbs is not None:
         out["copy_ceiling"] = {"kind": "device-to-device copy of the payload buffer (HBM read + "
-                                       "write), median of %d" % reps,
+                                       "write), median of %d" % det["reps"],
                                "traffic_GBps": round(copy_gbs, 1),
                                "bulk_kernel_frac_of_copy": round(achieved / copy_gbs, 4)}
     import hashlib
@@ -379,12 +413,33 @@ def main():
     for arr in (w.key, w.ivs, w.lens, w.aad if w.aad is not None else np.zeros(0, np.uint8)):
         h.update(np.ascontiguousarray(arr).tobytes())
     out["inputs_sha256"] = h.hexdigest()    # key, IVs, lengths, AAD (the payload is seeded too)
+    key.free()
+    del b
+    torch.cuda.empty_cache()
+
+    # the other workloads, same measurement with fewer passes, so that one line covers all five
+    configs = {str(args.config): res}
+    if not args.only and not args.host_bounce:
+        for cfg in (1, 2, 3, 4, 5):
+            if cfg == args.config:
+                continue
+            wc = workload(cfg)
+            steps = min(args.steps, 200 if cfg == 1 else 30)
+            rc, _, bc, kc = measure_workload(pgcm, torch, wc, args, steps, min(args.warmup, 10),
+                                             False)
+            rc["timed_kernel"] = timed_kernel_name(wc)
+            configs[str(cfg)] = rc
+            kc.free()
+            del bc
+            torch.cuda.empty_cache()
+    res["timed_kernel"] = timed_kernel_name(w)
+    out["configs"] = {k: configs[k] for k in sorted(configs)}
+
     if not args.no_cpu_baseline:
-        chunks = args.cpu_chunks or max(1, int(40e6 // max(1, int(w.lens.mean()))))
+        chunks = args.cpu_chunks or max(1, int(600e6 // max(1, int(w.lens.mean()))))   # about 15 s
         threads = min(16, os.cpu_count() or 1)
         out["cpu_baseline"] = cpu_baseline(w, chunks, threads)
         out["cpu_libcrypto"] = libcrypto_rates(w)
-    key.free()
     print(json.dumps(out))
 
 

@@ -1,4 +1,6 @@
-"""Runs a workloads.Workload through the GPU library's C ABI (via the Python binding)."""
+"""Lays a workloads.Workload out in device memory and runs it through the GPU library's C ABI
+(via the Python binding): used by the tests, the smoke check and the benchmark.  No cipher
+arithmetic here."""
 import numpy as np
 import torch
 
@@ -62,6 +64,14 @@ class DeviceBatch:
         pgcm.decrypt_verify_batch(key, self.ivs, self.aad_ptrs, self.aad_lens, self.ptrs(src),
                                   self.lens, self.ptrs(dst), tags, self.ok, stream,
                                   iv_bytes=self.iv_bytes)
+
+    def measure(self, key, steps, direction=0, stream=None) -> float:
+        """host milliseconds for `steps` passes over this batch, enqueued by the library's own
+        loop: plain -> cipher -> back (direction 0), plain -> cipher (1), cipher -> back (2)"""
+        return pgcm.measure_passes(key, self.ivs, self.aad_ptrs, self.aad_lens,
+                                   self.ptrs(self.plain), self.lens, self.ptrs(self.cipher),
+                                   self.ptrs(self.back), self.tags, self.ok, steps, direction,
+                                   stream, self.iv_bytes or 12)
 
     def chunk_host(self, buf: torch.Tensor, i: int) -> np.ndarray:
         off, ln = int(self.w.offsets[i]), int(self.w.lens[i])

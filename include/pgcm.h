@@ -306,6 +306,22 @@ int pgcm_set_unit_bytes(pgcm_key_t *key, uint32_t unit_bytes);
  * wrote, or a negative pgcm_status.
  */
 int pgcm_set_timing(pgcm_key_t *key, int enable);
+
+/*
+ * Measurement aid: `steps` passes of the path over one batch, enqueued back to back by a loop
+ * inside the library, so that what is timed is the library and the GPU and not the caller's
+ * language.  A pass is pgcm_encrypt_batch_iv (src -> cipher, tags written) followed by
+ * pgcm_decrypt_verify_batch_iv (cipher -> back, tags read, ok written) when direction is 0, the
+ * first alone when it is 1, the second alone when it is 2 (cipher and tags must then hold a
+ * batch encrypted earlier).  The stream is synchronised before the first pass and after the
+ * last; *host_ms receives the host's wall-clock time between the two.  Arrays as for the _iv
+ * batch calls.  Stops at the first call that fails and returns its status.
+ */
+int pgcm_measure_passes(pgcm_key_t *key, size_t n, const uint8_t *ivs, uint32_t iv_bytes,
+                        const void *const *aad,
+                        const uint32_t *aad_len, const void *const *src, const uint64_t *len,
+                        void *const *cipher, void *const *back, uint8_t *tags, uint8_t *ok,
+                        void *hip_stream, uint32_t steps, int direction, double *host_ms);
 int pgcm_last_bulk_kernel_ms(pgcm_key_t *key, float *ms);
 int64_t pgcm_bulk_kernel_ms_history(pgcm_key_t *key, float *ms, size_t max);
 

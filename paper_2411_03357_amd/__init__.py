@@ -8,5 +8,5 @@ from .binding import (PgcmError, Key, expand_key, expand_key_bytes, encrypt_batc
                       encrypt_batch_keys, decrypt_verify_batch_keys, encrypt_batch_static, reserve,
                       describe_schedule, STATIC_WORKSPACE_BYTES, STATIC_MAX_CHUNKS,
                       plan_units, unit_bytes, batch_unit_bytes, library_path, load_library, set_timing, set_unit_bytes, copy_key_tables,
-                      last_bulk_kernel_ms, bulk_kernel_ms_history, EXPORTS, Sequencer, seq_iv_bytes, SEQ_EXPORTS, BouncePool,
+                      last_bulk_kernel_ms, bulk_kernel_ms_history, measure_passes, EXPORTS, Sequencer, seq_iv_bytes, SEQ_EXPORTS, BouncePool,
                       BOUNCE_EXPORTS, Pipe, Receiver, PIPE_EXPORTS)

@@ -15,7 +15,8 @@ EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_en
            "pgcm_strerror", "pgcm_last_hip_error", "pgcm_plan_units", "pgcm_unit_bytes",
            "pgcm_batch_unit_bytes", "pgcm_set_unit_bytes", "pgcm_key_tables_bytes",
            "pgcm_copy_key_tables",
-           "pgcm_set_timing", "pgcm_last_bulk_kernel_ms", "pgcm_bulk_kernel_ms_history")
+           "pgcm_set_timing", "pgcm_last_bulk_kernel_ms", "pgcm_bulk_kernel_ms_history",
+           "pgcm_measure_passes")
 
 
 class PgcmError(RuntimeError):
@@ -87,6 +88,9 @@ def load_library():
     lib.pgcm_set_timing.restype = C.c_int
     lib.pgcm_last_bulk_kernel_ms.argtypes = [vp, C.POINTER(C.c_float)]
     lib.pgcm_last_bulk_kernel_ms.restype = C.c_int
+    lib.pgcm_measure_passes.argtypes = [vp, sz, vp, C.c_uint32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                        C.c_uint32, C.c_int, C.POINTER(C.c_double)]
+    lib.pgcm_measure_passes.restype = C.c_int
     lib.pgcm_bulk_kernel_ms_history.argtypes = [vp, vp, sz]
     lib.pgcm_bulk_kernel_ms_history.restype = C.c_int64
     _lib = lib
@@ -384,6 +388,25 @@ def bulk_kernel_ms_history(key: Key, max_launches: int = 256):
     if n < 0:
         raise PgcmError(int(n), load_library().pgcm_last_hip_error() if n == -5 else 0)
     return [float(v) for v in out[:n]]
+
+
+def measure_passes(key: Key, ivs, aad, aad_len, src, length, cipher, back, tags, ok, steps,
+                   direction=0, stream=None, iv_bytes=12) -> float:
+    """pgcm_measure_passes -> host milliseconds for `steps` passes (direction 0: encrypt then
+    decrypt-verify, 1: encrypt only, 2: decrypt-verify only)"""
+    n = len(length)
+    src_a = _host_array(src, np.uint64, n, "src")
+    ct_a = _host_array(cipher, np.uint64, n, "cipher")
+    back_a = _host_array(back, np.uint64, n, "back")
+    len_a = _host_array(length, np.uint64, n, "length")
+    aad_a = _host_array(aad, np.uint64, n, "aad")
+    alen_a = _host_array(aad_len, np.uint32, n, "aad_len")
+    ms = C.c_double(0.0)
+    _check(load_library().pgcm_measure_passes(
+        key.handle, n, _dev_ptr(ivs), iv_bytes, _addr(aad_a), _addr(alen_a), _addr(src_a),
+        _addr(len_a), _addr(ct_a), _addr(back_a), _dev_ptr(tags), _dev_ptr(ok), _stream_handle(stream), steps,
+        direction, C.byref(ms)))
+    return float(ms.value)
 
 
 def unit_bytes() -> int:

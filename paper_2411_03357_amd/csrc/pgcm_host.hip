@@ -5,6 +5,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <chrono>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -1074,6 +1075,32 @@ int pgcm_set_timing(pgcm_key_t* key, int enable) {
     }
     key->timing = enable != 0;
     key->timed = 0;
+    return PGCM_OK;
+}
+
+int pgcm_measure_passes(pgcm_key_t* key, size_t n, const uint8_t* ivs, uint32_t iv_bytes,
+                        const void* const* aad,
+                        const uint32_t* aad_len, const void* const* src, const uint64_t* len,
+                        void* const* cipher, void* const* back, uint8_t* tags, uint8_t* ok,
+                        void* hip_stream, uint32_t steps, int direction, double* host_ms) {
+    if (host_ms == nullptr || direction < 0 || direction > 2) return PGCM_ERR_ARG;
+    const hipStream_t stream = (hipStream_t)hip_stream;
+    PGCM_HIP(hipStreamSynchronize(stream));
+    const auto t0 = std::chrono::steady_clock::now();
+    for (uint32_t k = 0; k < steps; ++k) {
+        int rc = PGCM_OK;
+        if (direction != 2)
+            rc = pgcm_encrypt_batch_iv(key, n, ivs, iv_bytes, aad, aad_len, src, len, cipher, tags,
+                                       hip_stream);
+        if (rc == PGCM_OK && direction != 1)
+            rc = pgcm_decrypt_verify_batch_iv(key, n, ivs, iv_bytes, aad, aad_len,
+                                              reinterpret_cast<const void* const*>(cipher), len,
+                                              back, tags, ok, hip_stream);
+        if (rc != PGCM_OK) return rc;
+    }
+    PGCM_HIP(hipStreamSynchronize(stream));
+    *host_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0)
+                   .count();
     return PGCM_OK;
 }
 

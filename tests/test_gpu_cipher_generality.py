@@ -9,7 +9,7 @@ import iv_craft
 import openssl_ref
 import oracle
 import workloads
-from gpu_harness import DeviceBatch, expand
+from device_batch import DeviceBatch, expand
 from test_gpu_parity import _full_parity
 
 import paper_2411_03357_amd as pgcm

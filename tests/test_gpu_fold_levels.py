@@ -11,7 +11,7 @@ import torch
 import openssl_ref
 import oracle
 import workloads
-from gpu_harness import DeviceBatch
+from device_batch import DeviceBatch
 
 import paper_2411_03357_amd as pgcm
 

@@ -22,7 +22,7 @@ import torch
 import openssl_ref
 import oracle
 import workloads
-from gpu_harness import DeviceBatch, apply_tampers
+from device_batch import DeviceBatch, apply_tampers
 
 import paper_2411_03357_amd as pgcm
 

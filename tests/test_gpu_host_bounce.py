@@ -7,7 +7,7 @@ import torch
 
 import oracle
 import workloads
-from gpu_harness import DeviceBatch
+from device_batch import DeviceBatch
 
 import paper_2411_03357_amd as pgcm
 

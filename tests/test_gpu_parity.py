@@ -9,7 +9,7 @@ import torch
 import openssl_ref
 import oracle
 import workloads
-from gpu_harness import DeviceBatch, apply_tampers, expand
+from device_batch import DeviceBatch, apply_tampers, expand
 
 import paper_2411_03357_amd as pgcm
 

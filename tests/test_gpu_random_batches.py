@@ -8,7 +8,7 @@ import torch
 
 import openssl_ref
 import workloads
-from gpu_harness import DeviceBatch, expand
+from device_batch import DeviceBatch, expand
 
 import paper_2411_03357_amd as pgcm
 
