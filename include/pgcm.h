@@ -294,6 +294,16 @@ int pgcm_copy_key_tables(pgcm_key_t *key, void *out, size_t bytes);
 int pgcm_set_unit_bytes(pgcm_key_t *key, uint32_t unit_bytes);
 
 /*
+ * Tuning and test aid.  A batch of at most 24 chunks with 96-bit IVs that does not fill the chip
+ * (every unit gets a wavefront of its own: up to a few megabytes on an MI355X) is done by one
+ * kernel launch, the whole invocation from the first block to the tag, its descriptors passed as
+ * kernel arguments (section 5.1: swaps come a few chunks at a time, and what counts for them is
+ * the time of the call).  enable = 0 sends such batches through the same sequence of kernels as
+ * larger ones instead (descriptor upload, unit kernel, fold, final step); results are identical.
+ */
+int pgcm_set_one_launch(pgcm_key_t *key, int enable);
+
+/*
  * Measurement aid.  With timing enabled, every batch call also records a pair of HIP events on
  * its stream around the bulk kernel (the one launch that touches the payload: keystream, XOR
  * and GHASH of every unit; for the small-transfer path, its one kernel).  The library keeps the

@@ -16,7 +16,7 @@ EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_en
            "pgcm_batch_unit_bytes", "pgcm_set_unit_bytes", "pgcm_key_tables_bytes",
            "pgcm_copy_key_tables",
            "pgcm_set_timing", "pgcm_last_bulk_kernel_ms", "pgcm_bulk_kernel_ms_history",
-           "pgcm_measure_passes")
+           "pgcm_measure_passes", "pgcm_set_one_launch")
 
 
 class PgcmError(RuntimeError):
@@ -84,6 +84,8 @@ def load_library():
     lib.pgcm_copy_key_tables.restype = C.c_int
     lib.pgcm_set_unit_bytes.argtypes = [vp, C.c_uint32]
     lib.pgcm_set_unit_bytes.restype = C.c_int
+    lib.pgcm_set_one_launch.argtypes = [vp, C.c_int]
+    lib.pgcm_set_one_launch.restype = C.c_int
     lib.pgcm_set_timing.argtypes = [vp, C.c_int]
     lib.pgcm_set_timing.restype = C.c_int
     lib.pgcm_last_bulk_kernel_ms.argtypes = [vp, C.POINTER(C.c_float)]
@@ -367,6 +369,11 @@ def copy_key_tables(key: Key) -> dict:
 def set_unit_bytes(key: Key, unit_bytes: int):
     """pgcm_set_unit_bytes (0: chosen per batch)"""
     _check(load_library().pgcm_set_unit_bytes(key.handle, unit_bytes))
+
+
+def set_one_launch(key: Key, enable: bool):
+    """pgcm_set_one_launch"""
+    _check(load_library().pgcm_set_one_launch(key.handle, 1 if enable else 0))
 
 
 def set_timing(key: Key, enable: bool):

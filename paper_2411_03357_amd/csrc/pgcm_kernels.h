@@ -18,6 +18,15 @@ __global__ void bulk_kernel(const KeyTables* kt, const ChunkDesc* chunks,
                             uint32_t nunits_total, uint32_t unit_power, uint32_t* counter,
                             const uint8_t* ivs, const Block* j0, Block* ekj0, Block* sets);
 
+// The whole invocation of a few chunks in one launch: gridDim.x = sum of the chunks' ngroups.
+// ekj0: one block per chunk; sets: one set (64 blocks) per workgroup; arrive: one word per
+// chunk, zero on entry and left zero.
+template <bool kDecrypt, int kRounds>
+__global__ void swap_kernel(const KeyTables* kt, ArgBatch batch, const uint8_t* ivs, Block* ekj0,
+                            Block* sets, uint32_t* arrive, uint8_t* tags, uint8_t* ok);
+
+__global__ void clear_words_kernel(uint32_t* words, uint32_t n);
+
 __global__ void fold_kernel(const KeyTables* kt, const FoldItem* items, uint32_t power,
                             Block* sets);
 

@@ -339,6 +339,43 @@ __device__ __forceinline__ void global_write128(uint8_t* p, u32x4 v) {
     *reinterpret_cast<global_u128_ptr>(reinterpret_cast<uintptr_t>(p)) = v;
 }
 
+// A block written so that a wavefront on another XCD can read it while this kernel still runs:
+// the XCDs' L2 caches are not coherent with each other for ordinary accesses, and a release or
+// acquire fence at device scope writes back or invalidates the whole L2 (tens of microseconds
+// when megabytes of fresh ciphertext sit there).  Relaxed atomic accesses at device scope go
+// through to memory instead, for these few bytes only.
+__device__ __forceinline__ void store_block_device_scope(Block* p, uint32_t w0, uint32_t w1,
+                                                         uint32_t w2, uint32_t w3) {
+    uint64_t* q = reinterpret_cast<uint64_t*>(p);
+    __hip_atomic_store(q, (uint64_t)w0 | ((uint64_t)w1 << 32), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(q + 1, (uint64_t)w2 | ((uint64_t)w3 << 32), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ Block load_block_device_scope(const Block* p) {
+    uint64_t* q = reinterpret_cast<uint64_t*>(const_cast<Block*>(p));
+    const uint64_t a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint64_t b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return Block{{(uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32)}};
+}
+
+// Payload stores that go through to memory at once instead of staying dirty in this XCD's L2:
+// for output that a wavefront on another XCD may overwrite later in the same kernel (the wipe of
+// a rejected chunk), where two L2s holding different dirty versions of a line would leave it to
+// chance which one memory keeps.
+__device__ __forceinline__ void global_write128_through(uint8_t* p, u32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void global_write8_through(uint8_t* p, uint8_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// waits until every global load and store this wavefront has issued is complete (for a
+// device-scope store: has reached memory)
+__device__ __forceinline__ void wait_for_own_global_accesses() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 // LDS byte address of a __shared__ object
 __device__ __forceinline__ uint32_t lds_offset(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
@@ -597,7 +634,8 @@ __device__ __forceinline__ void ghash_mul_lds(uint32_t base, uint32_t y[4]) {
 // idle, the last lane may hold the chunk's ragged last block, and the lane of block 0 folds in
 // the AAD state.  One code path serves both kinds: idle lanes run the cipher on a dummy counter,
 // touch no payload and keep a zero hash state.
-template <bool kDecrypt, int kRounds>
+// kThrough: the payload is written through to memory (see global_write128_through).
+template <bool kDecrypt, int kRounds, bool kThrough = false>
 __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAddr& A,
                                          const CtrConsts& C, uint32_t ctr1, const uint8_t* src,
                                          uint8_t* dst, uint64_t len, int64_t blk, bool edge,
@@ -643,14 +681,20 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
 
     if (whole) {
         u32x4 o = {o0, o1, o2, o3};
-        global_write128(dp, o);
+        if constexpr (kThrough)
+            global_write128_through(dp, o);
+        else
+            global_write128(dp, o);
     }
     if (edge && tail) {
 #pragma unroll
         for (uint32_t b = 0; b < 15; ++b) {
             if (b < tail) {
                 const uint32_t w = b / 4 == 0 ? o0 : b / 4 == 1 ? o1 : b / 4 == 2 ? o2 : o3;
-                dp[b] = (uint8_t)(w >> (8 * (b % 4)));
+                if constexpr (kThrough)
+                    global_write8_through(dp + b, (uint8_t)(w >> (8 * (b % 4))));
+                else
+                    dp[b] = (uint8_t)(w >> (8 * (b % 4)));
             }
         }
         // bytes past the end count as zero in the hash
@@ -673,11 +717,78 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
         if (blk == -1) {
             // the counter block of "block -1" is J0 itself: this idle lane has just computed
             // E_K(J0), the mask of the chunk's tag (SP 800-38D 7.1 steps 2 and 6)
-            *ekj0_out = Block{{s0, s1, s2, s3}};
+            // (read by another kernel, or by another workgroup of this one: device scope)
+            store_block_device_scope(ekj0_out, s0, s1, s2, s3);
         }
         if (!active) c0 = c1 = c2 = c3 = 0;  // idle lanes only occur before a chunk's start: Y = 0
     }
     y[0] = G.z0 ^ c0, y[1] = G.z1 ^ c1, y[2] = G.z2 ^ c2, y[3] = G.z3 ^ c3;
+}
+
+}  // namespace
+
+namespace {
+
+// Brings the bulk kernels' tables into LDS; every thread of the 1024 calls it, and a barrier
+// must follow.  Round tables: 32 copies of every entry, lane-interleaved.  A row of the map is
+// sixteen 16-byte pieces, eight per table of its pair; every thread fetches the eight entries
+// its pieces need at once (independent loads) and writes each four times over in one store, and
+// a wavefront's store covers four whole rows, so the stores run at the full LDS width.
+__device__ __forceinline__ void fill_bulk_lds(BulkLds& lds, const KeyTables* __restrict__ kt,
+                                              uint32_t tid) {
+    constexpr uint32_t kPieces = kLdsTeBytes / 16;
+    static_assert(kPieces % kGroupThreads == 0, "pieces per thread");
+    constexpr uint32_t kPerThread = kPieces / kGroupThreads;
+    uint32_t v[kPerThread];
+#pragma unroll
+    for (uint32_t k = 0; k < kPerThread; ++k) {
+        const uint32_t g = k * kGroupThreads + tid;  // piece number
+        const uint32_t pair = g >> 12, row = (g >> 4) & 255, t = 2 * pair + ((g >> 3) & 1);
+        v[k] = kt->te[t][row];
+    }
+    u32x4* te4 = reinterpret_cast<u32x4*>(lds.te);
+#pragma unroll
+    for (uint32_t k = 0; k < kPerThread; ++k) {
+        const u32x4 q = {v[k], v[k], v[k], v[k]};
+        te4[k * kGroupThreads + tid] = q;
+    }
+    for (uint32_t i = tid; i < kNibbleTableEntries; i += kGroupThreads)
+        lds.gh[i] = kt->ghash[kRowPower][i];
+}
+
+// One unit of one chunk, walked by one wavefront in rows of 64 blocks: keystream, XOR, and the
+// lane's GHASH sum over the unit's rows, sum over rows r of C(r, lane) * (H^64)^(rows after r),
+// left in y.  unit 0 also takes "block -1", whose counter block is J0, and stores E_K(J0).
+template <bool kDecrypt, int kRounds, bool kThrough = false>
+__device__ __forceinline__ void walk_unit(const KeyTables* __restrict__ kt,
+                                          const uint32_t* __restrict__ rk, AesAddr& A,
+                                          uint32_t lane, uint32_t lds_base, const uint8_t* src,
+                                          uint8_t* dst, uint64_t len, const uint8_t* aad,
+                                          uint32_t aad_len, uint32_t unit, uint32_t nunits,
+                                          uint32_t first_blocks, uint32_t unit_power,
+                                          const Block& j, Block* __restrict__ ekj0_out,
+                                          uint32_t y[4]) {
+    // the unit's blocks [b0, b1) of the chunk
+    const int64_t b0 =
+        unit == 0 ? -1 : (int64_t)first_blocks + ((int64_t)(unit - 1) << unit_power);
+    const int64_t b1 = unit == 0 ? (int64_t)first_blocks : b0 + ((int64_t)1 << unit_power);
+    const uint32_t nrows = (uint32_t)((b1 - b0 + kRowBlocks - 1) / kRowBlocks);
+
+    const CtrConsts C = ctr_consts(rk, lane, j.w[0], j.w[1], j.w[2], lds_base);
+    const uint32_t ctr1 = bswap32(j.w[3]) + 1u;
+
+    Block aad_y{{0, 0, 0, 0}};
+    if (unit == 0 && aad_len != 0) aad_y = aad_hash(kt, aad, aad_len);
+
+    y[0] = y[1] = y[2] = y[3] = 0;
+    // rows are aligned to the unit's end; only rows at the chunk's start can have idle lanes
+    // (block index below 0) or block 0, only its very last row can hold a ragged block
+    int64_t row_blk = b1 - (int64_t)nrows * kRowBlocks;
+    for (uint32_t r = 0; r < nrows; ++r, row_blk += kRowBlocks) {
+        const bool edge = row_blk <= 0 || (unit + 1 == nunits && r + 1 == nrows);
+        bulk_row<kDecrypt, kRounds, kThrough>(rk, A, C, ctr1, src, dst, len, row_blk + lane, edge,
+                                              aad_y, ekj0_out, lds_base, y);
+    }
 }
 
 }  // namespace
@@ -689,8 +800,7 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
 // be bound by it).  Unit i belongs to the
 // chunk c with unit_base[c] <= i < unit_base[c + 1] (unit_base has one entry more than there are
 // chunks); coarse_map[i >> kCoarseShift] is a chunk at or before the right one.
-// sets[i * 64 + lane] receives lane's GHASH sum over the unit's rows:
-//   sum over rows r of C(r, lane) * (H^64)^(rows after r).
+// sets[i * 64 + lane] receives lane's GHASH sum over the unit's rows.
 // ivs: 96-bit IVs (a chunk's at its `index`), read when j0 is null; otherwise j0[c] is chunk c's J0.
 template <bool kDecrypt, int kRounds>
 __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
@@ -705,13 +815,7 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     const uint32_t lds_base = lds_offset(&lds);
 
     const uint32_t tid = threadIdx.x;
-    // fill: 32 copies of every table entry, lane-interleaved
-    for (uint32_t i = tid; i < kLdsTeBytes / 4; i += kGroupThreads) {
-        uint32_t pair = i >> 14, row = (i >> 6) & 255, t = ((i >> 5) & 1) + 2 * pair;
-        lds.te[i] = kt->te[t][row];
-    }
-    for (uint32_t i = tid; i < kNibbleTableEntries; i += kGroupThreads)
-        lds.gh[i] = kt->ghash[kRowPower][i];
+    fill_bulk_lds(lds, kt, tid);
     __syncthreads();
 
     const uint32_t lane = tid & 63;
@@ -731,34 +835,11 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
         uint32_t chunk = coarse_map[item >> kCoarseShift];
         while (unit_base[chunk + 1] <= item) ++chunk;  // ends: unit_base[nchunks] > item
         const ChunkDesc* __restrict__ cd = chunks + chunk;
-        const uint8_t* src = cd->src;
-        uint8_t* dst = cd->dst;
-        const uint64_t len = cd->len;
-        const uint32_t unit = item - cd->unit_base, nunits = cd->nunits;
-        const uint32_t first_blocks = cd->first_blocks;
-        // the unit's blocks [b0, b1) of the chunk
-        // unit 0 also takes "block -1", whose counter block is J0
-        const int64_t b0 =
-            unit == 0 ? -1 : (int64_t)first_blocks + ((int64_t)(unit - 1) << unit_power);
-        const int64_t b1 = unit == 0 ? (int64_t)first_blocks : b0 + ((int64_t)1 << unit_power);
-        const uint32_t nrows = (uint32_t)((b1 - b0 + kRowBlocks - 1) / kRowBlocks);
-
         const Block j = chunk_j0(kt, ivs, j0, chunk, cd->index);
-        const CtrConsts C = ctr_consts(rk, lane, j.w[0], j.w[1], j.w[2], lds_base);
-        const uint32_t ctr1 = bswap32(j.w[3]) + 1u;
-
-        Block aad_y{{0, 0, 0, 0}};
-        if (unit == 0 && cd->aad_len != 0) aad_y = aad_hash(kt, cd->aad, cd->aad_len);
-
-        uint32_t y[4] = {0, 0, 0, 0};
-        // rows are aligned to the unit's end; only rows at the chunk's start can have idle lanes
-        // (block index below 0) or block 0, only its very last row can hold a ragged block
-        int64_t row_blk = b1 - (int64_t)nrows * kRowBlocks;
-        for (uint32_t r = 0; r < nrows; ++r, row_blk += kRowBlocks) {
-            const bool edge = row_blk <= 0 || (unit + 1 == nunits && r + 1 == nrows);
-            bulk_row<kDecrypt, kRounds>(rk, A, C, ctr1, src, dst, len, row_blk + lane, edge, aad_y,
-                                        ekj0 + chunk, lds_base, y);
-        }
+        uint32_t y[4];
+        walk_unit<kDecrypt, kRounds>(kt, rk, A, lane, lds_base, cd->src, cd->dst, cd->len,
+                                     cd->aad, cd->aad_len, item - cd->unit_base, cd->nunits,
+                                     cd->first_blocks, unit_power, j, ekj0 + chunk, y);
         sets[(uint64_t)item * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
         if (one_each) break;
         if (lane == 0)
@@ -1021,6 +1102,201 @@ template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, 
                                             const uint8_t*, const Block*, const Block*,
                                             const Block*, uint8_t*, uint8_t*, uint32_t,
                                             uint32_t*, uint32_t);
+
+// ------------------------------------------------------------------------------------------
+// A few chunks in ONE launch (the paper's swaps come a few chunks at a time, section 5.1).
+// Descriptors are kernel arguments.  Every wavefront walks one unit as in bulk_kernel; then the
+// workgroup, whose sixteen units belong to one chunk, folds their sets as a tree in LDS (the round
+// tables are no longer needed: their space takes the GHASH tables of the fold).  A chunk of one
+// workgroup is finished there and then.  Otherwise the workgroup writes its set through to memory
+// (device-scope stores, no cache-wide fence), waits for the stores to complete and counts itself
+// in on the chunk's arrival word; the workgroup that arrives last reads the workgroups' sets
+// (device-scope loads) and folds them, each wavefront a run of them and then a tree across the
+// wavefronts, folds the lanes and writes the tag or the verdict.  Nobody waits for anybody: every
+// workgroup runs to its end whatever the others do.
+//
+// LDS after the round tables are done with, in tables of 8 KiB:
+//   0..5   H^(2^k), k = 0 .. 5: lane tree, length block
+//   6..9   H^(2^(p + j)), j = 0 .. 3: tree over the workgroup's sixteen units (p = unit_power)
+//   10     H^(2^(p + 4)): from one workgroup's set to the next
+//   11..14 H^(2^(p + 4 + l + j)), j = 0 .. 3: tree over the sixteen wavefronts' runs of 2^l sets
+//   15..16 sixteen sets, one per wavefront
+namespace {
+
+constexpr uint32_t kSwapLaneTables = 0, kSwapUnitTables = 6, kSwapRunTable = 10,
+                   kSwapWaveTables = 11, kSwapPartial = 15;
+static_assert((kSwapPartial + 2) * kLdsGhBytes <= kLdsBytes, "tables and sets fit the LDS object");
+
+// sixteen sets (one per wavefront, in y) -> one in wavefront 0, leaves counted back from the
+// last: rounds j = 0 .. 3 with H^(2^(first_power + j)) at tables[first_table + j]
+__device__ __forceinline__ void fold_waves(Block (*tables)[kNibbleTableEntries], Block (*partial)[64],
+                                           uint32_t first_table, uint32_t wave, uint32_t lane,
+                                           uint32_t y[4]) {
+    // every wavefront passes every barrier; only the shrinking front half has work to do
+    for (uint32_t j = 0; j < 4; ++j) {
+        partial[wave][lane] = Block{{y[0], y[1], y[2], y[3]}};
+        __syncthreads();
+        if (wave < (kWavesPerGroup >> (j + 1))) {
+            const Block a = partial[2 * wave][lane], b = partial[2 * wave + 1][lane];
+            y[0] = a.w[0], y[1] = a.w[1], y[2] = a.w[2], y[3] = a.w[3];
+            ghash_mul_lds(lds_offset(tables[first_table + j]), y);
+            y[0] ^= b.w[0], y[1] ^= b.w[1], y[2] ^= b.w[2], y[3] ^= b.w[3];
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace
+
+template <bool kDecrypt, int kRounds>
+__global__ __launch_bounds__(kGroupThreads) void swap_kernel(
+    const KeyTables* __restrict__ kt, const ArgBatch batch, const uint8_t* __restrict__ ivs,
+    Block* __restrict__ ekj0, Block* __restrict__ sets, uint32_t* __restrict__ arrive,
+    uint8_t* __restrict__ tags, uint8_t* __restrict__ ok) {
+    __shared__ BulkLds lds;
+    __shared__ uint32_t last_flag;
+    const uint32_t lds_base = lds_offset(&lds);
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    fill_bulk_lds(lds, kt, tid);
+
+    // this workgroup's chunk: the one whose workgroups include blockIdx.x (host: the grid is the
+    // sum of the chunks' ngroups, so the scan ends inside the array)
+    uint32_t chunk = 0;
+    while (chunk + 1 < batch.nchunks && batch.c[chunk + 1].group_base <= blockIdx.x) ++chunk;
+    const ArgChunk cd = batch.c[chunk];
+    const uint32_t unit_power = batch.unit_power;
+    // units are dealt to the chunk's workgroups counted back from its end: workgroup g of G takes
+    // units nunits - 16 (G - g) + wave; a negative number is a wavefront without a unit
+    const uint32_t g = blockIdx.x - cd.group_base;
+    const int32_t unit = (int32_t)cd.nunits - (int32_t)(kWavesPerGroup * (cd.ngroups - g)) + (int32_t)wave;
+    __syncthreads();
+
+    uint32_t y[4] = {0, 0, 0, 0};
+    if (unit >= 0) {
+        AesAddr A;
+        aes_addr_init(A, lane);
+        uint32_t rk[4 * (kRounds + 1)];
+#pragma unroll
+        for (int i = 0; i < 4 * (kRounds + 1); ++i) rk[i] = kt->rk[i];
+        const Block j = j0_from_iv(kt, ivs + (uint64_t)cd.index * 12, 12);
+        // When decrypting, the workgroup that finishes the chunk may have to wipe plaintext that
+        // other workgroups (on other XCDs) wrote: their stores go through to memory, and must be
+        // there before the arrival is counted.  So must E_K(J0), which unit 0's wavefront stores.
+        walk_unit<kDecrypt, kRounds, kDecrypt>(kt, rk, A, lane, lds_base, cd.src, cd.dst, cd.len,
+                                               cd.aad, cd.aad_len, (uint32_t)unit, cd.nunits,
+                                               cd.first_blocks, unit_power, j, ekj0 + chunk, y);
+        if (kDecrypt || unit == 0) wait_for_own_global_accesses();
+    }
+    __syncthreads();  // the round tables are done with: their LDS now takes GHASH tables
+
+    Block(*tables)[kNibbleTableEntries] = reinterpret_cast<Block(*)[kNibbleTableEntries]>(&lds);
+    Block(*partial)[64] = reinterpret_cast<Block(*)[64]>(tables[kSwapPartial]);
+    const bool alone = cd.ngroups == 1;
+    if (cd.nunits > 1)
+        for (uint32_t j = 0; j < 4; ++j)
+            copy_power_table(tables[kSwapUnitTables + j], kt, unit_power + j, tid, kGroupThreads);
+    if (alone)
+        for (uint32_t k = 0; k < 6; ++k)
+            copy_power_table(tables[kSwapLaneTables + k], kt, k, tid, kGroupThreads);
+    __syncthreads();
+    if (cd.nunits > 1) fold_waves(tables, partial, kSwapUnitTables, wave, lane, y);
+    else if (wave == kWavesPerGroup - 1) {
+        // a single unit sits in the last wavefront: hand its set to wavefront 0
+        partial[0][lane] = Block{{y[0], y[1], y[2], y[3]}};
+    }
+    if (cd.nunits <= 1) {
+        __syncthreads();
+        if (wave == 0) {
+            const Block a = partial[0][lane];
+            y[0] = a.w[0], y[1] = a.w[1], y[2] = a.w[2], y[3] = a.w[3];
+        }
+    }
+
+    if (!alone) {
+        // hand this workgroup's set over and count it in; the last one to arrive goes on
+        if (wave == 0) {
+            store_block_device_scope(sets + (uint64_t)blockIdx.x * 64 + lane, y[0], y[1], y[2], y[3]);
+            // the set (and E_K(J0), waited for before the last barrier) must have reached memory
+            // before the arrival is counted: both are device-scope stores, so waiting for them
+            // to complete is enough, and no cache needs writing back
+            wait_for_own_global_accesses();
+            if (lane == 0) {
+                const uint32_t before = __hip_atomic_fetch_add(arrive + chunk, 1u, __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+                last_flag = before + 1 == cd.ngroups;
+                if (before + 1 == cd.ngroups)
+                    __hip_atomic_store(arrive + chunk, 0u, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);  // left zero for the next batch
+            }
+        }
+        __syncthreads();
+        if (!last_flag) return;  // uniform over the workgroup
+        // the others' sets are read with device-scope loads, issued after the arrival count
+        // was seen: they come from memory, not from this XCD's caches
+
+        // runs of 2^l sets per wavefront, the smallest l with 16 * 2^l >= ngroups; leaves are
+        // counted back from the last set, missing ones at the front count as zero
+        uint32_t l = 0;
+        while ((kWavesPerGroup << l) < cd.ngroups) ++l;
+        for (uint32_t k = 0; k < 6; ++k)
+            copy_power_table(tables[kSwapLaneTables + k], kt, k, tid, kGroupThreads);
+        copy_power_table(tables[kSwapRunTable], kt, unit_power + 4, tid, kGroupThreads);
+        for (uint32_t j = 0; j < 4; ++j)
+            copy_power_table(tables[kSwapWaveTables + j], kt, unit_power + 4 + l + j, tid,
+                             kGroupThreads);
+        const uint32_t run = 1u << l, pad = (kWavesPerGroup << l) - cd.ngroups;
+        const Block* __restrict__ in = sets + (uint64_t)cd.group_base * 64 + lane;
+        y[0] = y[1] = y[2] = y[3] = 0;
+        const uint32_t first_leaf = wave * run;
+        __syncthreads();
+        bool started = false;  // uniform over the wavefront, like everything in this loop
+        for (uint32_t k = 0; k < run; ++k) {
+            const uint32_t leaf = first_leaf + k;
+            if (leaf < pad) continue;
+            if (started) ghash_mul_lds(lds_offset(tables[kSwapRunTable]), y);
+            started = true;
+            const Block b = load_block_device_scope(in + (uint64_t)(leaf - pad) * 64);
+            y[0] ^= b.w[0], y[1] ^= b.w[1], y[2] ^= b.w[2], y[3] ^= b.w[3];
+        }
+        fold_waves(tables, partial, kSwapWaveTables, wave, lane, y);
+    }
+    if (wave != 0) return;
+
+    // wavefront 0 holds the chunk's 64 lane sums (nothing at all for an empty chunk)
+    Block mask;
+    if (cd.nunits == 0) {
+        const Block a = aad_hash(kt, cd.aad, cd.aad_len);
+        y[0] = a.w[0], y[1] = a.w[1], y[2] = a.w[2], y[3] = a.w[3];
+        const Block j = j0_from_iv(kt, ivs + (uint64_t)cd.index * 12, 12);
+        uint32_t e[4] = {j.w[0], j.w[1], j.w[2], j.w[3]};
+        aes_block_global(kt, e);
+        mask = Block{{e[0], e[1], e[2], e[3]}};
+    } else {
+        fold_lanes(lds_offset(tables[kSwapLaneTables]), y);
+        mask = load_block_device_scope(ekj0 + chunk);
+    }
+    ChunkDesc d{};
+    d.dst = cd.dst;
+    d.len = cd.len;
+    d.aad_len = cd.aad_len;
+    d.index = cd.index;
+    finish_chunk<kDecrypt>(lds_offset(tables[kSwapLaneTables]), y, mask.w, d, tags, ok, lane);
+}
+
+#define PGCM_INSTANTIATE_SWAP(D, R)                                                          \
+    template __global__ void swap_kernel<D, R>(const KeyTables*, ArgBatch, const uint8_t*, Block*, \
+                                               Block*, uint32_t*, uint8_t*, uint8_t*)
+PGCM_INSTANTIATE_SWAP(false, 10);
+PGCM_INSTANTIATE_SWAP(false, 12);
+PGCM_INSTANTIATE_SWAP(false, 14);
+PGCM_INSTANTIATE_SWAP(true, 10);
+PGCM_INSTANTIATE_SWAP(true, 12);
+PGCM_INSTANTIATE_SWAP(true, 14);
+#undef PGCM_INSTANTIATE_SWAP
+
+__global__ __launch_bounds__(64) void clear_words_kernel(uint32_t* __restrict__ words, uint32_t n) {
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) words[i] = 0;
+}
 
 // ------------------------------------------------------------------------------------------
 // The small-transfer path: a batch whose chunks are all at most kSmallChunkBytes long (the

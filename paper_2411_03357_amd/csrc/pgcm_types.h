@@ -80,6 +80,33 @@ struct alignas(16) FoldItem {
     uint32_t pad_;
 };
 
+// A batch of few chunks that does not fill the chip (every unit gets a wavefront of its own) is
+// done by ONE kernel, its descriptors travelling as kernel arguments: the paper's swaps arrive a
+// few chunks at a time between synchronisations (section 5.1), and for them the time of a call
+// counts, not the rate.  Every chunk gets workgroups of its own, sixteen units each, counted back
+// from the chunk's end so that only its first workgroup can be short.
+constexpr uint32_t kArgChunks = 24;
+struct alignas(16) ArgChunk {
+    const uint8_t* src;
+    uint8_t* dst;
+    const uint8_t* aad;
+    uint64_t len;
+    uint32_t aad_len;
+    uint32_t nunits;        // 0 for an empty chunk
+    uint32_t first_blocks;  // blocks in unit 0; every later unit has 2^unit_power
+    uint32_t index;         // the chunk's place in the caller's ivs, tags and ok arrays
+    uint32_t group_base;    // first workgroup of the chunk = its first set slot
+    uint32_t ngroups;       // max(1, ceil(nunits / 16))
+    uint32_t pad_[2];
+};
+static_assert(sizeof(ArgChunk) == 64, "argument layout");
+struct alignas(16) ArgBatch {
+    uint32_t nchunks;
+    uint32_t unit_power;
+    uint32_t pad_[2];
+    ArgChunk c[kArgChunks];
+};
+
 // A batch whose chunks are all at most this long takes the small-transfer path: one kernel (the
 // paper's non-swap transfers are usually < 8 KB, section 4.2): eight rows of 64 blocks.
 constexpr uint64_t kSmallChunkBytes = 8192;
