@@ -191,6 +191,64 @@ def pipeline_bench(args):
         "traces": out}))
 
 
+def bitsliced_bench(args):
+    """--bitsliced: the cost of the one alternative to table-driven AES rounds, measured.  The
+    bitsliced kernel writes the counter-mode keystream for as many blocks as the KV-cache swap
+    shape has (no payload is read, nothing is hashed: the round function alone plus the store);
+    the table-driven bulk kernel of the batch calls is timed beside it on that shape, doing the
+    whole of AES-GCM.  Prints ONE JSON line."""
+    import re
+    import torch
+
+    import workloads
+    import paper_2411_03357_amd as pgcm
+    from device_batch import DeviceBatch
+
+    torch.cuda.set_device(0)
+    w = workloads.config2()
+    key = pgcm.expand_key(w.key)
+    nblocks = w.payload_bytes // 16
+    out = torch.empty(16 * nblocks, dtype=torch.uint8, device="cuda")
+    iv = w.ivs[0].tobytes()
+    for _ in range(3):
+        pgcm.bitsliced_keystream(key, iv, 0, nblocks, out)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(max(3, args.steps // 10))]
+    for s, e in ev:
+        s.record()
+        pgcm.bitsliced_keystream(key, iv, 0, nblocks, out)
+        e.record()
+    torch.cuda.synchronize()
+    ms = sorted(s.elapsed_time(e) for s, e in ev)
+    bs_ms = ms[len(ms) // 2]
+    del out
+    # the table-driven kernel on the same number of blocks (whole AES-GCM: keystream, XOR, GHASH)
+    b = DeviceBatch(w, w.payload_device())
+    b.measure(key, 5, direction=1)
+    pgcm.set_timing(key, True)
+    b.measure(key, 20, direction=1)
+    table_ms = sorted(pgcm.bulk_kernel_ms_history(key, 20))[10]
+    pgcm.set_timing(key, False)
+    key.free()
+    gen = open(os.path.join(ROOT, "paper_2411_03357_amd", "csrc", "pgcm_bitsliced_gen.h")).read()
+    sbox = int(re.search(r"kSboxInstructions = (\d+)", gen).group(1))
+    mix = int(re.search(r"kMixColumnInstructions = (\d+)", gen).group(1))
+    per_round = 16 * sbox + 4 * mix                   # wavefront instructions per 2048 blocks
+    print(json.dumps({
+        "metric": "bitsliced AES-256 counter-mode keystream on 1 MI355X, GB/s (measurement of the "
+                  "alternative round function; not the batch path)",
+        "value": round(16 * nblocks / (bs_ms * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
+        "higher_is_better": True, "data": "synthetic", "dtype": "u32 bit planes",
+        "config": {"workload": "%d counter blocks (the block count of %s), keystream only"
+                               % (nblocks, w.name)},
+        "bitsliced_kernel_ms": round(bs_ms, 4),
+        "table_driven_bulk_kernel_ms": round(table_ms, 4),
+        "table_driven_GBps_whole_gcm": round(w.payload_bytes / (table_ms * 1e-3) / 1e9, 2),
+        "sbox_instructions": sbox, "mixcolumn_addkey_instructions_per_column": mix,
+        "valu_instructions_per_round_per_64_blocks": round(per_round / 32.0, 2),
+        "note": "dynamic instruction counts (SQ_INSTS_VALU) are in profiles/"}))
+
+
 def measure_workload(pgcm, torch, w, args, steps, warmup, headline):
     """One workload through the library's own timing loop.  Returns (results dict, batch, key);
     the caller frees them.  steps passes (encrypt + decrypt-verify) are timed by the host clock,
@@ -289,6 +347,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of the payload buffer (a kernel of known "
                          "traffic to scale hardware byte counters by)")
+    ap.add_argument("--bitsliced", action="store_true",
+                    help="measure the bitsliced round function beside the table-driven one "
+                         "instead (its own JSON line)")
     ap.add_argument("--pipeline", action="store_true",
                     help="measure the speculative pipeline on swap traces instead (its own JSON "
                          "line; --steps is the number of rounds per trace)")
@@ -300,6 +361,9 @@ def main():
 
     if args.pipeline:
         pipeline_bench(args)
+        return
+    if args.bitsliced:
+        bitsliced_bench(args)
         return
 
     import numpy as np

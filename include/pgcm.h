@@ -318,6 +318,23 @@ int pgcm_set_one_launch(pgcm_key_t *key, int enable);
 int pgcm_set_timing(pgcm_key_t *key, int enable);
 
 /*
+ * Measurement aid: the keystream of nblocks consecutive counter blocks, E_K(iv || be32(ctr_base)),
+ * E_K(iv || be32(ctr_base + 1)), .. (the blocks the cipher XORs onto a transfer's payload,
+ * SP 800-38D 6.5), computed by a BITSLICED round function: no table lookups, the S-box as a
+ * Boolean circuit over registers that each hold one bit of 32 blocks.  The batch calls do not use
+ * it; it is here so that the cost of the one alternative to their table-driven rounds can be
+ * measured on the chip and checked for correctness.
+ *   iv         HOST, 12 bytes.
+ *   ctr_base   first counter value; a multiple of 32 (a lane's 32 blocks differ in the low five
+ *              bits of the counter); the counter wraps modulo 2^32.
+ *   nblocks    a multiple of 2048 (32 blocks in each of a wavefront's 64 lanes), at most 2^31.
+ *   out        DEVICE, 16 * nblocks bytes, 16-byte aligned, written.
+ * PGCM_ERR_ARG when a constraint is not met.
+ */
+int pgcm_bitsliced_keystream(pgcm_key_t *key, const uint8_t iv[12], uint32_t ctr_base,
+                             uint64_t nblocks, void *out, void *hip_stream);
+
+/*
  * Measurement aid: `steps` passes of the path over one batch, enqueued back to back by a loop
  * inside the library, so that what is timed is the library and the GPU and not the caller's
  * language.  A pass is pgcm_encrypt_batch_iv (src -> cipher, tags written) followed by

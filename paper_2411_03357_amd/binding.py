@@ -16,7 +16,7 @@ EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_en
            "pgcm_batch_unit_bytes", "pgcm_set_unit_bytes", "pgcm_key_tables_bytes",
            "pgcm_copy_key_tables",
            "pgcm_set_timing", "pgcm_last_bulk_kernel_ms", "pgcm_bulk_kernel_ms_history",
-           "pgcm_measure_passes", "pgcm_set_one_launch")
+           "pgcm_measure_passes", "pgcm_set_one_launch", "pgcm_bitsliced_keystream")
 
 
 class PgcmError(RuntimeError):
@@ -84,6 +84,8 @@ def load_library():
     lib.pgcm_copy_key_tables.restype = C.c_int
     lib.pgcm_set_unit_bytes.argtypes = [vp, C.c_uint32]
     lib.pgcm_set_unit_bytes.restype = C.c_int
+    lib.pgcm_bitsliced_keystream.argtypes = [vp, vp, C.c_uint32, C.c_uint64, vp, vp]
+    lib.pgcm_bitsliced_keystream.restype = C.c_int
     lib.pgcm_set_one_launch.argtypes = [vp, C.c_int]
     lib.pgcm_set_one_launch.restype = C.c_int
     lib.pgcm_set_timing.argtypes = [vp, C.c_int]
@@ -369,6 +371,16 @@ def copy_key_tables(key: Key) -> dict:
 def set_unit_bytes(key: Key, unit_bytes: int):
     """pgcm_set_unit_bytes (0: chosen per batch)"""
     _check(load_library().pgcm_set_unit_bytes(key.handle, unit_bytes))
+
+
+def bitsliced_keystream(key: Key, iv, ctr_base: int, nblocks: int, out, stream=None):
+    """pgcm_bitsliced_keystream: iv is 12 bytes (host), out a CUDA uint8 tensor of 16 * nblocks
+    bytes or a device address"""
+    v = np.frombuffer(bytes(iv), dtype=np.uint8)
+    if v.size != 12:
+        raise ValueError("IVs are 12 bytes")
+    _check(load_library().pgcm_bitsliced_keystream(key.handle, v.ctypes.data, ctr_base, nblocks,
+                                                   _dev_ptr(out), _stream_handle(stream)))
 
 
 def set_one_launch(key: Key, enable: bool):

@@ -6,8 +6,9 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpgcm.so")
-SOURCES = ["pgcm_kernels.hip", "pgcm_host.hip", "pgcm_bounce.hip", "pgcm_pipe.hip", "pgcm_seq.cpp"]
-HEADERS = ["pgcm_kernels.h", "pgcm_types.h", os.path.join("..", "..", "include", "pgcm.h"),
+SOURCES = ["pgcm_kernels.hip", "pgcm_bitsliced.hip", "pgcm_host.hip", "pgcm_bounce.hip", "pgcm_pipe.hip",
+           "pgcm_seq.cpp"]
+HEADERS = ["pgcm_kernels.h", "pgcm_types.h", "pgcm_bitsliced_gen.h", os.path.join("..", "..", "include", "pgcm.h"),
            os.path.join("..", "..", "include", "pgcm_seq.h"),
            os.path.join("..", "..", "include", "pgcm_bounce.h"),
            os.path.join("..", "..", "include", "pgcm_pipe.h")]

@@ -1158,6 +1158,37 @@ int pgcm_set_unit_bytes(pgcm_key_t* key, uint32_t unit_bytes) {
     return PGCM_ERR_ARG;
 }
 
+int pgcm_bitsliced_keystream(pgcm_key_t* key, const uint8_t iv[12], uint32_t ctr_base,
+                             uint64_t nblocks, void* out, void* hip_stream) {
+    constexpr uint64_t kPerGroup = pgcm_bitsliced::kLaneBlocks * pgcm_bitsliced::kGroupLanes;
+    if (key == nullptr || key->tables == nullptr || iv == nullptr || out == nullptr)
+        return PGCM_ERR_ARG;
+    if (ctr_base % pgcm_bitsliced::kLaneBlocks != 0 || nblocks % kPerGroup != 0 ||
+        nblocks > ((uint64_t)1 << 31) || ((uintptr_t)out & 15))
+        return PGCM_ERR_ARG;
+    if (nblocks == 0) return PGCM_OK;
+    int cur_device = -1;
+    PGCM_HIP(hipGetDevice(&cur_device));
+    if (cur_device != key->device) return PGCM_ERR_ARG;
+    uint32_t w[3];
+    memcpy(w, iv, 12);  // little-endian loads of the IV bytes, like the round-key words
+    const dim3 grid((uint32_t)(nblocks / kPerGroup)), block(pgcm_bitsliced::kGroupLanes);
+    const hipStream_t stream = (hipStream_t)hip_stream;
+    const KeyTables* kt = key->tables;
+    uint32_t* o = static_cast<uint32_t*>(out);
+    if (key->rounds == 10)
+        hipLaunchKernelGGL(pgcm_bitsliced::keystream_kernel<10>, grid, block, 0, stream, kt, w[0],
+                           w[1], w[2], ctr_base, o);
+    else if (key->rounds == 12)
+        hipLaunchKernelGGL(pgcm_bitsliced::keystream_kernel<12>, grid, block, 0, stream, kt, w[0],
+                           w[1], w[2], ctr_base, o);
+    else
+        hipLaunchKernelGGL(pgcm_bitsliced::keystream_kernel<14>, grid, block, 0, stream, kt, w[0],
+                           w[1], w[2], ctr_base, o);
+    PGCM_HIP(hipGetLastError());
+    return PGCM_OK;
+}
+
 int pgcm_set_one_launch(pgcm_key_t* key, int enable) {
     if (key == nullptr) return PGCM_ERR_ARG;
     key->one_launch = enable != 0;

@@ -58,3 +58,12 @@ __global__ void small_wide_kernel(const KeyTables* kt, const ChunkDesc* chunks_h
 __global__ void upload_kernel(uint4* dst, const uint4* src_host, uint32_t n16, uint32_t* clear);
 
 }  // namespace pgcm
+
+namespace pgcm_bitsliced {
+// pgcm_bitsliced.hip: keystream of counter blocks by a bitsliced round function (measurement)
+constexpr uint32_t kLaneBlocks = 32;   // counter blocks per lane: one per bit of a register
+constexpr uint32_t kGroupLanes = 64;
+template <int kRounds>
+__global__ void keystream_kernel(const pgcm::KeyTables* kt, uint32_t iv0, uint32_t iv1,
+                                 uint32_t iv2, uint32_t ctr_base, uint32_t* out);
+}  // namespace pgcm_bitsliced
