@@ -19,7 +19,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
-VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit op per lane-clock
+# 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz, one 32-bit op per lane-clock: a wavefront instruction
+# whose operands are all vector registers occupies its SIMD for two cycles (measured: 1.77 such
+# instructions per clock per CU; one with a scalar-register operand takes four).  The same
+# count as the published 157.3 TFLOP/s of FP32 vector rate at two flops per lane-clock.
+VALU_PEAK_TOPS = 256 * 128 * 2.4e9 / 1e12
 LDS_PEAK_GCYCLES = 256 * 2.4               # 256 CUs, one LDS pipe each, 2.4 GHz: port cycles per ns
 
 # Hardware counters of one bulk_kernel launch on the default workload, taken with
@@ -27,17 +31,17 @@ LDS_PEAK_GCYCLES = 256 * 2.4               # 256 CUs, one LDS pipe each, 2.4 GHz
 # (pgcm_kernels.hip and the two headers it includes) whose hash is given; once those change the
 # counters no longer apply and bench.py reports null.
 COUNTERS = {
-    "sources_sha256": "fe8984312c3d91b1d28d5afbb62eab3deef9dce2e15b2a13524384063f83da38",
+    "sources_sha256": "3592ddd1f2066d53c32b9872b84881e0903e1d36d84091d2e3c09ca74715c67d",
     "workload": "c2_opt13b_kv_4096x320KiB",
-    "fetch_size_kib": 657226.9,     # FETCH_SIZE per launch
-    "fetch_scale": 1310720.0 / 655383.3,   # a 1 310 720 KiB device copy reads 655 383
-    "write_size_kib": 1395322.2,    # WRITE_SIZE per launch
+    "fetch_size_kib": 657160.7,     # FETCH_SIZE per launch
+    "fetch_scale": 1310720.0 / 655383.0,   # a 1 310 720 KiB device copy reads 655 383
+    "write_size_kib": 1395456.0,    # WRITE_SIZE per launch
     "write_scale": 1310720.0 / 1310720.0,  # the same copy writes 1 310 720.0
-    "valu_wave_instructions": 609253376.0,  # SQ_INSTS_VALU per launch
-    "lds_wave_instructions": 321931264.0,   # SQ_INSTS_LDS per launch
+    "valu_wave_instructions": 608147456.0,  # SQ_INSTS_VALU per launch
+    "lds_wave_instructions": 321832960.0,   # SQ_INSTS_LDS per launch
     "lds_active_cycles": 728154112.0,   # SQ_LDS_IDX_ACTIVE per launch, summed over the 256 CUs
-    "gui_active_cycles": 1.0,           # GRBM_GUI_ACTIVE per launch ...
-    "pmc_launch_ms": 1.0,               # ... and the launch's duration in that same run
+    "gui_active_cycles": 24966249.3 / 8,  # GRBM_GUI_ACTIVE per launch (summed over the 8 XCDs) ...
+    "pmc_launch_ms": 1.6109499,           # ... and the launch's duration in that same run
 }
 
 
@@ -249,6 +253,55 @@ def bitsliced_bench(args):
         "note": "dynamic instruction counts (SQ_INSTS_VALU) are in profiles/"}))
 
 
+def latency_bench(args):
+    """--latency: time of ONE call on batches that do not fill the chip (the paper's swaps come a
+    few chunks at a time, section 5.1): encrypt calls and encrypt + decrypt-verify passes enqueued
+    back to back by the library's own loop, microseconds per call.  Prints ONE JSON line."""
+    import numpy as np
+    import torch
+
+    import workloads
+    import paper_2411_03357_amd as pgcm
+    from device_batch import DeviceBatch
+
+    torch.cuda.set_device(0)
+    kib, mib = 1024, 1 << 20
+    cases = [("1 x 1 B", [1]), ("1 x 4 KiB", [4096]), ("64 x 4 KiB", [4096] * 64),
+             ("1 x 320 KiB", [320 * kib]), ("16 x 320 KiB", [320 * kib] * 16),
+             ("1 x 2 MiB", [2 * mib]), ("4 x 2 MiB", [2 * mib] * 4), ("1 x 8 MiB", [8 * mib]),
+             ("256 x 320 KiB", [320 * kib] * 256), ("1 x 64 MiB", [64 * mib])]
+    reps = max(50, args.steps * 3)
+    out = {}
+    for name, lens in cases:
+        rng = np.random.default_rng(1)
+        lens = np.array(lens, np.uint64)
+        off, total = workloads._layout(lens)
+        w = workloads.Workload("latency", 1, rng.integers(0, 256, 32, dtype=np.uint8),
+                               workloads.iv_sequence(5, lens.size), lens, off, total, "u8")
+        key = pgcm.expand_key(w.key)
+        b = DeviceBatch(w, w.payload_device())
+        row = {}
+        for label, one_launch in (("us_per_encrypt_call", True), ("several_kernels", False)):
+            pgcm.set_one_launch(key, one_launch)
+            b.measure(key, 50, direction=1)
+            row[label] = round(min(b.measure(key, reps, direction=1) for _ in range(3)) /
+                               reps * 1e3, 2)
+        pgcm.set_one_launch(key, True)
+        b.measure(key, 20)
+        row["us_per_pass"] = round(b.measure(key, reps) / reps * 1e3, 2)
+        row["GBps_encrypt"] = round(w.payload_bytes / row["us_per_encrypt_call"] / 1e3, 1)
+        out[name] = row
+        key.free()
+    print(json.dumps({
+        "metric": "time of one encrypt call on a batch that does not fill the chip, us "
+                  "(back to back on one stream)",
+        "value": out["1 x 320 KiB"]["us_per_encrypt_call"], "unit": "us",
+        "higher_is_better": False, "n_gpus": 1, "data": "synthetic", "dtype": "u8",
+        "config": {"workload": "1 x 320 KiB (one KV-cache block of the OPT-13B shape); the other "
+                               "batches in `batches`", "calls_timed": reps},
+        "batches": out}))
+
+
 def measure_workload(pgcm, torch, w, args, steps, warmup, headline):
     """One workload through the library's own timing loop.  Returns (results dict, batch, key);
     the caller frees them.  steps passes (encrypt + decrypt-verify) are timed by the host clock,
@@ -347,6 +400,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of the payload buffer (a kernel of known "
                          "traffic to scale hardware byte counters by)")
+    ap.add_argument("--latency", action="store_true",
+                    help="time single calls on small batches instead (its own JSON line)")
     ap.add_argument("--bitsliced", action="store_true",
                     help="measure the bitsliced round function beside the table-driven one "
                          "instead (its own JSON line)")
@@ -364,6 +419,9 @@ def main():
         return
     if args.bitsliced:
         bitsliced_bench(args)
+        return
+    if args.latency:
+        latency_bench(args)
         return
 
     import numpy as np
@@ -409,16 +467,19 @@ def main():
             and not args.host_bounce and args.unit_bytes == 0):
         traffic = int(1024 * (COUNTERS["fetch_size_kib"] * COUNTERS["fetch_scale"] +
                               COUNTERS["write_size_kib"] * COUNTERS["write_scale"]))
-        # the clock the chip ran at under this kernel, as measured in the counter run:
+        # The clock the chip ran at under this kernel, measured in the counter run:
         # GRBM_GUI_ACTIVE (cycles of the graphics clock while the launch was in flight) over the
-        # launch's duration in the same run
-        clock_ghz = COUNTERS["gui_active_cycles"] / (COUNTERS["pmc_launch_ms"] * 1e-3) / 1e9
+        # launch's duration in that run.  Boxes of the pool differ in the clock they sustain, so
+        # the fractions "at the measured clock" are taken inside the counter run alone (busy
+        # cycles over elapsed cycles of the same launch), not against this run's kernel time.
+        cycles = COUNTERS["gui_active_cycles"]
+        clock_ghz = cycles / (COUNTERS["pmc_launch_ms"] * 1e-3) / 1e9
         lane_ops = COUNTERS["valu_wave_instructions"] * 64
         alu_achieved = lane_ops / (kern_avg_ms * 1e-3) / 1e12
         alu = {"bound": "alu", "achieved": round(alu_achieved, 2), "peak": round(VALU_PEAK_TOPS, 2),
                "unit": "T 32-bit lane-ops/s", "frac": round(alu_achieved / VALU_PEAK_TOPS, 4),
                "measured_clock_GHz": round(clock_ghz, 3),
-               "frac_at_measured_clock": round(alu_achieved / (256 * 64 * clock_ghz / 1e3), 4),
+               "frac_at_measured_clock": round(lane_ops / (256 * 128 * cycles), 4),
                "valu_ops_per_payload_byte": round(lane_ops / payload, 2),
                "lds_lookups_per_payload_byte": round(COUNTERS["lds_wave_instructions"] * 64 / payload, 2)}
         # the resource that binds: cycles in which a CU's LDS pipe is serving lookups (a 64-lane
@@ -427,7 +488,7 @@ def main():
         lds = {"bound": "lds", "achieved": round(lds_achieved, 1), "peak": round(LDS_PEAK_GCYCLES, 1),
                "unit": "G LDS-pipe cycles/s", "frac": round(lds_achieved / LDS_PEAK_GCYCLES, 4),
                "measured_clock_GHz": round(clock_ghz, 3),
-               "frac_at_measured_clock": round(lds_achieved / (256 * clock_ghz), 4),
+               "frac_at_measured_clock": round(COUNTERS["lds_active_cycles"] / (256 * cycles), 4),
                "lds_cycles_per_payload_byte": round(COUNTERS["lds_active_cycles"] / payload, 4)}
 
     out = {
