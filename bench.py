@@ -312,6 +312,8 @@ def measure_workload(pgcm, torch, w, args, steps, warmup, headline):
 
     key = pgcm.expand_key(w.key) if w.key.size == 32 else pgcm.expand_key_bytes(w.key)
     pgcm.set_unit_bytes(key, args.unit_bytes)
+    if args.matrix_hash:
+        pgcm.set_matrix_hash(key, True)
     b = DeviceBatch(w, w.payload_device())
     if args.host_bounce:
         b.cipher = torch.zeros(w.total_bytes, dtype=torch.uint8, pin_memory=True)
@@ -392,6 +394,8 @@ def main():
                     help="IV length; the headline (and the paper's transport) is 12")
     ap.add_argument("--unit-bytes", type=int, default=0,
                     help="force the scheduler's unit size (1024 .. 16384); 0: its own choice")
+    ap.add_argument("--matrix-hash", action="store_true",
+                    help="GHASH row multiplication on the matrix cores instead of the LDS table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-chunks", type=int, default=0)
     ap.add_argument("--host-bounce", action="store_true",
@@ -464,7 +468,7 @@ def main():
     alu = None
     lds = None
     if (COUNTERS["workload"] == w.name and COUNTERS["sources_sha256"] == sources_sha256()
-            and not args.host_bounce and args.unit_bytes == 0):
+            and not args.host_bounce and args.unit_bytes == 0 and not args.matrix_hash):
         traffic = int(1024 * (COUNTERS["fetch_size_kib"] * COUNTERS["fetch_scale"] +
                               COUNTERS["write_size_kib"] * COUNTERS["write_scale"]))
         # The clock the chip ran at under this kernel, measured in the counter run:
@@ -509,6 +513,7 @@ def main():
                    "step": "encrypt batch + decrypt-verify batch, enqueued by the library's own "
                            "loop (pgcm_measure_passes)",
                    "unit_bytes": res["unit_bytes"],
+                   "row_hash": "matrix cores" if args.matrix_hash else "LDS table",
                    "key_bytes": args.key_bytes, "iv_bytes": args.iv_bytes,
                    "ciphertext": "pinned host memory" if args.host_bounce else "device memory"},
         "enc_GBps": res["enc_GBps"],

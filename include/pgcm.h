@@ -304,6 +304,16 @@ int pgcm_set_unit_bytes(pgcm_key_t *key, uint32_t unit_bytes);
 int pgcm_set_one_launch(pgcm_key_t *key, int enable);
 
 /*
+ * Tuning and test aid.  The kernel that does batches which fill the chip multiplies every
+ * lane's running GHASH sum by H^64 once per 1 KiB row: thirty-two lookups in a table in LDS.
+ * enable = 1 makes it a product with a fixed 128 x 128 matrix over GF(2) on the matrix cores
+ * instead (SP 800-38D 6.3: multiplication by a constant is linear), which takes a fifth of the
+ * LDS lookups' time off the LDS pipe and puts more work on the vector ALUs; measured 8 % slower
+ * on an MI355X, hence off by default.  Results are identical.
+ */
+int pgcm_set_matrix_hash(pgcm_key_t *key, int enable);
+
+/*
  * Measurement aid.  With timing enabled, every batch call also records a pair of HIP events on
  * its stream around the bulk kernel (the one launch that touches the payload: keystream, XOR
  * and GHASH of every unit; for the small-transfer path, its one kernel).  The library keeps the

@@ -16,7 +16,8 @@ EXPORTS = ("pgcm_expand_key", "pgcm_expand_key_bytes", "pgcm_free_key", "pgcm_en
            "pgcm_batch_unit_bytes", "pgcm_set_unit_bytes", "pgcm_key_tables_bytes",
            "pgcm_copy_key_tables",
            "pgcm_set_timing", "pgcm_last_bulk_kernel_ms", "pgcm_bulk_kernel_ms_history",
-           "pgcm_measure_passes", "pgcm_set_one_launch", "pgcm_bitsliced_keystream")
+           "pgcm_measure_passes", "pgcm_set_one_launch", "pgcm_set_matrix_hash",
+           "pgcm_bitsliced_keystream")
 
 
 class PgcmError(RuntimeError):
@@ -88,6 +89,8 @@ def load_library():
     lib.pgcm_bitsliced_keystream.restype = C.c_int
     lib.pgcm_set_one_launch.argtypes = [vp, C.c_int]
     lib.pgcm_set_one_launch.restype = C.c_int
+    lib.pgcm_set_matrix_hash.argtypes = [vp, C.c_int]
+    lib.pgcm_set_matrix_hash.restype = C.c_int
     lib.pgcm_set_timing.argtypes = [vp, C.c_int]
     lib.pgcm_set_timing.restype = C.c_int
     lib.pgcm_last_bulk_kernel_ms.argtypes = [vp, C.POINTER(C.c_float)]
@@ -355,7 +358,8 @@ def plan_units(length):
 
 def copy_key_tables(key: Key) -> dict:
     """pgcm_copy_key_tables, taken apart: rk (60 uint32), rounds, te (4, 256) uint32, h (16 uint8),
-    ghash (31, 512, 16) uint8"""
+    ghash (31, 512, 16) uint8, row_matrix (4, 2, 64, 4) uint32: [product tile][depth slice][lane]
+    [register] of the matrix-core operands of the multiplication by H^64"""
     n = int(load_library().pgcm_key_tables_bytes())
     raw = np.zeros(n, np.uint8)
     _check(load_library().pgcm_copy_key_tables(key.handle, raw.ctypes.data, n))
@@ -363,7 +367,8 @@ def copy_key_tables(key: Key) -> dict:
     out = {"rk": words[:60].copy(), "rounds": int(words[60]),
            "te": raw[256:256 + 4096].view(np.uint32).reshape(4, 256).copy(),
            "h": raw[4352:4368].copy(),
-           "ghash": raw[4368:].reshape(-1, 512, 16).copy()}
+           "ghash": raw[4368:4368 + 31 * 8192].reshape(31, 512, 16).copy(),
+           "row_matrix": raw[4368 + 31 * 8192:].view(np.uint32).reshape(4, 2, 64, 4).copy()}
     raw[:] = 0
     return out
 
@@ -381,6 +386,11 @@ def bitsliced_keystream(key: Key, iv, ctr_base: int, nblocks: int, out, stream=N
         raise ValueError("IVs are 12 bytes")
     _check(load_library().pgcm_bitsliced_keystream(key.handle, v.ctypes.data, ctr_base, nblocks,
                                                    _dev_ptr(out), _stream_handle(stream)))
+
+
+def set_matrix_hash(key: Key, enable: bool):
+    """pgcm_set_matrix_hash"""
+    _check(load_library().pgcm_set_matrix_hash(key.handle, 1 if enable else 0))
 
 
 def set_one_launch(key: Key, enable: bool):

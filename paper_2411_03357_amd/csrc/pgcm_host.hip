@@ -140,6 +140,7 @@ struct pgcm_key {
     int rounds = 0;  // 10, 12 or 14
     uint32_t forced_unit_power = 0;  // 0: chosen per batch
     bool one_launch = true;          // batches of few chunks that do not fill the chip: one kernel
+    bool matrix_hash = false;        // unit kernel: GHASH row multiplication on the matrix cores
     KeyTables* tables = nullptr;  // device
     std::mutex mu;                 // guards `contexts` and the binding fields of each context
     std::vector<Context*> contexts;
@@ -327,14 +328,26 @@ int end_of_batch(Context* c, int s, hipStream_t stream) {
 constexpr size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // the kernels that run the cipher are compiled once per round count
-template <bool kDecrypt, class... Args>
-void launch_bulk(int rounds, dim3 grid, hipStream_t stream, Args... args) {
+template <bool kDecrypt, bool kMatrixHash, class... Args>
+void launch_bulk_rounds(int rounds, dim3 grid, hipStream_t stream, Args... args) {
     if (rounds == 10)
-        hipLaunchKernelGGL((bulk_kernel<kDecrypt, 10>), grid, dim3(kGroupThreads), 0, stream, args...);
+        hipLaunchKernelGGL((bulk_kernel<kDecrypt, 10, kMatrixHash>), grid, dim3(kGroupThreads), 0,
+                           stream, args...);
     else if (rounds == 12)
-        hipLaunchKernelGGL((bulk_kernel<kDecrypt, 12>), grid, dim3(kGroupThreads), 0, stream, args...);
+        hipLaunchKernelGGL((bulk_kernel<kDecrypt, 12, kMatrixHash>), grid, dim3(kGroupThreads), 0,
+                           stream, args...);
     else
-        hipLaunchKernelGGL((bulk_kernel<kDecrypt, 14>), grid, dim3(kGroupThreads), 0, stream, args...);
+        hipLaunchKernelGGL((bulk_kernel<kDecrypt, 14, kMatrixHash>), grid, dim3(kGroupThreads), 0,
+                           stream, args...);
+}
+
+// ... and once per engine of the row hash (matrix cores or LDS tables)
+template <bool kDecrypt, class... Args>
+void launch_bulk(int rounds, bool matrix_hash, dim3 grid, hipStream_t stream, Args... args) {
+    if (matrix_hash)
+        launch_bulk_rounds<kDecrypt, true>(rounds, grid, stream, args...);
+    else
+        launch_bulk_rounds<kDecrypt, false>(rounds, grid, stream, args...);
 }
 
 template <bool kDecrypt, class... Args>
@@ -749,13 +762,13 @@ int run_unit_batch(pgcm_key* key, Context* ctx, const BatchArgs& a, const BatchP
         if (groups > (uint32_t)key->num_cu) groups = (uint32_t)key->num_cu;
         rc_timing = record_timing_start(key, a.stream);
         if (a.decrypt)
-            launch_bulk<true>(key->rounds, dim3(groups), a.stream, kt, d_desc, d_ubase, d_coarse,
-                              p.nunits, p.unit_power, d_counter, a.ivs, (const Block*)d_j0, d_ekj0,
-                              d_sets);
+            launch_bulk<true>(key->rounds, key->matrix_hash, dim3(groups), a.stream, kt, d_desc,
+                              d_ubase, d_coarse, p.nunits, p.unit_power, d_counter, a.ivs,
+                              (const Block*)d_j0, d_ekj0, d_sets);
         else
-            launch_bulk<false>(key->rounds, dim3(groups), a.stream, kt, d_desc, d_ubase, d_coarse,
-                               p.nunits, p.unit_power, d_counter, a.ivs, (const Block*)d_j0,
-                               d_ekj0, d_sets);
+            launch_bulk<false>(key->rounds, key->matrix_hash, dim3(groups), a.stream, kt, d_desc,
+                               d_ubase, d_coarse, p.nunits, p.unit_power, d_counter, a.ivs,
+                               (const Block*)d_j0, d_ekj0, d_sets);
         if (rc_timing == PGCM_OK) rc_timing = record_timing_stop(key, a.stream);
     }
     for (uint32_t l = 0; l < kMaxLevels; ++l) {
@@ -1186,6 +1199,12 @@ int pgcm_bitsliced_keystream(pgcm_key_t* key, const uint8_t iv[12], uint32_t ctr
         hipLaunchKernelGGL(pgcm_bitsliced::keystream_kernel<14>, grid, block, 0, stream, kt, w[0],
                            w[1], w[2], ctr_base, o);
     PGCM_HIP(hipGetLastError());
+    return PGCM_OK;
+}
+
+int pgcm_set_matrix_hash(pgcm_key_t* key, int enable) {
+    if (key == nullptr) return PGCM_ERR_ARG;
+    key->matrix_hash = enable != 0;
     return PGCM_OK;
 }
 

@@ -11,8 +11,9 @@ __global__ void expand_key_kernel(KeyTables* kt, const uint32_t* key_words, uint
 __global__ void j0_kernel(const KeyTables* kt, const ChunkDesc* chunks, const uint8_t* ivs,
                           uint32_t iv_len, uint32_t nchunks, Block* j0);
 
-// kRounds: 10, 12 or 14
-template <bool kDecrypt, int kRounds>
+// kRounds: 10, 12 or 14; kMatrixHash: the GHASH multiplication of every row runs on the matrix
+// cores (from KeyTables::row_matrix) instead of table lookups in LDS
+template <bool kDecrypt, int kRounds, bool kMatrixHash>
 __global__ void bulk_kernel(const KeyTables* kt, const ChunkDesc* chunks,
                             const uint32_t* unit_base, const uint32_t* coarse_map,
                             uint32_t nunits_total, uint32_t unit_power, uint32_t* counter,

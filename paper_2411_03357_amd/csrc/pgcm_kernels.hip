@@ -239,6 +239,29 @@ __global__ __launch_bounds__(1024) void expand_key_kernel(KeyTables* __restrict_
         x.w[byte / 4] = bits << (8 * (byte % 4));
         kt->ghash[k][idx] = gf_to_block(gf_mul_bits(gf_from_block(x), powers[k]));
     }
+
+    // Multiplication by H^64 as a 128 x 128 matrix over GF(2), laid out as operands of the
+    // 4-bit floating-point matrix instruction (see GhashRowMatrix): cols[b] = x^b * H^64 for the
+    // block whose only set bit is bit b % 32 of word b / 32.
+    __shared__ Block cols[128];
+    if (tid < 128) {
+        Block x{{0, 0, 0, 0}};
+        x.w[tid / 32] = 1u << (tid % 32);
+        cols[tid] = gf_to_block(gf_mul_bits(gf_from_block(x), powers[kRowPower]));
+    }
+    __syncthreads();
+    for (uint32_t e = tid; e < kRowMatrixWords; e += blockDim.x) {
+        const uint32_t r = e % 4, lane = (e / 4) % 64, ks = (e / 256) % 2, mt = e / 512;
+        // the operand row this lane holds, the product bit it makes, the operand quarter
+        const uint32_t ml = lane % 32, h = lane / 32, reg = 4 * (ml / 8) + ml % 4;
+        const uint32_t word = 2 * ((ml / 4) % 2) + mt / 2, bit = 16 * (reg / 8) + 8 * (mt % 2) + reg % 8;
+        uint32_t v = 0;
+        for (uint32_t j = 0; j < 8; ++j) {
+            const uint32_t in = 32 * r + 4 * j + 2 * ks + h;
+            if ((cols[in].w[word] >> bit) & 1u) v |= 0x2u << (4 * j);  // 1.0 in e2m1
+        }
+        kt->row_matrix[e] = v;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -490,6 +513,7 @@ __device__ __forceinline__ uint32_t nibble_offset(uint32_t v, uint32_t mask_f0) 
 // eight XORs each) so that the steps can be spread over the AES rounds of the same row: the
 // hash arithmetic then fills the time the wavefront would wait for round-table lookups.
 struct GhashRowMul {
+    static constexpr bool kMatrix = false;
     uint32_t table; // LDS address of the nibble table of H^64
     uint32_t w[4];  // the multiplicand
     uint32_t t;     // current word << 4: its byte k carries the low nibble of byte k
@@ -521,16 +545,143 @@ struct GhashRowMul {
     }
 };
 
+// Y * H^64 on the matrix cores.  Multiplication by a constant is linear over GF(2): product bit
+// m is the parity of the number of bits k with M[m][k] = Y[k] = 1, and the matrix instruction
+// counts those for 32 product bits of 32 lanes at once when every bit is spread out to a 4-bit
+// floating-point number (0 or 1.0).  Per row of 64 lanes: 4 product tiles x 2 column groups (lanes
+// 0..31, lanes 32..63) x 2 instructions of depth 64.  Products are scaled down into the denormal
+// range, where a float's pattern is the integer it counts in units of 2^-149 (the matrix
+// pipeline keeps denormals, in its results and in the sum it continues from), and rows are
+// scaled apart: result register i of a lane counts in units of 2^(i % 8), and the second tile of
+// a pair shares the first one's registers, another 2^8 up.  So one register holds two counts
+// (each at most 128) whose lowest bits, the parities, sit at bits i % 8 and 8 + i % 8: one
+// masked OR per register collects them, eight registers to a half word.
+// No table lookups: the 8 KiB matrix image is read from LDS, 16 bytes per lane and instruction.
+//
+// Operand layout of v_mfma_scale_f32_32x32x64_f8f6f4 with 4-bit operands: lane l holds row (or
+// column) l % 32, depth elements 32 (l / 32) .. + 31, eight to a register, lowest nibble first;
+// one scale (a power of two, biased by 127, in byte 0) per lane.  Result register i of lane l is
+// row 8 (i / 4) + 4 (l / 32) + i % 4 of column l % 32.
+// Depth element <-> bit of Y: quarter c = 0..3 of the depth holds bits 4 j + c of the four words,
+// left where they are inside their nibble (worth 0.5, 1.0, 2.0; bit 3 would be the sign and is
+// moved down one place), the lane's scale making up for it.  A column's quarters 0, 2 belong in
+// lanes 0..31 and 1, 3 in lanes 32..63: one swap of lane halves per register serves both groups.
+// Product bit <-> row: lanes 0..31 make words 0 and 1 of both groups' columns, lanes 32..63
+// words 2 and 3; tile pair p makes word 2 (l / 32) + p, register i of tile 2 p + f its bit
+// 16 (i / 8) + 8 f + i % 8 (KeyTables::row_matrix is laid out to match).
+typedef int v8i32 __attribute__((ext_vector_type(8)));
+typedef float v16f32 __attribute__((ext_vector_type(16)));
+
+struct GhashRowMatrix {
+    static constexpr bool kMatrix = true;
+    uint32_t image;    // LDS address of this lane's first piece of the matrix image
+    uint32_t scale_b;  // scale of this lane's quarter of the first depth slice
+    uint32_t scale_a;  // scale of this lane's matrix row in the first tile of a pair
+    uint32_t scale_a2; // ... in the second
+    uint32_t q[4][4];  // operand quarters; after begin(): q[g], q[2 + g] are group g's operands
+    uint32_t out[2][2];
+    u32x4 a0, a1;
+    v16f32 acc;
+    uint32_t z0, z1, z2, z3;
+
+    // matrix entries (1.0) are scaled to 2^-127 and up, the other operand's to 2^-22
+    static constexpr int kScaleHalf = 127 - 23;  // quarters 2 and 3 hold 2.0
+
+    __device__ __forceinline__ void init(uint32_t lds_table, uint32_t lane) {
+        image = lds_table + lane * 16;
+        scale_b = lane < 32 ? 127u - 21u : 127u - 22u;  // quarter 0 holds 0.5, quarter 1 1.0
+        const uint32_t row = lane & 31, reg = 4 * (row / 8) + row % 4;
+        scale_a = reg % 8;  // 2^(reg % 8 - 127)
+        scale_a2 = scale_a + 8;
+    }
+    __device__ __forceinline__ void begin(const uint32_t w[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            q[0][i] = w[i] & 0x11111111u;
+            q[1][i] = w[i] & 0x22222222u;
+            q[2][i] = w[i] & 0x44444444u;
+            q[3][i] = (w[i] >> 1) & 0x44444444u;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            // lanes 32..63 of the first operand change places with lanes 0..31 of the second
+            auto a = __builtin_amdgcn_permlane32_swap(q[0][i], q[1][i], false, false);
+            q[0][i] = a[0], q[1][i] = a[1];
+            auto b = __builtin_amdgcn_permlane32_swap(q[2][i], q[3][i], false, false);
+            q[2][i] = b[0], q[3][i] = b[1];
+        }
+    }
+    // Chain C = 2 * pair + group is four instructions into one set of sums, in two halves F
+    // (the pair's tiles), each in three steps that the caller spreads over an AES round: the
+    // tile's two matrix pieces are fetched, the first instruction starts or continues the sums,
+    // the second (which has to wait for the first) follows.
+    template <int C, int F>
+    __device__ __forceinline__ void load() {
+        constexpr int mt = 2 * (C / 2) + F;
+        a0 = lds_read128(image + (mt * 2 + 0) * 1024);
+        a1 = lds_read128(image + (mt * 2 + 1) * 1024);
+    }
+    template <int C, int F>
+    __device__ __forceinline__ void first() {
+        constexpr int g = C % 2;
+        const v8i32 A0 = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, 0, 0, 0, 0};
+        const v8i32 B0 = {(int)q[g][0], (int)q[g][1], (int)q[g][2], (int)q[g][3], 0, 0, 0, 0};
+        if constexpr (F == 0) {
+            const v16f32 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f,
+                                 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+            acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A0, B0, zero, 4, 4, 0,
+                                                                   (int)scale_a, 0, (int)scale_b);
+        } else {
+            acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A0, B0, acc, 4, 4, 0,
+                                                                   (int)scale_a2, 0, (int)scale_b);
+        }
+    }
+    template <int C, int F>
+    __device__ __forceinline__ void second() {
+        constexpr int g = C % 2;
+        const v8i32 A1 = {(int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w, 0, 0, 0, 0};
+        const v8i32 B1 = {(int)q[2 + g][0], (int)q[2 + g][1], (int)q[2 + g][2], (int)q[2 + g][3],
+                          0, 0, 0, 0};
+        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+            A1, B1, acc, 4, 4, 0, (int)(F == 0 ? scale_a : scale_a2), 0, kScaleHalf);
+    }
+    // the chain's thirty-two parities: registers 0..7 give the low half word, 8..15 the high
+    template <int C>
+    __device__ __forceinline__ void consume() {
+        uint32_t lo = __float_as_uint(acc[0]) & 0x0101u, hi = __float_as_uint(acc[8]) & 0x0101u;
+#pragma unroll
+        for (int i = 1; i < 8; ++i) {
+            // (sum & mask) | collected, in one instruction (truth table 0xEA)
+            const uint32_t mask = 0x0101u << i;
+            lo = __builtin_amdgcn_bitop3_b32(__float_as_uint(acc[i]), mask, lo, 0xEA);
+            hi = __builtin_amdgcn_bitop3_b32(__float_as_uint(acc[8 + i]), mask, hi, 0xEA);
+        }
+        out[C % 2][C / 2] = (hi << 16) | lo;
+    }
+    // lanes 0..31 made words 0, 1 of both groups' columns, lanes 32..63 words 2, 3: the halves
+    // of every column come home
+    __device__ __forceinline__ void finish() {
+        auto r0 = __builtin_amdgcn_permlane32_swap(out[0][0], out[1][0], false, false);
+        auto r1 = __builtin_amdgcn_permlane32_swap(out[0][1], out[1][1], false, false);
+        z0 = r0[0], z1 = r1[0], z2 = r0[1], z3 = r1[1];
+    }
+};
+
 // E_K(J0[0..95] || be32(ctr)) for this lane's counter, with the row's GHASH multiplication G
 // riding along; rk is wave-uniform (scalar registers).  Between rounds the state is carried
 // without its round key: the key bytes are added while the next round's addresses are formed.
 // The sixteen byte steps of G: three in round 1, the other thirteen spread evenly over rounds
 // 2 .. kRounds (one each for AES-256, one or two each for the shorter keys).
-template <int kRounds>
+// On the matrix cores the multiplication is four chains of four instructions instead: chain c is
+// issued in rounds 2 c + 2 and 2 c + 3 (two matrix pieces fetched ahead of each round's lookups,
+// two instructions, one before and one after the round's sums) and its result packed in the
+// middle of round 2 c + 4, so that neither the fetch nor the matrix pipeline is waited for.
+template <int kRounds, class Hash>
 __device__ __forceinline__ void aes_ctr_lds(const uint32_t* __restrict__ rk, AesAddr& A,
-                                               const CtrConsts& C, uint32_t ctr, GhashRowMul& G,
+                                               const CtrConsts& C, uint32_t ctr, Hash& G,
                                                uint32_t base, uint32_t& o0, uint32_t& o1,
                                                uint32_t& o2, uint32_t& o3) {
+    static_assert(kRounds >= 10, "eight chains and their packing need rounds 2 .. 10");
     // round 1: the counter is the last word, big endian: state byte k is counter byte 3 - k
     key_xor_into_addr<3, 0>(A.a[3][3], rk[3], ctr);
     key_xor_into_addr<2, 1>(A.a[3][2], rk[3], ctr);
@@ -538,11 +689,13 @@ __device__ __forceinline__ void aes_ctr_lds(const uint32_t* __restrict__ rk, Aes
     key_xor_into_addr<0, 3>(A.a[3][0], rk[3], ctr);
     uint32_t l0 = te_read<3>(A.a[3][3], base), l1 = te_read<2>(A.a[3][2], base), l2 = te_read<1>(A.a[3][1], base),
              l3 = te_read<0>(A.a[3][0], base);
-    G.issue<0>();
+    if constexpr (!Hash::kMatrix) G.template issue<0>();
     uint32_t u0 = C.k[0] ^ l0, u1 = C.k[1] ^ l1, u2 = C.k[2] ^ l2, u3 = C.k[3] ^ l3;
-    G.consume();
-    G.step<1>();
-    G.step<2>();
+    if constexpr (!Hash::kMatrix) {
+        G.consume();
+        G.template step<1>();
+        G.template step<2>();
+    }
     __builtin_amdgcn_sched_barrier(0);
     static_for<2, kRounds + 1>([&](auto round) __attribute__((always_inline)) {
         constexpr int r = decltype(round)::value;
@@ -550,6 +703,10 @@ __device__ __forceinline__ void aes_ctr_lds(const uint32_t* __restrict__ rk, Aes
                       step_end = 3 + (13 * (r - 1)) / (kRounds - 1);
         static_assert(step_end - step_begin == 1 || step_end - step_begin == 2, "hash steps");
         const uint32_t* k = rk + 4 * (r - 1);
+        if constexpr (Hash::kMatrix) {
+            if constexpr (r <= 9) G.template load<(r - 2) / 2, (r - 2) % 2>();
+            __builtin_amdgcn_sched_barrier(0);
+        }
         key_xor_into_addr<0, 0>(A.a[0][0], k[0], u0);
         key_xor_into_addr<1, 1>(A.a[0][1], k[0], u0);
         key_xor_into_addr<2, 2>(A.a[0][2], k[0], u0);
@@ -574,7 +731,14 @@ __device__ __forceinline__ void aes_ctr_lds(const uint32_t* __restrict__ rk, Aes
                  t02 = te_read<2>(A.a[0][2], base), t13 = te_read<3>(A.a[1][3], base);
         uint32_t t30 = te_read<0>(A.a[3][0], base), t01 = te_read<1>(A.a[0][1], base),
                  t12 = te_read<2>(A.a[1][2], base), t23 = te_read<3>(A.a[2][3], base);
-        G.template issue<step_begin>();
+        if constexpr (Hash::kMatrix) {
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (r >= 4 && r <= 10 && r % 2 == 0) G.template consume<(r - 4) / 2>();
+            if constexpr (r <= 9) G.template first<(r - 2) / 2, (r - 2) % 2>();
+            __builtin_amdgcn_sched_barrier(0);
+        } else {
+            G.template issue<step_begin>();
+        }
         if constexpr (r < kRounds) {
             u0 = xor3(t00, t11, t22) ^ t33;
             u1 = xor3(t10, t21, t32) ^ t03;
@@ -593,8 +757,15 @@ __device__ __forceinline__ void aes_ctr_lds(const uint32_t* __restrict__ rk, Aes
             o2 = last(t20, t31, t02, t13, rk[4 * kRounds + 2]);
             o3 = last(t30, t01, t12, t23, rk[4 * kRounds + 3]);
         }
-        G.consume();
-        if constexpr (step_end - step_begin == 2) G.template step<step_begin + 1>();
+        if constexpr (Hash::kMatrix) {
+            if constexpr (r <= 9) {
+                __builtin_amdgcn_sched_barrier(0);  // after the round's sums, not before
+                G.template second<(r - 2) / 2, (r - 2) % 2>();
+            }
+        } else {
+            G.consume();
+            if constexpr (step_end - step_begin == 2) G.template step<step_begin + 1>();
+        }
         // keep every round's hash step with its round: without this the compiler sinks the
         // hash XORs to the end of the block and spills the table entries they wait for
         __builtin_amdgcn_sched_barrier(0);
@@ -635,7 +806,9 @@ __device__ __forceinline__ void ghash_mul_lds(uint32_t base, uint32_t y[4]) {
 // the AAD state.  One code path serves both kinds: idle lanes run the cipher on a dummy counter,
 // touch no payload and keep a zero hash state.
 // kThrough: the payload is written through to memory (see global_write128_through).
-template <bool kDecrypt, int kRounds, bool kThrough = false>
+// kMatrixHash: the hash multiplication runs on the matrix cores; the first 8 KiB of the LDS
+// object then hold the matrix image instead of the nibble table.
+template <bool kDecrypt, int kRounds, bool kThrough = false, bool kMatrixHash = false>
 __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAddr& A,
                                          const CtrConsts& C, uint32_t ctr1, const uint8_t* src,
                                          uint8_t* dst, uint64_t len, int64_t blk, bool edge,
@@ -672,11 +845,17 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
     // counter block inc32^(blk + 1)(J0): the first 96 bits of J0, then its counter field plus
     // blk + 1 modulo 2^32 (SP 800-38D 6.2, 7.1 step 3; ctr1 is that field plus 1, 2 for a 96-bit
     // IV) ... while the hash state moves one row along: Y <- Y * H^64
-    GhashRowMul G;
-    G.table = lds_base;  // the nibble table is the first member of BulkLds
-    G.w[0] = y[0], G.w[1] = y[1], G.w[2] = y[2], G.w[3] = y[3];
+    std::conditional_t<kMatrixHash, GhashRowMatrix, GhashRowMul> G;
+    if constexpr (kMatrixHash) {
+        G.init(lds_base, __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)));
+        G.begin(y);
+    } else {
+        G.table = lds_base;  // the nibble table is the first member of BulkLds
+        G.w[0] = y[0], G.w[1] = y[1], G.w[2] = y[2], G.w[3] = y[3];
+    }
     uint32_t s0, s1, s2, s3;
     aes_ctr_lds<kRounds>(rk, A, C, (uint32_t)blk + ctr1, G, lds_base, s0, s1, s2, s3);
+    if constexpr (kMatrixHash) G.finish();
     uint32_t o0 = x0 ^ s0, o1 = x1 ^ s1, o2 = x2 ^ s2, o3 = x3 ^ s3;
 
     if (whole) {
@@ -734,6 +913,7 @@ namespace {
 // sixteen 16-byte pieces, eight per table of its pair; every thread fetches the eight entries
 // its pieces need at once (independent loads) and writes each four times over in one store, and
 // a wavefront's store covers four whole rows, so the stores run at the full LDS width.
+template <bool kMatrixHash = false>
 __device__ __forceinline__ void fill_bulk_lds(BulkLds& lds, const KeyTables* __restrict__ kt,
                                               uint32_t tid) {
     constexpr uint32_t kPieces = kLdsTeBytes / 16;
@@ -752,14 +932,18 @@ __device__ __forceinline__ void fill_bulk_lds(BulkLds& lds, const KeyTables* __r
         const u32x4 q = {v[k], v[k], v[k], v[k]};
         te4[k * kGroupThreads + tid] = q;
     }
-    for (uint32_t i = tid; i < kNibbleTableEntries; i += kGroupThreads)
-        lds.gh[i] = kt->ghash[kRowPower][i];
+    for (uint32_t i = tid; i < kNibbleTableEntries; i += kGroupThreads) {
+        if constexpr (kMatrixHash)
+            lds.gh[i] = reinterpret_cast<const Block*>(kt->row_matrix)[i];
+        else
+            lds.gh[i] = kt->ghash[kRowPower][i];
+    }
 }
 
 // One unit of one chunk, walked by one wavefront in rows of 64 blocks: keystream, XOR, and the
 // lane's GHASH sum over the unit's rows, sum over rows r of C(r, lane) * (H^64)^(rows after r),
 // left in y.  unit 0 also takes "block -1", whose counter block is J0, and stores E_K(J0).
-template <bool kDecrypt, int kRounds, bool kThrough = false>
+template <bool kDecrypt, int kRounds, bool kThrough = false, bool kMatrixHash = false>
 __device__ __forceinline__ void walk_unit(const KeyTables* __restrict__ kt,
                                           const uint32_t* __restrict__ rk, AesAddr& A,
                                           uint32_t lane, uint32_t lds_base, const uint8_t* src,
@@ -786,8 +970,9 @@ __device__ __forceinline__ void walk_unit(const KeyTables* __restrict__ kt,
     int64_t row_blk = b1 - (int64_t)nrows * kRowBlocks;
     for (uint32_t r = 0; r < nrows; ++r, row_blk += kRowBlocks) {
         const bool edge = row_blk <= 0 || (unit + 1 == nunits && r + 1 == nrows);
-        bulk_row<kDecrypt, kRounds, kThrough>(rk, A, C, ctr1, src, dst, len, row_blk + lane, edge,
-                                              aad_y, ekj0_out, lds_base, y);
+        bulk_row<kDecrypt, kRounds, kThrough, kMatrixHash>(rk, A, C, ctr1, src, dst, len,
+                                                           row_blk + lane, edge, aad_y, ekj0_out,
+                                                           lds_base, y);
     }
 }
 
@@ -802,7 +987,8 @@ __device__ __forceinline__ void walk_unit(const KeyTables* __restrict__ kt,
 // chunks); coarse_map[i >> kCoarseShift] is a chunk at or before the right one.
 // sets[i * 64 + lane] receives lane's GHASH sum over the unit's rows.
 // ivs: 96-bit IVs (a chunk's at its `index`), read when j0 is null; otherwise j0[c] is chunk c's J0.
-template <bool kDecrypt, int kRounds>
+// kMatrixHash: see bulk_row.
+template <bool kDecrypt, int kRounds, bool kMatrixHash>
 __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     const KeyTables* __restrict__ kt, const ChunkDesc* __restrict__ chunks,
     const uint32_t* __restrict__ unit_base, const uint32_t* __restrict__ coarse_map,
@@ -815,7 +1001,7 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     const uint32_t lds_base = lds_offset(&lds);
 
     const uint32_t tid = threadIdx.x;
-    fill_bulk_lds(lds, kt, tid);
+    fill_bulk_lds<kMatrixHash>(lds, kt, tid);
     __syncthreads();
 
     const uint32_t lane = tid & 63;
@@ -837,9 +1023,9 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
         const ChunkDesc* __restrict__ cd = chunks + chunk;
         const Block j = chunk_j0(kt, ivs, j0, chunk, cd->index);
         uint32_t y[4];
-        walk_unit<kDecrypt, kRounds>(kt, rk, A, lane, lds_base, cd->src, cd->dst, cd->len,
-                                     cd->aad, cd->aad_len, item - cd->unit_base, cd->nunits,
-                                     cd->first_blocks, unit_power, j, ekj0 + chunk, y);
+        walk_unit<kDecrypt, kRounds, false, kMatrixHash>(
+            kt, rk, A, lane, lds_base, cd->src, cd->dst, cd->len, cd->aad, cd->aad_len,
+            item - cd->unit_base, cd->nunits, cd->first_blocks, unit_power, j, ekj0 + chunk, y);
         sets[(uint64_t)item * 64 + lane] = Block{{y[0], y[1], y[2], y[3]}};
         if (one_each) break;
         if (lane == 0)
@@ -849,16 +1035,22 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     }
 }
 
-#define PGCM_INSTANTIATE_BULK(D, R)                                                              \
-    template __global__ void bulk_kernel<D, R>(const KeyTables*, const ChunkDesc*, const uint32_t*, \
-                                               const uint32_t*, uint32_t, uint32_t, uint32_t*,      \
-                                               const uint8_t*, const Block*, Block*, Block*)
-PGCM_INSTANTIATE_BULK(false, 10);
-PGCM_INSTANTIATE_BULK(false, 12);
-PGCM_INSTANTIATE_BULK(false, 14);
-PGCM_INSTANTIATE_BULK(true, 10);
-PGCM_INSTANTIATE_BULK(true, 12);
-PGCM_INSTANTIATE_BULK(true, 14);
+#define PGCM_INSTANTIATE_BULK(D, R, M)                                                       \
+    template __global__ void bulk_kernel<D, R, M>(                                              \
+        const KeyTables*, const ChunkDesc*, const uint32_t*, const uint32_t*, uint32_t, uint32_t, \
+        uint32_t*, const uint8_t*, const Block*, Block*, Block*)
+PGCM_INSTANTIATE_BULK(false, 10, false);
+PGCM_INSTANTIATE_BULK(false, 12, false);
+PGCM_INSTANTIATE_BULK(false, 14, false);
+PGCM_INSTANTIATE_BULK(true, 10, false);
+PGCM_INSTANTIATE_BULK(true, 12, false);
+PGCM_INSTANTIATE_BULK(true, 14, false);
+PGCM_INSTANTIATE_BULK(false, 10, true);
+PGCM_INSTANTIATE_BULK(false, 12, true);
+PGCM_INSTANTIATE_BULK(false, 14, true);
+PGCM_INSTANTIATE_BULK(true, 10, true);
+PGCM_INSTANTIATE_BULK(true, 12, true);
+PGCM_INSTANTIATE_BULK(true, 14, true);
 #undef PGCM_INSTANTIATE_BULK
 
 // ------------------------------------------------------------------------------------------

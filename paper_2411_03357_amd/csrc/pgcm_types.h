@@ -42,6 +42,11 @@ constexpr uint32_t kMaxLevels = 4;     // 2^22 units (the GCM length limit) / 32
 constexpr uint32_t kNibbleTableEntries = 32 * 16;
 constexpr uint32_t kNumPowers = kUnitPower + kFanPower * kMaxLevels + 1;  // H^(2^0) .. H^(2^30)
 
+// Multiplication by H^64 is linear over GF(2): a 128 x 128 bit matrix.  As operands of the 4-bit
+// floating-point matrix instruction (an entry per nibble) it takes as much room as a nibble table.
+constexpr uint32_t kRowMatrixWords = 128 * 128 / 8;
+static_assert(kRowMatrixWords * 4 == kNibbleTableEntries * 16, "same room as a nibble table");
+
 struct alignas(16) Block {
     uint32_t w[4];  // bytes 4i..4i+3 of the block, loaded little-endian into w[i]
 };
@@ -54,6 +59,7 @@ struct alignas(16) KeyTables {
     uint32_t te[4][256];   // round tables: te[r][x] = MixColumns contribution of S(x) in row r
     Block h;               // GHASH key H = E_K(0^128)
     Block ghash[kNumPowers][kNibbleTableEntries];
+    uint32_t row_matrix[kRowMatrixWords];  // multiplication by H^64 as matrix-core operands
 };
 
 struct alignas(16) ChunkDesc {

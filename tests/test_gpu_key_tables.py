@@ -1,6 +1,7 @@
 """The tables the key set-up kernel leaves on the device, piece by piece against the oracle: key
 schedule (FIPS-197 5.2), round tables (S-box and MixColumns coefficients), H = E_K(0), and the
-nibble tables of H^(2^k), each entry being one GF(2^128) product (SP 800-38D 6.3)."""
+nibble tables of H^(2^k), each entry being one GF(2^128) product (SP 800-38D 6.3), and the
+multiplication by H^64 written out as a 128 x 128 matrix over GF(2) for the matrix cores."""
 import numpy as np
 import pytest
 
@@ -22,7 +23,7 @@ def test_device_tables_entry_by_entry(key_bytes):
     key = pgcm.expand_key_bytes(keyb)
     t = pgcm.copy_key_tables(key)
     key.free()
-    assert pgcm.load_library().pgcm_key_tables_bytes() == 256 + 4096 + 16 + 31 * 512 * 16
+    assert pgcm.load_library().pgcm_key_tables_bytes() == 256 + 4096 + 16 + 31 * 512 * 16 + 8192
 
     # key schedule
     rk = oracle.aes_key_expand(keyb)
@@ -60,3 +61,32 @@ def test_device_tables_entry_by_entry(key_bytes):
             for b in range(16):
                 assert np.array_equal(rows[:, a ^ b], rows[:, a] ^ rows[:, b])
         power = oracle.gf128_mul(power, power)               # H^(2^(k+1))
+
+
+    # Multiplication by H^64 as matrix-core operands.  Bit b of a block, as the kernels hold it, is
+    # bit b % 32 of the little-endian word b // 32.  Lane l of tile mt holds the matrix row whose
+    # sum lands in result register reg = 4 * (l % 32 // 8) + l % 4 and makes bit
+    # 16 * (reg // 8) + 8 * (mt % 2) + reg % 8 of product word 2 * ((l % 32 // 4) % 2) + mt // 2;
+    # nibble j of register r in depth slice ks is the entry for multiplicand bit
+    # 32 r + 4 j + 2 ks + l // 32: 2 (1.0 as a 4-bit float) where x^bit * H^64 has the product bit.
+    h64 = h
+    for _ in range(6):
+        h64 = oracle.gf128_mul(h64, h64)
+    cols = []
+    for b in range(128):
+        x = bytearray(16)
+        x[b // 8] = 1 << (b % 8)
+        cols.append(int.from_bytes(oracle.gf128_mul(bytes(x), h64), "little"))
+    m = t["row_matrix"]
+    for mt in range(4):
+        for ks in range(2):
+            for lane in range(64):
+                ml, half = lane % 32, lane // 32
+                reg = 4 * (ml // 8) + ml % 4
+                out_bit = 32 * (2 * ((ml // 4) % 2) + mt // 2) + 16 * (reg // 8) + 8 * (mt % 2) + reg % 8
+                for r in range(4):
+                    want = 0
+                    for j in range(8):
+                        if (cols[32 * r + 4 * j + 2 * ks + half] >> out_bit) & 1:
+                            want |= 2 << (4 * j)
+                    assert int(m[mt, ks, lane, r]) == want, (mt, ks, lane, r)

@@ -26,12 +26,16 @@ def _oracle_encrypt(w, host_buf, idx=None):
     return cts, tags
 
 
-def _full_parity(w, flip=None, iv_entry=None, unit_bytes=0):
+def _full_parity(w, flip=None, iv_entry=None, unit_bytes=0, matrix_hash=False):
     """encrypt + decrypt-verify of the whole workload compared with the oracle on every byte;
-    unit_bytes forces the scheduler's unit size (0: its own choice for the batch)"""
+    unit_bytes forces the scheduler's unit size (0: its own choice for the batch); matrix_hash
+    sends the batch through the unit kernel with its row hash on the matrix cores"""
     host = w.payload_host()
     key = expand(w)
     pgcm.set_unit_bytes(key, unit_bytes)
+    if matrix_hash:
+        pgcm.set_matrix_hash(key, True)
+        pgcm.set_one_launch(key, False)     # few chunks would otherwise skip the unit kernel
     b = DeviceBatch(w, torch.from_numpy(host).cuda(), iv_entry=iv_entry)
     b.cipher.fill_(0xEE)            # gaps between chunks must stay untouched
     b.encrypt(key)
@@ -112,6 +116,23 @@ def test_every_unit_size_full_parity(unit_bytes):
             pgcm.set_unit_bytes(key, bad)
         assert e.value.status == -1
     key.free()
+
+
+@pytest.mark.parametrize("unit_bytes", [0, 1024, 16384, 128 * 1024])
+def test_row_hash_on_matrix_cores_full_parity(unit_bytes):
+    """The unit kernel's other engine for Y * H^64 (a GF(2) matrix product on the matrix cores
+    instead of table lookups) on the same batches, byte for byte against the oracle: every length
+    class, tampered chunks, the four KV / weight / mixed batch shapes, forced unit sizes, and the
+    two shorter key lengths (other round counts are other kernels)."""
+    w = workloads.ragged_small()
+    last = int(w.lens[13]) - 1
+    _full_parity(w, flip=[(13, last, 7, "ct"), (25, 0, 0, "ct"), (2, 15, 3, "tag")],
+                 unit_bytes=unit_bytes or 2048, matrix_hash=True)
+    for cfg in (2, 3, 4, 5):
+        _full_parity(workloads.mini(cfg), unit_bytes=unit_bytes, matrix_hash=True)
+    for key_bytes in (16, 24):
+        _full_parity(workloads.with_cipher(workloads.mini(4), key_bytes, 12),
+                     unit_bytes=unit_bytes, matrix_hash=True)
 
 
 def test_small_transfer_path_full_parity():
