@@ -164,3 +164,50 @@ def test_full_size_decrypt_verify_every_chunk_against_the_oracle(cfg, capsys):
              % (cfg, lo, hi - 1, w.n, time.time() - t0))
     bad_gap = _gaps_hold(w, back, BACK_FILL)
     assert bad_gap is None, "bytes after chunk %d were written" % bad_gap
+
+
+@pytest.mark.parametrize("cfg", [2, 4])
+def test_full_size_matrix_hash_engine(cfg):
+    """The unit kernel's second engine for the row hash (GF(2) matrix product on the matrix cores)
+    at full size.  It shares everything but the multiplication Y * H^64 with the table engine,
+    whose output the tests above compare with the oracle chunk by chunk; here every ciphertext
+    byte, tag, verdict and output byte must equal the table engine's on the same inputs, with
+    the configuration's tampering (config 4 has none: three chunks are tampered with here), and
+    every ciphertext and tag is checked against libcrypto as well."""
+    w = workloads.FULL[cfg]()
+    key, b = _encrypt_on_gpu(w)                       # table engine
+    ref_cipher, ref_tags = b.cipher.clone(), b.tags.clone()
+    pgcm.set_matrix_hash(key, True)
+    b.cipher.fill_(CIPHER_FILL)
+    b.tags.zero_()
+    b.encrypt(key)
+    torch.cuda.synchronize()
+    assert torch.equal(b.cipher, ref_cipher) and torch.equal(b.tags, ref_tags)
+    differs = _first_chunk_libcrypto_disagrees_with(
+        w, b.plain.cpu().numpy(), b.cipher.cpu().numpy(), b.tags.cpu().numpy().reshape(-1, 16))
+    assert differs is None, "chunk %d: ciphertext or tag differs from libcrypto's" % differs
+
+    cipher_t, tags_t = ref_cipher, ref_tags.clone()
+    rejected = [7, w.n // 2, w.n - 1]
+    cipher_t[int(w.offsets[rejected[0]])] ^= 0x01                                   # first byte
+    cipher_t[int(w.offsets[rejected[1]]) + int(w.lens[rejected[1]]) - 1] ^= 0x80    # last byte
+    tags_t[16 * rejected[2] + 5] ^= 0x10
+    outs = []
+    for matrix in (False, True):
+        pgcm.set_matrix_hash(key, matrix)
+        b.back.fill_(BACK_FILL)
+        b.ok.fill_(9)
+        b.decrypt(key, src=cipher_t, tags=tags_t)
+        torch.cuda.synchronize()
+        outs.append((b.back.clone(), b.ok.clone()))
+    key.free()
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    ok = outs[1][1].cpu().numpy()
+    assert sorted(np.flatnonzero(ok == 0).tolist()) == rejected and int((ok == 1).sum()) == w.n - 3
+    for i in rejected:
+        off, ln = int(w.offsets[i]), int(w.lens[i])
+        assert not bool(outs[1][0][off:off + ln].any())
+    good = np.setdiff1d(np.arange(w.n), rejected)[:: max(1, w.n // 64)]
+    for i in good:
+        off, ln = int(w.offsets[i]), int(w.lens[i])
+        assert torch.equal(outs[1][0][off:off + ln], b.plain[off:off + ln])
