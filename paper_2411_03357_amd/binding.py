@@ -359,7 +359,8 @@ def plan_units(length):
 def copy_key_tables(key: Key) -> dict:
     """pgcm_copy_key_tables, taken apart: rk (60 uint32), rounds, te (4, 256) uint32, h (16 uint8),
     ghash (31, 512, 16) uint8, row_matrix (4, 2, 64, 4) uint32: [product tile][depth slice][lane]
-    [register] of the matrix-core operands of the multiplication by H^64"""
+    [register] of the matrix-core operands of the multiplication by H^64, ghash_lane (3, 512, 16)
+    uint8: nibble tables of H^3, H^12, H^48"""
     n = int(load_library().pgcm_key_tables_bytes())
     raw = np.zeros(n, np.uint8)
     _check(load_library().pgcm_copy_key_tables(key.handle, raw.ctypes.data, n))
@@ -368,7 +369,9 @@ def copy_key_tables(key: Key) -> dict:
            "te": raw[256:256 + 4096].view(np.uint32).reshape(4, 256).copy(),
            "h": raw[4352:4368].copy(),
            "ghash": raw[4368:4368 + 31 * 8192].reshape(31, 512, 16).copy(),
-           "row_matrix": raw[4368 + 31 * 8192:].view(np.uint32).reshape(4, 2, 64, 4).copy()}
+           "row_matrix": raw[4368 + 31 * 8192:4368 + 32 * 8192].view(np.uint32)
+                         .reshape(4, 2, 64, 4).copy(),
+           "ghash_lane": raw[4368 + 32 * 8192:].reshape(3, 512, 16).copy()}
     raw[:] = 0
     return out
 

@@ -183,6 +183,7 @@ __global__ __launch_bounds__(1024) void expand_key_kernel(KeyTables* __restrict_
                                                           const uint32_t* __restrict__ key_words,
                                                           uint32_t nk) {
     __shared__ Gf powers[kNumPowers];
+    __shared__ Gf lane_powers[kNumLanePowers];
     const uint32_t tid = threadIdx.x;
 
     // round tables: te[0][x] = (2s, s, s, 3s) in bytes 0..3, te[r] = te[0] rotated left by 8r bits
@@ -228,6 +229,9 @@ __global__ __launch_bounds__(1024) void expand_key_kernel(KeyTables* __restrict_
             p = gf_mul_bits(p, p);
             powers[k] = p;
         }
+        lane_powers[0] = gf_mul_bits(powers[1], powers[0]);  // H^3
+        lane_powers[1] = gf_mul_bits(powers[3], powers[2]);  // H^12
+        lane_powers[2] = gf_mul_bits(powers[5], powers[4]);  // H^48
     }
     __syncthreads();
     for (uint32_t e = tid; e < kNumPowers * kNibbleTableEntries; e += blockDim.x) {
@@ -238,6 +242,15 @@ __global__ __launch_bounds__(1024) void expand_key_kernel(KeyTables* __restrict_
         Block x{{0, 0, 0, 0}};
         x.w[byte / 4] = bits << (8 * (byte % 4));
         kt->ghash[k][idx] = gf_to_block(gf_mul_bits(gf_from_block(x), powers[k]));
+    }
+    for (uint32_t e = tid; e < kNumLanePowers * kNibbleTableEntries; e += blockDim.x) {
+        uint32_t k = e / kNibbleTableEntries, idx = e % kNibbleTableEntries;
+        uint32_t pos = idx / 16, val = idx % 16;
+        uint32_t byte = pos / 2;
+        uint32_t bits = (pos & 1) ? val : (val << 4);
+        Block x{{0, 0, 0, 0}};
+        x.w[byte / 4] = bits << (8 * (byte % 4));
+        kt->ghash_lane[k][idx] = gf_to_block(gf_mul_bits(gf_from_block(x), lane_powers[k]));
     }
 
     // Multiplication by H^64 as a 128 x 128 matrix over GF(2), laid out as operands of the
@@ -1134,6 +1147,90 @@ __device__ __forceinline__ void fold_lanes(uint32_t tree_tables, uint32_t y[4],
     for (int k = 0; k < 4; ++k) y[k] = __builtin_amdgcn_readlane(y[k], holder);
 }
 
+// The same fold for whole rows (every lane may hold a sum), in groups of four: three
+// multiplications deep instead of seven.  With l = 16 b + 4 c + j, H^(64 - l) =
+// H^(16 (3 - b)) * H^(4 - j) * H^(4 (3 - c)).  In every step the four rows of sixteen lanes take
+// one power each (a wavefront's table lookups collide in the LDS banks unless the lanes that are
+// served together, sixteen neighbours, read one and the same table), and the four rows' products
+// are then added up, every row keeping the sum:
+//   1. row b multiplies its own sums by H^(16 (3 - b)); after the addition every row holds, at
+//      place q = 4 c + j, the value V_q of the sixteen columns;
+//   2. row r takes element j = r of every quad and multiplies by H^(4 - r); after the addition
+//      every row holds W_c in all of quad c;
+//   3. row r takes W_r and multiplies by H^(4 (3 - r)); the addition leaves the chunk's GHASH
+//      state in every lane.
+// Tables, 8 KiB apart from lane_tables: H^1, H^2, H^3, H^4, H^8, H^12, H^16, H^32, H^48.
+constexpr uint32_t kLaneTables = 9;
+
+__device__ __forceinline__ void copy_lane_tables(Block (*tables)[kNibbleTableEntries],
+                                                 const KeyTables* __restrict__ kt, uint32_t tid,
+                                                 uint32_t nthreads) {
+    for (uint32_t i = tid; i < kNibbleTableEntries; i += nthreads) {
+        tables[0][i] = kt->ghash[0][i];
+        tables[1][i] = kt->ghash[1][i];
+        tables[2][i] = kt->ghash_lane[0][i];
+        tables[3][i] = kt->ghash[2][i];
+        tables[4][i] = kt->ghash[3][i];
+        tables[5][i] = kt->ghash_lane[1][i];
+        tables[6][i] = kt->ghash[4][i];
+        tables[7][i] = kt->ghash[5][i];
+        tables[8][i] = kt->ghash_lane[2][i];
+    }
+}
+
+// the XOR of the four rows' values, lane by lane, left in every row: rows 1, 3 change places with
+// rows 0, 2 of a copy, then lanes 32..63 with lanes 0..31
+__device__ __forceinline__ uint32_t rows_summed(uint32_t v) {
+    const auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = a[0] ^ a[1];
+    const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return b[0] ^ b[1];
+}
+
+// element kElement of every quad in all four lanes of the quad, in the rows of kRowMask only
+template <int kElement, int kRowMask>
+__device__ __forceinline__ uint32_t quad_element(uint32_t keep, uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)keep, (int)v, kElement * 0x55, kRowMask, 0xF,
+                                                 false);
+}
+
+__device__ __forceinline__ void fold_lanes_by_four(uint32_t lane_tables, uint32_t y[4],
+                                                   uint32_t lane) {
+    const uint32_t row = lane >> 4;
+    const bool last_row = row == 3;
+    {
+        uint32_t m[4] = {y[0], y[1], y[2], y[3]};
+        ghash_mul_lds(lane_tables + (8 - (last_row ? 2 : row)) * kLdsGhBytes, m);  // H^48, 32, 16
+#pragma unroll
+        for (int k = 0; k < 4; ++k) y[k] = rows_summed(last_row ? y[k] : m[k]);
+    }
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            uint32_t t = quad_element<0, 1>(y[k], y[k]);
+            t = quad_element<1, 2>(t, y[k]);
+            t = quad_element<2, 4>(t, y[k]);
+            y[k] = quad_element<3, 8>(t, y[k]);
+        }
+        ghash_mul_lds(lane_tables + (3 - row) * kLdsGhBytes, y);  // H^4, H^3, H^2, H^1
+#pragma unroll
+        for (int k = 0; k < 4; ++k) y[k] = rows_summed(y[k]);
+    }
+    {
+        uint32_t m[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t w0 = __builtin_amdgcn_readlane(y[k], 0), w1 = __builtin_amdgcn_readlane(y[k], 4),
+                           w2 = __builtin_amdgcn_readlane(y[k], 8), w3 = __builtin_amdgcn_readlane(y[k], 12);
+            y[k] = row == 0 ? w0 : row == 1 ? w1 : row == 2 ? w2 : w3;
+            m[k] = y[k];
+        }
+        ghash_mul_lds(lane_tables + (5 - (last_row ? 2 : row)) * kLdsGhBytes, m);  // H^12, 8, 4
+#pragma unroll
+        for (int k = 0; k < 4; ++k) y[k] = rows_summed(last_row ? y[k] : m[k]);
+    }
+}
+
 // From the GHASH state over A and C (the same in every lane) to the end of the invocation:
 // length block, one more H, mask with E_K(J0) (SP 800-38D 7.1 steps 5-6); then write the tag, or
 // compare it and write the verdict (7.2), wiping the output of a rejected chunk.
@@ -1239,9 +1336,9 @@ __global__ __launch_bounds__(kFoldTreeWaves * 64) void fold_tree_kernel(
 // of them then take a chunk each (the host spreads a batch of few chunks over the compute units:
 // the wavefronts of one unit share its LDS pipe, and every chunk is a chain of dependent
 // multiplications).  Workgroup 0 also clears `counter` for the next batch.
-// LDS: nibble tables of H^1 .. H^32 (tree), and of the two most common fold distances.
+// LDS: the nine nibble tables of the lane tree, and those of the two most common fold distances.
 // unit_power: log2 of the blocks per unit the batch was cut into.
-constexpr uint32_t kFinalTables = 8;
+constexpr uint32_t kFinalTables = kLaneTables + 2;
 
 template <bool kDecrypt>
 __global__ __launch_bounds__(kFinalWaves * 64) void final_kernel(
@@ -1252,11 +1349,11 @@ __global__ __launch_bounds__(kFinalWaves * 64) void final_kernel(
     __shared__ Block tables[kFinalTables][kNibbleTableEntries];
     const uint32_t tid = threadIdx.x, lane = tid & 63;
     if (blockIdx.x == 0 && tid == 0) *counter = 0;
-    // tables 0..5: H^(2^k) for the lane tree; 6, 7: the fold distances of chunks with no and
-    // with one fold level behind them
-    for (uint32_t k = 0; k < 6; ++k) copy_power_table(tables[k], kt, k, tid, blockDim.x);
-    copy_power_table(tables[6], kt, unit_power, tid, blockDim.x);
-    copy_power_table(tables[7], kt, unit_power + kFanPower, tid, blockDim.x);
+    // tables 0..8: the lane tree's (the first is H's); then the fold distances of chunks with no
+    // and with one fold level behind them
+    copy_lane_tables(tables, kt, tid, blockDim.x);
+    copy_power_table(tables[kLaneTables], kt, unit_power, tid, blockDim.x);
+    copy_power_table(tables[kLaneTables + 1], kt, unit_power + kFanPower, tid, blockDim.x);
     __syncthreads();
 
     if ((tid >> 6) >= chunks_per_group) return;
@@ -1277,10 +1374,10 @@ __global__ __launch_bounds__(kFinalWaves * 64) void final_kernel(
         mask = Block{{e[0], e[1], e[2], e[3]}};
     } else {
         uint32_t fold_table = 0xFFFFFFFFu;
-        if (cd.final_power == unit_power) fold_table = lds_offset(tables[6]);
-        if (cd.final_power == unit_power + kFanPower) fold_table = lds_offset(tables[7]);
+        if (cd.final_power == unit_power) fold_table = lds_offset(tables[kLaneTables]);
+        if (cd.final_power == unit_power + kFanPower) fold_table = lds_offset(tables[kLaneTables + 1]);
         fold_sets(kt, sets, cd.final_base, cd.final_count, cd.final_power, lane, fold_table, y);
-        fold_lanes(lds_offset(tables[0]), y);
+        fold_lanes_by_four(lds_offset(tables[0]), y, lane);
         mask = ekj0[i];
     }
     finish_chunk<kDecrypt>(lds_offset(tables[0]), y, mask.w, cd, tags, ok, lane);
@@ -1308,15 +1405,17 @@ template __global__ void final_kernel<true>(const KeyTables*, const ChunkDesc*, 
 // workgroup runs to its end whatever the others do.
 //
 // LDS after the round tables are done with, in tables of 8 KiB:
-//   0..5   H^(2^k), k = 0 .. 5: lane tree, length block
-//   6..9   H^(2^(p + j)), j = 0 .. 3: tree over the workgroup's sixteen units (p = unit_power)
-//   10     H^(2^(p + 4)): from one workgroup's set to the next
-//   11..14 H^(2^(p + 4 + l + j)), j = 0 .. 3: tree over the sixteen wavefronts' runs of 2^l sets
+//   0..8   lane tree (see fold_lanes_by_four); the first is H's, for the length block
+//   9..12  H^(2^(p + j)), j = 0 .. 3: tree over the workgroup's sixteen units (p = unit_power);
+//          later, in the workgroup that arrives last,
+//          H^(2^(p + 4 + l + j)), j = 0 .. 3: tree over the sixteen wavefronts' runs of 2^l sets
+//   13     H^(2^(p + 4)): from one workgroup's set to the next
 //   15..16 sixteen sets, one per wavefront
 namespace {
 
-constexpr uint32_t kSwapLaneTables = 0, kSwapUnitTables = 6, kSwapRunTable = 10,
-                   kSwapWaveTables = 11, kSwapPartial = 15;
+constexpr uint32_t kSwapLaneTables = 0, kSwapUnitTables = kLaneTables, kSwapRunTable = 13,
+                   kSwapWaveTables = kLaneTables, kSwapPartial = 15;
+static_assert(kSwapUnitTables + 4 <= kSwapRunTable && kSwapRunTable < kSwapPartial, "table slots");
 static_assert((kSwapPartial + 2) * kLdsGhBytes <= kLdsBytes, "tables and sets fit the LDS object");
 
 // sixteen sets (one per wavefront, in y) -> one in wavefront 0, leaves counted back from the
@@ -1387,9 +1486,7 @@ __global__ __launch_bounds__(kGroupThreads) void swap_kernel(
     if (cd.nunits > 1)
         for (uint32_t j = 0; j < 4; ++j)
             copy_power_table(tables[kSwapUnitTables + j], kt, unit_power + j, tid, kGroupThreads);
-    if (alone)
-        for (uint32_t k = 0; k < 6; ++k)
-            copy_power_table(tables[kSwapLaneTables + k], kt, k, tid, kGroupThreads);
+    if (alone) copy_lane_tables(tables + kSwapLaneTables, kt, tid, kGroupThreads);
     __syncthreads();
     if (cd.nunits > 1) fold_waves(tables, partial, kSwapUnitTables, wave, lane, y);
     else if (wave == kWavesPerGroup - 1) {
@@ -1430,8 +1527,7 @@ __global__ __launch_bounds__(kGroupThreads) void swap_kernel(
         // counted back from the last set, missing ones at the front count as zero
         uint32_t l = 0;
         while ((kWavesPerGroup << l) < cd.ngroups) ++l;
-        for (uint32_t k = 0; k < 6; ++k)
-            copy_power_table(tables[kSwapLaneTables + k], kt, k, tid, kGroupThreads);
+        copy_lane_tables(tables + kSwapLaneTables, kt, tid, kGroupThreads);
         copy_power_table(tables[kSwapRunTable], kt, unit_power + 4, tid, kGroupThreads);
         for (uint32_t j = 0; j < 4; ++j)
             copy_power_table(tables[kSwapWaveTables + j], kt, unit_power + 4 + l + j, tid,
@@ -1464,7 +1560,7 @@ __global__ __launch_bounds__(kGroupThreads) void swap_kernel(
         aes_block_global(kt, e);
         mask = Block{{e[0], e[1], e[2], e[3]}};
     } else {
-        fold_lanes(lds_offset(tables[kSwapLaneTables]), y);
+        fold_lanes_by_four(lds_offset(tables[kSwapLaneTables]), y, lane);
         mask = load_block_device_scope(ekj0 + chunk);
     }
     ChunkDesc d{};

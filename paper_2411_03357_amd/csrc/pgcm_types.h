@@ -47,6 +47,10 @@ constexpr uint32_t kNumPowers = kUnitPower + kFanPower * kMaxLevels + 1;  // H^(
 constexpr uint32_t kRowMatrixWords = 128 * 128 / 8;
 static_assert(kRowMatrixWords * 4 == kNibbleTableEntries * 16, "same room as a nibble table");
 
+// The lane tree of the kernels that finish large chunks folds the 64 lanes in groups of four,
+// three multiplications deep; beside H^(2^k) it needs the nibble tables of H^3, H^12 and H^48.
+constexpr uint32_t kNumLanePowers = 3;
+
 struct alignas(16) Block {
     uint32_t w[4];  // bytes 4i..4i+3 of the block, loaded little-endian into w[i]
 };
@@ -60,6 +64,7 @@ struct alignas(16) KeyTables {
     Block h;               // GHASH key H = E_K(0^128)
     Block ghash[kNumPowers][kNibbleTableEntries];
     uint32_t row_matrix[kRowMatrixWords];  // multiplication by H^64 as matrix-core operands
+    Block ghash_lane[kNumLanePowers][kNibbleTableEntries];  // nibble tables of H^3, H^12, H^48
 };
 
 struct alignas(16) ChunkDesc {

@@ -1,7 +1,8 @@
 """The tables the key set-up kernel leaves on the device, piece by piece against the oracle: key
 schedule (FIPS-197 5.2), round tables (S-box and MixColumns coefficients), H = E_K(0), and the
 nibble tables of H^(2^k), each entry being one GF(2^128) product (SP 800-38D 6.3), and the
-multiplication by H^64 written out as a 128 x 128 matrix over GF(2) for the matrix cores."""
+multiplication by H^64 written out as a 128 x 128 matrix over GF(2) for the matrix cores, and the
+nibble tables of H^3, H^12, H^48 the lane tree uses."""
 import numpy as np
 import pytest
 
@@ -23,7 +24,7 @@ def test_device_tables_entry_by_entry(key_bytes):
     key = pgcm.expand_key_bytes(keyb)
     t = pgcm.copy_key_tables(key)
     key.free()
-    assert pgcm.load_library().pgcm_key_tables_bytes() == 256 + 4096 + 16 + 31 * 512 * 16 + 8192
+    assert pgcm.load_library().pgcm_key_tables_bytes() == 256 + 4096 + 16 + 31 * 512 * 16 + 8192 + 3 * 512 * 16
 
     # key schedule
     rk = oracle.aes_key_expand(keyb)
@@ -62,6 +63,25 @@ def test_device_tables_entry_by_entry(key_bytes):
                 assert np.array_equal(rows[:, a ^ b], rows[:, a] ^ rows[:, b])
         power = oracle.gf128_mul(power, power)               # H^(2^(k+1))
 
+
+    # the three constants of the lane tree that are not H^(2^k)
+    def power(e):
+        r, base = None, h
+        while e:
+            if e & 1:
+                r = base if r is None else oracle.gf128_mul(r, base)
+            base = oracle.gf128_mul(base, base)
+            e >>= 1
+        return r
+    assert t["ghash_lane"].shape == (3, 512, 16)
+    for k, e in enumerate((3, 12, 48)):
+        c = power(e)
+        tab = t["ghash_lane"][k]
+        for pos in range(32):
+            for val in range(16):
+                x = bytearray(16)
+                x[pos // 2] = val << 4 if pos % 2 == 0 else val
+                assert tab[pos * 16 + val].tobytes() == oracle.gf128_mul(bytes(x), c), (e, pos, val)
 
     # Multiplication by H^64 as matrix-core operands.  Bit b of a block, as the kernels hold it, is
     # bit b % 32 of the little-endian word b // 32.  Lane l of tile mt holds the matrix row whose
