@@ -8,13 +8,15 @@
 //     always reads bank l % 32: table lookups never collide, whatever the data.  AddRoundKey is
 //     folded into forming the next round's lookup addresses (one SDWA XOR per state byte).
 //   * GHASH multiplies by fixed powers of H with 4-bit tables (Shoup).  In the bulk kernel the
-//     row power H^64 sits in LDS and its thirty-two lookups are spread over the AES rounds.
+//     row power H^64 sits in LDS and its thirty-two lookups are spread over the AES rounds;
+//     as an alternative the same multiplication runs on the matrix cores, as a product with a
+//     128 x 128 matrix over GF(2) (GhashRowMatrix).
 //   * One wavefront walks one unit (1 to 16 KiB of one chunk, the size chosen per batch) in rows
 //     of 64 blocks, one block per lane, 16-byte coalesced loads and stores, ciphertext hashed
 //     from registers.  Wavefront w starts with unit w; what is left is handed out by a
 //     device-side counter.  Each unit leaves 64 per-lane hash sums; fold kernels (a chain per
 //     wavefront, or a tree per workgroup when there are few) and the final kernel combine them
-//     per chunk (powers H^(2^k) from tables, DPP reduction tree over the lanes).
+//     per chunk (powers of H from tables; the 64 lanes are folded in groups of four).
 //   * A batch of short chunks only is done by one kernel, a wavefront per chunk.
 #include <hip/hip_runtime.h>
 #include <stddef.h>
