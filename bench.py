@@ -332,6 +332,12 @@ def measure_workload(pgcm, torch, w, args, steps, warmup, headline):
     pgcm.set_timing(key, False)
     assert len(launches) == min(2 * steps, 256) and len(launches) % 2 == 0
     assert bool((b.ok == 1).all()) and torch.equal(b.back, b.plain), "round trip failed"
+    # the same passes without the event pairs: the events' hand-overs cost the GPU a few
+    # microseconds per call, which is nothing to a batch that fills the chip and a third of a
+    # pass of the small-transfer path
+    plain_steps = max(5, min(steps, 20))
+    b.measure(key, min(warmup, 12))     # the checks above let the clocks drop
+    ms_plain = b.measure(key, plain_steps) / plain_steps
 
     # each direction alone, again by the library's loop; a series starts with untimed passes
     # because the checks in between leave the GPU idle long enough for its clocks to drop.
@@ -359,6 +365,8 @@ def measure_workload(pgcm, torch, w, args, steps, warmup, headline):
     res = {"workload": w.name, "chunks": w.n, "payload_bytes": payload,
            "value": round(2.0 * payload * steps / (ms * 1e-3) / 1e9, 2), "unit": "GB/s",
            "steps": steps, "ms_per_step": round(ms / steps, 4),
+           "ms_per_step_without_launch_events": round(ms_plain, 4),
+           "value_without_launch_events": round(2.0 * payload / (ms_plain * 1e-3) / 1e9, 2),
            "enc_GBps": round(payload / (enc_ms * 1e-3) / 1e9, 2),
            "dec_verify_GBps": round(payload / (dec_ms * 1e-3) / 1e9, 2),
            "chunks_rejected_in_dec_verify": len(rejected),
