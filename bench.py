@@ -31,17 +31,17 @@ LDS_PEAK_GCYCLES = 256 * 2.4               # 256 CUs, one LDS pipe each, 2.4 GHz
 # (pgcm_kernels.hip and the two headers it includes) whose hash is given; once those change the
 # counters no longer apply and bench.py reports null.
 COUNTERS = {
-    "sources_sha256": "4aa482649ba56595aee30b7be7f283c7acab5edb3555ca2c085b6e527ce3b7b7",
+    "sources_sha256": "23d93b85df471d2e331f0279dbec7481c4e09c6246208d02277e6dbc7621b70a",
     "workload": "c2_opt13b_kv_4096x320KiB",
-    "fetch_size_kib": 657195.2,     # FETCH_SIZE per launch
+    "fetch_size_kib": 657146.8,     # FETCH_SIZE per launch
     "fetch_scale": 1310720.0 / 655383.0,   # a 1 310 720 KiB device copy reads 655 383
     "write_size_kib": 1395456.0,    # WRITE_SIZE per launch
     "write_scale": 1310720.0 / 1310720.0,  # the same copy writes 1 310 720.0
-    "valu_wave_instructions": 608147456.0,  # SQ_INSTS_VALU per launch
+    "valu_wave_instructions": 588482560.0,  # SQ_INSTS_VALU per launch
     "lds_wave_instructions": 321832960.0,   # SQ_INSTS_LDS per launch
     "lds_active_cycles": 728154112.0,   # SQ_LDS_IDX_ACTIVE per launch, summed over the 256 CUs
-    "gui_active_cycles": 24987719.6 / 8,  # GRBM_GUI_ACTIVE per launch (summed over the 8 XCDs) ...
-    "pmc_launch_ms": 1.5708016,           # ... and the launch's duration in that same run
+    "gui_active_cycles": 24682199.5 / 8,  # GRBM_GUI_ACTIVE per launch (summed over the 8 XCDs) ...
+    "pmc_launch_ms": 1.5139392,           # ... and the launch's duration in that same run
 }
 
 

@@ -376,6 +376,16 @@ __device__ __forceinline__ u32x4 global_read128(const uint8_t* p) {
 __device__ __forceinline__ void global_write128(uint8_t* p, u32x4 v) {
     *reinterpret_cast<global_u128_ptr>(reinterpret_cast<uintptr_t>(p)) = v;
 }
+// ... and so do the single bytes of a ragged last block: one flat access anywhere in the row loop
+// would make every wait in it a wait for everything
+typedef __attribute__((address_space(1))) const uint8_t* global_u8_cptr;
+typedef __attribute__((address_space(1))) uint8_t* global_u8_ptr;
+__device__ __forceinline__ uint8_t global_read8(const uint8_t* p) {
+    return *reinterpret_cast<global_u8_cptr>(reinterpret_cast<uintptr_t>(p));
+}
+__device__ __forceinline__ void global_write8(uint8_t* p, uint8_t v) {
+    *reinterpret_cast<global_u8_ptr>(reinterpret_cast<uintptr_t>(p)) = v;
+}
 
 // A block written so that a wavefront on another XCD can read it while this kernel still runs:
 // the XCDs' L2 caches are not coherent with each other for ordinary accesses, and a release or
@@ -466,9 +476,15 @@ __device__ __forceinline__ void key_xor_into_addr(uint32_t& a, uint32_t rk, uint
 // byte 1 is rewritten every round.
 struct AesAddr {
     uint32_t a[4][4];
+    // the last round key, in vector registers: the sixty key words and everything else a kernel
+    // keeps in scalar registers do not fit them all, and one that is spilled costs a vector
+    // instruction per use
+    uint32_t last_key[4];
 };
 
-__device__ __forceinline__ void aes_addr_init(AesAddr& A, uint32_t lane) {
+// last_round_key: the four words of round key Nr
+__device__ __forceinline__ void aes_addr_init(AesAddr& A, uint32_t lane,
+                                              const uint32_t* __restrict__ last_round_key) {
     const uint32_t lo = (lane & 31) * 4, hi = lo | 0x10000u;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -476,6 +492,8 @@ __device__ __forceinline__ void aes_addr_init(AesAddr& A, uint32_t lane) {
         A.a[j][1] = lo;
         A.a[j][2] = hi;
         A.a[j][3] = hi;
+        A.last_key[j] = last_round_key[j];
+        asm volatile("" : "+v"(A.last_key[j]));  // a vector register, and kept there
     }
 }
 
@@ -767,10 +785,10 @@ __device__ __forceinline__ void aes_ctr_lds(const uint32_t* __restrict__ rk, Aes
                 uint32_t hi = __builtin_amdgcn_perm(v2, v3, 0x00040c0cu);  // [0, 0, v2.b0, v3.b0]
                 return xor3(lo, hi, key);
             };
-            o0 = last(t00, t11, t22, t33, rk[4 * kRounds + 0]);
-            o1 = last(t10, t21, t32, t03, rk[4 * kRounds + 1]);
-            o2 = last(t20, t31, t02, t13, rk[4 * kRounds + 2]);
-            o3 = last(t30, t01, t12, t23, rk[4 * kRounds + 3]);
+            o0 = last(t00, t11, t22, t33, A.last_key[0]);
+            o1 = last(t10, t21, t32, t03, A.last_key[1]);
+            o2 = last(t20, t31, t02, t13, A.last_key[2]);
+            o3 = last(t30, t01, t12, t23, A.last_key[3]);
         }
         if constexpr (Hash::kMatrix) {
             if constexpr (r <= 9) {
@@ -818,11 +836,13 @@ __device__ __forceinline__ void ghash_mul_lds(uint32_t base, uint32_t y[4]) {
 // One row of a unit: block `blk` of the chunk in this lane.  On `edge` rows (the first and the
 // last row of a chunk; a wave-uniform flag) some lanes may lie before the chunk's start and stay
 // idle, the last lane may hold the chunk's ragged last block, and the lane of block 0 folds in
-// the AAD state.  One code path serves both kinds: idle lanes run the cipher on a dummy counter,
-// touch no payload and keep a zero hash state.
+// the AAD state; idle lanes run the cipher on a dummy counter, touch no payload and keep a zero
+// hash state.
 // kThrough: the payload is written through to memory (see global_write128_through).
 // kMatrixHash: the hash multiplication runs on the matrix cores; the first 8 KiB of the LDS
 // object then hold the matrix image instead of the nibble table.
+// `edge` is the same in every lane and held in a scalar register (walk_unit sees to that), so
+// the rows that are no edge rows branch past all of the checks.
 template <bool kDecrypt, int kRounds, bool kThrough = false, bool kMatrixHash = false>
 __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAddr& A,
                                          const CtrConsts& C, uint32_t ctr1, const uint8_t* src,
@@ -831,28 +851,32 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
                                          uint32_t lds_base, uint32_t y[4]) {
     bool active = true;
     uint32_t tail = 0;  // bytes in a ragged block, 0 = whole block
-    if (edge) {
-        active = blk >= 0;
-        if (active && (uint64_t)blk * 16 + 16 > len) tail = (uint32_t)(len & 15);
-    }
-    const bool whole = active && tail == 0;
-
-    uint32_t x0 = 0, x1 = 0, x2 = 0, x3 = 0;
+    bool whole = true;
+    uint32_t x0, x1, x2, x3;
     const uint8_t* sp = src + blk * 16;
     uint8_t* dp = dst + blk * 16;
-    if (whole) {
-        u32x4 v = global_read128(sp);
+    if (!edge) {
+        const u32x4 v = global_read128(sp);
         x0 = v.x, x1 = v.y, x2 = v.z, x3 = v.w;
-    }
-    if (edge && tail) {
+    } else {
+        active = blk >= 0;
+        if (active && (uint64_t)blk * 16 + 16 > len) tail = (uint32_t)(len & 15);
+        whole = active && tail == 0;
+        x0 = x1 = x2 = x3 = 0;
+        if (whole) {
+            const u32x4 v = global_read128(sp);
+            x0 = v.x, x1 = v.y, x2 = v.z, x3 = v.w;
+        }
+        if (tail) {
 #pragma unroll
-        for (uint32_t b = 0; b < 15; ++b) {
-            if (b < tail) {
-                const uint32_t v = (uint32_t)sp[b] << (8 * (b % 4));
-                if (b / 4 == 0) x0 |= v;
-                if (b / 4 == 1) x1 |= v;
-                if (b / 4 == 2) x2 |= v;
-                if (b / 4 == 3) x3 |= v;
+            for (uint32_t b = 0; b < 15; ++b) {
+                if (b < tail) {
+                    const uint32_t v = (uint32_t)global_read8(sp + b) << (8 * (b % 4));
+                    if (b / 4 == 0) x0 |= v;
+                    if (b / 4 == 1) x1 |= v;
+                    if (b / 4 == 2) x2 |= v;
+                    if (b / 4 == 3) x3 |= v;
+                }
             }
         }
     }
@@ -873,12 +897,17 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
     if constexpr (kMatrixHash) G.finish();
     uint32_t o0 = x0 ^ s0, o1 = x1 ^ s1, o2 = x2 ^ s2, o3 = x3 ^ s3;
 
-    if (whole) {
+    auto store_block = [&]() __attribute__((always_inline)) {
         u32x4 o = {o0, o1, o2, o3};
         if constexpr (kThrough)
             global_write128_through(dp, o);
         else
             global_write128(dp, o);
+    };
+    if (!edge) {
+        store_block();
+    } else if (whole) {
+        store_block();
     }
     if (edge && tail) {
 #pragma unroll
@@ -888,7 +917,7 @@ __device__ __forceinline__ void bulk_row(const uint32_t* __restrict__ rk, AesAdd
                 if constexpr (kThrough)
                     global_write8_through(dp + b, (uint8_t)(w >> (8 * (b % 4))));
                 else
-                    dp[b] = (uint8_t)(w >> (8 * (b % 4)));
+                    global_write8(dp + b, (uint8_t)(w >> (8 * (b % 4))));
             }
         }
         // bytes past the end count as zero in the hash
@@ -967,6 +996,27 @@ __device__ __forceinline__ void walk_unit(const KeyTables* __restrict__ kt,
                                           uint32_t first_blocks, uint32_t unit_power,
                                           const Block& j, Block* __restrict__ ekj0_out,
                                           uint32_t y[4]) {
+    // What describes the unit is the same in every lane, and was fetched from memory just now:
+    // moved to scalar registers here, (1) the wait for it comes before the row loop (placed at
+    // the first use inside the loop, that wait would make every row wait for the previous row's
+    // store as well), (2) which rows are edge rows is decided by a scalar branch, and (3) the
+    // payload addresses are a scalar base plus the lane's offset.  (The length, which only edge
+    // rows look at, stays where it is: scalar registers are short, and one that is spilled
+    // costs a vector instruction per use.)
+    // (the builtin returns a signed int: without the casts to uint32_t a low half with its top
+    // bit set would be sign-extended over the high half)
+    auto same_in_all_lanes = [](uint64_t v) __attribute__((always_inline)) {
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)v);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return (uint64_t)lo | ((uint64_t)hi << 32);
+    };
+    src = reinterpret_cast<const uint8_t*>(same_in_all_lanes(reinterpret_cast<uint64_t>(src)));
+    dst = reinterpret_cast<uint8_t*>(same_in_all_lanes(reinterpret_cast<uint64_t>(dst)));
+    unit = __builtin_amdgcn_readfirstlane(unit);
+    nunits = __builtin_amdgcn_readfirstlane(nunits);
+    first_blocks = __builtin_amdgcn_readfirstlane(first_blocks);
+    unit_power = __builtin_amdgcn_readfirstlane(unit_power);
+
     // the unit's blocks [b0, b1) of the chunk
     const int64_t b0 =
         unit == 0 ? -1 : (int64_t)first_blocks + ((int64_t)(unit - 1) << unit_power);
@@ -1020,12 +1070,13 @@ __global__ __launch_bounds__(kGroupThreads) void bulk_kernel(
     __syncthreads();
 
     const uint32_t lane = tid & 63;
-    AesAddr A;
-    aes_addr_init(A, lane);
-    // the round keys stay in scalar registers for the whole kernel
+    // the round keys stay in scalar registers for the whole kernel (the last one in vector
+    // registers, see AesAddr)
     uint32_t rk[4 * (kRounds + 1)];
 #pragma unroll
     for (int i = 0; i < 4 * (kRounds + 1); ++i) rk[i] = kt->rk[i];
+    AesAddr A;
+    aes_addr_init(A, lane, rk + 4 * kRounds);
 
     const uint32_t nwaves = gridDim.x * kWavesPerGroup;
     const bool one_each = nunits_total <= nwaves;
@@ -1466,11 +1517,11 @@ __global__ __launch_bounds__(kGroupThreads) void swap_kernel(
 
     uint32_t y[4] = {0, 0, 0, 0};
     if (unit >= 0) {
-        AesAddr A;
-        aes_addr_init(A, lane);
         uint32_t rk[4 * (kRounds + 1)];
 #pragma unroll
         for (int i = 0; i < 4 * (kRounds + 1); ++i) rk[i] = kt->rk[i];
+        AesAddr A;
+        aes_addr_init(A, lane, rk + 4 * kRounds);
         const Block j = j0_from_iv(kt, ivs + (uint64_t)cd.index * 12, 12);
         // When decrypting, the workgroup that finishes the chunk may have to wipe plaintext that
         // other workgroups (on other XCDs) wrote: their stores go through to memory, and must be
